@@ -1,0 +1,159 @@
+#!/usr/bin/env python3
+"""Benchmark of the multi-adapter LoRA linear layer, forward + backward, on one MI355X.
+
+A step is one pass of the whole path over one packed batch: fwd (down projection, base GEMM with
+the fused up projection) then bwd (gradient down projection, base GEMM^T with fused up projection,
+dB and dA reductions).  Inputs are synthetic, seeded and resident in HBM before timing starts; the
+batch plan is built once outside the timed region (one packed batch shares its plan over every
+layer).  Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import re
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_FP32_TFLOPS = 157.3      # MI355X fp32 vector
+PEAK_HBM_GBS = 8000.0
+
+
+def cpu_baseline(p, budget_rows):
+    """The fp64 oracle, as it stands, on a bounded sample of the same workload."""
+    import numpy as np
+    import oracle
+    o = oracle.Oracle(p.x, p.W, p.A, p.B, p.s, p.dy, p.rank_off, p.seg_off, p.seg_task)
+    rows = np.linspace(0, p.T - 1, budget_rows).astype(np.int64)
+    t0 = time.perf_counter()
+    o.y(rows)
+    o.dx(rows)
+    t_rows = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    o.grads()
+    t_grads = time.perf_counter() - t0
+    per_token = t_rows / len(rows) + t_grads / p.T
+    cores = int(os.environ.get("OMP_NUM_THREADS", 0)) or len(os.sched_getaffinity(0))
+    return {
+        "value": 1.0 / per_token, "unit": "tokens/s", "cores": cores, "kind": "oracle",
+        "sample": "y and dx of %d evenly spaced rows (%.2f s) + dA, dB over all %d tokens (%.2f s); "
+                  "per-token cost = rows_time/rows + grads_time/T" % (len(rows), t_rows, p.T, t_grads),
+    }
+
+
+def read_traffic(workload):
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary."""
+    path = os.path.join(ROOT, "profiles", "gemm_%s_pmc.txt" % workload)
+    try:
+        m = re.search(r"^TRAFFIC_BYTES_PER_LAUNCH\s*=\s*([0-9.eE+]+)", open(path).read(), re.M)
+        return float(m.group(1)) if m else None
+    except OSError:
+        return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4, 5])
+    ap.add_argument("--order", default="shuffled", choices=["shuffled", "sorted"])
+    ap.add_argument("--oracle-rows", type=int, default=1536)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
+
+    import numpy as np
+    import torch
+    from paper_2509_01193_amd import binding as bd
+    from paper_2509_01193_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU")
+    torch.cuda.set_device(0)
+    p = wl.make_config(a.config, a.order)
+    t0 = time.perf_counter()
+    dp = bd.DeviceProblem(p)
+    torch.cuda.synchronize()
+
+    def timed(fn, steps, warmup):
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        w0 = time.perf_counter()
+        e0.record()
+        for _ in range(steps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        wall = (time.perf_counter() - w0) * 1e3 / steps
+        return wall, e0.elapsed_time(e1) / steps
+
+    ms_wall, ms_ev = timed(dp.step, a.steps, a.warmup)
+
+    # the same library with no adapters: base GEMM time, for the LoRA overhead figure
+    base = dp.base_only()
+    ms_base_wall, ms_base = timed(base.step, max(a.steps // 2, 1), min(a.warmup, 3))
+
+    # per-kernel durations from HIP events on the launch stream, over `steps` more passes
+    tr = bd.LaunchTrace(dp.plan, 32)
+    per = {}
+    for _ in range(a.steps):
+        tr.attach()
+        dp.step()
+        torch.cuda.synchronize()
+        for name, ms in tr.durations():
+            per.setdefault(name, []).append(ms)
+    tr.close()
+    kern = {k: {"launches_per_step": len(v) // a.steps, "avg_ms": float(np.mean(v))} for k, v in per.items()}
+
+    cnt = p.task_tokens()
+    tok_rank = float((cnt * p.ranks).sum())
+    flops = p.useful_flops()
+    # dominant kernel: the fused GEMM (two launches per step: y and dx)
+    gemm_flops = 0.5 * (4.0 * p.T * p.d_in * p.d_out + 2.0 * tok_rank * (p.d_in + p.d_out))
+    gemm_ms = kern.get("gemm", {}).get("avg_ms", float("nan"))
+    peak = PEAK_BF16_TFLOPS if p.dtype == "bf16" else PEAK_FP32_TFLOPS
+    achieved = gemm_flops / (gemm_ms * 1e-3) / 1e12
+    roofline = {"bound": "mfma" if p.dtype == "bf16" else "alu", "kernel": "gemm (base product + fused up projection)",
+                "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
+                "traffic": read_traffic("cfg%d" % a.config), "avg_launch_ms": gemm_ms,
+                "flops_per_launch": gemm_flops}
+    esz = 2 if p.dtype == "bf16" else 4
+    skinny = {}
+    if "shrink" in kern:   # x once (fwd) and dy once (bwd): mean bytes per launch
+        b = 0.5 * esz * p.T * (p.d_in + p.d_out)
+        skinny["shrink_GBs"] = b / (kern["shrink"]["avg_ms"] * 1e-3) / 1e9
+    if "grad_stage1" in kern:
+        b = 0.5 * esz * p.T * (p.d_in + p.d_out)
+        skinny["grad_stage1_GBs"] = b / (kern["grad_stage1"]["avg_ms"] * 1e-3) / 1e9
+
+    out = {
+        "metric": "multi-LoRA linear fwd+bwd tokens/s", "value": p.T / (ms_wall * 1e-3), "unit": "tokens/s",
+        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms_wall,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": p.dtype, "data": "synthetic",
+        "config": {"workload": p.name, "T": p.T, "d_in": p.d_in, "d_out": p.d_out,
+                   "n_tasks": p.n_tasks, "ranks": sorted(set(int(r) for r in p.ranks)),
+                   "segments": p.S, "order": a.order},
+        "useful_tflops": flops / (ms_wall * 1e-3) / 1e12,
+        "pct_of_peak": 100.0 * flops / (ms_wall * 1e-3) / 1e12 / peak,
+        "ms_per_step_events": ms_ev, "ms_base_only": ms_base,
+        "lora_overhead_pct": 100.0 * (ms_ev - ms_base) / ms_base,
+        "kernels": kern, "skinny_hbm": skinny, "roofline": roofline,
+        "setup_s": time.perf_counter() - t0,
+    }
+    if not a.no_cpu_baseline:
+        rows = a.oracle_rows if a.config == 2 else max(64, int(a.oracle_rows * (4096.0 * 4096) / (p.d_in * p.d_out)))
+        out["cpu_baseline"] = cpu_baseline(p, min(rows, p.T))
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

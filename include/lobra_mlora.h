@@ -1,0 +1,190 @@
+/*
+ * lobra_mlora.h - C ABI of the MI355X (gfx950) multi-adapter LoRA linear layer.
+ *
+ * The operation (paper section 2.1, "Fine-tuning based on LoRA", and the batch
+ * fusion of section 1 / Figure 1): one frozen weight W shared by all tasks, one
+ * low-rank adapter per task, the tokens of several tasks packed into one batch
+ * (section 2.1, "Processing Variable-length Data": sequences concatenated
+ * without padding).  For a token i that belongs to task t
+ *
+ *     y_i  = x_i W + s_t (A_t x_i) B_t                          forward
+ *     dx_i = dy_i W^T + s_t (B_t dy_i) A_t                      backward, input
+ *     dA_t = s_t sum_{i in t} (B_t dy_i)^T x_i                  backward, down factor
+ *     dB_t = s_t sum_{i in t} (A_t x_i)^T dy_i                  backward, up factor
+ *
+ * and a token without adapter (task -1) takes only the W terms.  W is never
+ * updated, so there is no dW.  The paper names the factors the other way round
+ * and has no scale (s_t = 1); the names here are the usual ones: A_t = down
+ * projection, B_t = up projection.
+ *
+ * Layouts (all row-major, all tensors DEVICE pointers owned by the caller):
+ *     x  [T, d_in]      W  [d_in, d_out]     y, dy [T, d_out]     dx [T, d_in]
+ *     A  [R_tot, d_in]  rows rank_off[t] .. rank_off[t+1]-1 are A_t (r_t x d_in)
+ *     B  [R_tot, d_out] rows rank_off[t] .. rank_off[t+1]-1 are B_t (r_t x d_out)
+ *     s  [n_tasks] fp32;   dA [R_tot, d_in] fp32;   dB [R_tot, d_out] fp32
+ * x, W, A, B, y, dy, dx have the element type desc.dtype (fp32, or bf16 with
+ * fp32 accumulation and one rounding to bf16 at the store).
+ *
+ * The packed batch is described by a segment table on the HOST: segment k holds
+ * tokens seg_off[k] .. seg_off[k+1]-1, all of task seg_task[k].  A task may own
+ * any number of segments, segments may be empty, seg_task = -1 marks tokens
+ * that take the base product only.
+ *
+ * Every function returns a lobra_status; nothing throws.  All argument checks
+ * run on the host before anything is launched, and on error nothing is
+ * written.  No call synchronises the stream except lobra_mlora_plan_create
+ * (one blocking upload of the plan) and lobra_mlora_plan_destroy.
+ */
+#ifndef LOBRA_MLORA_H
+#define LOBRA_MLORA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    LOBRA_OK = 0,
+    LOBRA_ERR_NULL = -1,      /* a required pointer is NULL */
+    LOBRA_ERR_SHAPE = -2,     /* T, d_in, d_out, n_tasks or S out of range */
+    LOBRA_ERR_DTYPE = -3,     /* dtype is neither LOBRA_F32 nor LOBRA_BF16 */
+    LOBRA_ERR_SEGMENTS = -4,  /* seg_off[0] != 0, decreasing, or seg_off[S] != T */
+    LOBRA_ERR_TASK_ID = -5,   /* a seg_task outside [-1, n_tasks) */
+    LOBRA_ERR_RANK = -6,      /* rank_off[0] != 0 or a rank outside [1, LOBRA_MAX_RANK] */
+    LOBRA_ERR_WORKSPACE = -7, /* workspace NULL or smaller than lobra_mlora_plan_sizes says */
+    LOBRA_ERR_ALIGN = -8,     /* a pointer not 16-byte aligned, or bf16 d_in/d_out not a multiple of 8 */
+    LOBRA_ERR_HIP = -9,       /* a HIP runtime call failed (no device, launch error, ...) */
+    LOBRA_ERR_PLAN = -10,     /* plan is NULL, host-only, or was built for another device */
+    LOBRA_ERR_NOMEM = -11     /* host or device allocation for the plan failed */
+} lobra_status;
+
+typedef enum { LOBRA_F32 = 0, LOBRA_BF16 = 1 } lobra_dtype;
+
+enum { LOBRA_MAX_RANK = 128 };
+
+/* flags of lobra_mlora_bwd */
+enum {
+    LOBRA_FLAG_ACCUMULATE_GRADS = 1, /* dA += ..., dB += ... (gradient accumulation over the
+                                        chunks of a step, section 2.1) instead of overwriting */
+    LOBRA_FLAG_NO_DX = 2             /* skip dx (first layer of a model) */
+};
+
+/* flags of lobra_mlora_plan_create */
+enum {
+    LOBRA_PLAN_HOST_ONLY = 1, /* build and keep the plan on the host only: no HIP call is made,
+                                 the plan can be inspected with lobra_mlora_plan_query but not run */
+    LOBRA_PLAN_PLAIN_KERNELS = 2 /* bf16 only: run the plain fp32-FMA kernels of the fp32 path on
+                                    bf16 storage instead of the MFMA kernels (slow; a cross-check) */
+};
+
+/* Problem descriptor.  Plain data; the three tables are HOST pointers that are read
+ * during lobra_mlora_validate / lobra_mlora_plan_create only (the plan keeps copies). */
+typedef struct {
+    int32_t dtype;           /* lobra_dtype of x, W, A, B, y, dy, dx */
+    int32_t d_in, d_out;     /* >= 1; multiples of 8 for LOBRA_BF16 */
+    int64_t T;               /* packed tokens, 0 <= T < 2^31 */
+    int32_t n_tasks;         /* >= 0; 0 = base product only */
+    int32_t S;               /* segments, >= 0 (S = 0 requires T = 0) */
+    const int32_t *rank_off; /* [n_tasks+1], rank_off[0] = 0, r_t = rank_off[t+1]-rank_off[t] */
+    const int32_t *seg_off;  /* [S+1], seg_off[0] = 0, non-decreasing, seg_off[S] = T */
+    const int32_t *seg_task; /* [S], each in [-1, n_tasks) */
+} lobra_mlora_desc;
+
+/* Opaque per-batch plan: the validated table plus the device-resident work lists (token
+ * blocks, per-tile segment ranges, reduction chunks).  One packed batch passes through every
+ * LoRA linear of every layer with the same table, so a plan is built once per batch and
+ * shared by all those calls.  Immutable after creation; concurrent calls may share it. */
+typedef struct lobra_mlora_plan lobra_mlora_plan;
+
+/* Host-only argument check of a descriptor (the checks plan_create performs). */
+lobra_status lobra_mlora_validate(const lobra_mlora_desc *desc);
+
+/* Build a plan on the current HIP device.  Allocates one small device buffer
+ * (a few bytes per 32 tokens) with hipMalloc and fills it with a blocking copy.
+ * *out is set only on success. */
+lobra_status lobra_mlora_plan_create(const lobra_mlora_desc *desc, uint32_t plan_flags,
+                                     lobra_mlora_plan **out);
+
+/* Frees the plan and its device buffer.  The caller makes sure no launched work still uses it.
+ * NULL is accepted. */
+lobra_status lobra_mlora_plan_destroy(lobra_mlora_plan *plan);
+
+/* Buffer sizes in bytes (each may be 0): h_save = the saved down-projected activations that
+ * fwd can hand to bwd; fwd_ws / bwd_ws = scratch for one call.  Any out pointer may be NULL. */
+lobra_status lobra_mlora_plan_sizes(const lobra_mlora_plan *plan, size_t *h_save_bytes,
+                                    size_t *fwd_ws_bytes, size_t *bwd_ws_bytes);
+
+/* Introspection of the host side of a plan (tests, debugging).  Copies up to `capacity`
+ * int32 values of list `what` into out (out may be NULL) and stores the list's full
+ * length in *count.
+ *   LOBRA_Q_SEGMENTS     compacted table (empty segments dropped, equal-task neighbours merged):
+ *                        n x {row0, row_end, task}
+ *   LOBRA_Q_ROWBLOCK_SEG per 32-row block: index of the compacted segment holding its first row
+ *   LOBRA_Q_TOKEN_BLOCKS n x {row0, nrows, task, rank_row0}: runs of <= 32 tokens of one adapter
+ *                        segment, grouped by task; rank_row0 = rank_off[task]
+ *   LOBRA_Q_GRAD_CHUNKS  n x {block_begin, block_end, task, partial_row0}: reduction work items
+ *   LOBRA_Q_TASK_CHUNKS  [n_tasks+1]: prefix of chunks per task */
+enum { LOBRA_Q_SEGMENTS = 0, LOBRA_Q_ROWBLOCK_SEG = 1, LOBRA_Q_TOKEN_BLOCKS = 2,
+       LOBRA_Q_GRAD_CHUNKS = 3, LOBRA_Q_TASK_CHUNKS = 4 };
+lobra_status lobra_mlora_plan_query(const lobra_mlora_plan *plan, int32_t what, int32_t *out,
+                                    size_t capacity, size_t *count);
+
+/* Forward: y = x W + s_t (A_t x) B_t for every token (section 2.1; fused batch, section 1).
+ *   x, W, A, B, y : device, element type desc.dtype, 16-byte aligned; A, B, s may be NULL
+ *                   when n_tasks = 0 or no segment carries a task
+ *   s             : device fp32 [n_tasks]
+ *   h_save        : device, h_save_bytes, or NULL.  When given, bwd can reuse the
+ *                   down-projected activations instead of recomputing them
+ *   ws, ws_bytes  : device scratch of at least fwd_ws_bytes (NULL allowed when that is 0)
+ *   hip_stream    : hipStream_t (NULL = default stream); work is enqueued, not awaited
+ * x, W, A, B, s are read only; y and h_save are overwritten. */
+lobra_status lobra_mlora_fwd(const lobra_mlora_plan *plan, const void *x, const void *W,
+                             const void *A, const void *B, const float *s, void *y,
+                             void *h_save, void *ws, size_t ws_bytes, void *hip_stream);
+
+/* Backward: dx, dA, dB as defined at the top (derivatives of the section 2.1 layer; W is
+ * frozen, so no dW).
+ *   dy      : device [T, d_out], element type desc.dtype
+ *   h_saved : what the matching fwd call wrote into h_save, or NULL to recompute from x
+ *   dx      : device [T, d_in], overwritten (ignored, may be NULL, with LOBRA_FLAG_NO_DX)
+ *   dA, dB  : device fp32 [R_tot, d_in] / [R_tot, d_out]; overwritten (rows of a task without
+ *             tokens become 0), or added to with LOBRA_FLAG_ACCUMULATE_GRADS
+ *   ws      : device scratch of at least bwd_ws_bytes
+ * The reductions run in a fixed order: results are bit-identical from run to run. */
+lobra_status lobra_mlora_bwd(const lobra_mlora_plan *plan, const void *x, const void *W,
+                             const void *A, const void *B, const float *s, const void *dy,
+                             const void *h_saved, void *dx, float *dA, float *dB,
+                             uint32_t flags, void *ws, size_t ws_bytes, void *hip_stream);
+
+/* Index probe: writes the task of every token (device int32 [T], -1 = none) and the number
+ * of tokens per task (device int64 [n_tasks]) with the same device-side table walk the
+ * kernels use.  Either output may be NULL. */
+lobra_status lobra_token_task_map(const lobra_mlora_plan *plan, int32_t *out_task,
+                                  int64_t *out_count, void *hip_stream);
+
+/* Profiling aid (bench, tests).  While a trace is attached, every kernel that fwd / bwd /
+ * token_task_map launch through this plan is bracketed by hipEventRecord on the call's stream:
+ * the i-th launch since the trace was attached records events[2i] before and events[2i+1]
+ * after it and stores which kernel it was in kernel_ids[i] (LOBRA_K_*); launches beyond
+ * n_pairs are not bracketed.  events are hipEvent_t created by the caller with timing
+ * enabled; events and kernel_ids are HOST arrays that must outlive the trace.  *n_launched
+ * (host, may be NULL) counts the launches seen.  n_pairs = 0 or events = NULL detaches.
+ * A plan with a trace attached must not be used from two threads at once. */
+enum { LOBRA_K_SHRINK = 1, LOBRA_K_GEMM = 2, LOBRA_K_GRAD_STAGE1 = 3, LOBRA_K_GRAD_STAGE2 = 4,
+       LOBRA_K_TOKEN_TASK = 5 };
+lobra_status lobra_mlora_plan_set_trace(lobra_mlora_plan *plan, void *const *events,
+                                        int32_t n_pairs, int32_t *kernel_ids,
+                                        int32_t *n_launched);
+
+/* Static, never NULL. */
+const char *lobra_status_string(lobra_status st);
+
+/* major * 10000 + minor * 100 + patch */
+int lobra_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LOBRA_MLORA_H */

@@ -1,0 +1,323 @@
+"""Thin Python binding of the C-ABI library (include/lobra_mlora.h): argument marshalling only.
+
+Tensors are PyTorch-ROCm tensors used for device memory and streams; every step of the layer
+runs in the library's HIP kernels.  There is no fallback: a missing library raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "liblobra_mlora.so")
+
+OK = 0
+F32, BF16 = 0, 1
+FLAG_ACCUMULATE_GRADS, FLAG_NO_DX = 1, 2
+PLAN_HOST_ONLY, PLAN_PLAIN_KERNELS = 1, 2
+Q_SEGMENTS, Q_ROWBLOCK_SEG, Q_TOKEN_BLOCKS, Q_GRAD_CHUNKS, Q_TASK_CHUNKS = 0, 1, 2, 3, 4
+MAX_RANK = 128
+
+EXPORTS = [
+    "lobra_mlora_validate", "lobra_mlora_plan_create", "lobra_mlora_plan_destroy",
+    "lobra_mlora_plan_sizes", "lobra_mlora_plan_query", "lobra_mlora_fwd", "lobra_mlora_bwd",
+    "lobra_token_task_map", "lobra_mlora_plan_set_trace", "lobra_status_string", "lobra_version",
+]
+
+
+class Desc(ctypes.Structure):
+    _fields_ = [
+        ("dtype", ctypes.c_int32), ("d_in", ctypes.c_int32), ("d_out", ctypes.c_int32),
+        ("T", ctypes.c_int64), ("n_tasks", ctypes.c_int32), ("S", ctypes.c_int32),
+        ("rank_off", ctypes.POINTER(ctypes.c_int32)),
+        ("seg_off", ctypes.POINTER(ctypes.c_int32)),
+        ("seg_task", ctypes.POINTER(ctypes.c_int32)),
+    ]
+
+
+class LobraError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = int(status)
+        super().__init__("%s: %s (%d)" % (where, status_string(status), status))
+
+
+_lib = None
+
+
+def lib():
+    """The loaded library.  Build it first with ``python -m paper_2509_01193_amd.build``."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                LIB_PATH + " is missing: build it with `python -m paper_2509_01193_amd.build`")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, u32, sz = ctypes.c_void_p, ctypes.c_uint32, ctypes.c_size_t
+        szp = ctypes.POINTER(sz)
+        L.lobra_mlora_validate.restype = ctypes.c_int
+        L.lobra_mlora_validate.argtypes = [ctypes.POINTER(Desc)]
+        L.lobra_mlora_plan_create.restype = ctypes.c_int
+        L.lobra_mlora_plan_create.argtypes = [ctypes.POINTER(Desc), u32, ctypes.POINTER(vp)]
+        L.lobra_mlora_plan_destroy.restype = ctypes.c_int
+        L.lobra_mlora_plan_destroy.argtypes = [vp]
+        L.lobra_mlora_plan_sizes.restype = ctypes.c_int
+        L.lobra_mlora_plan_sizes.argtypes = [vp, szp, szp, szp]
+        L.lobra_mlora_plan_query.restype = ctypes.c_int
+        L.lobra_mlora_plan_query.argtypes = [vp, ctypes.c_int32, ctypes.POINTER(ctypes.c_int32), sz, szp]
+        L.lobra_mlora_fwd.restype = ctypes.c_int
+        L.lobra_mlora_fwd.argtypes = [vp] * 8 + [vp, sz, vp]
+        L.lobra_mlora_bwd.restype = ctypes.c_int
+        L.lobra_mlora_bwd.argtypes = [vp] * 11 + [u32, vp, sz, vp]
+        L.lobra_token_task_map.restype = ctypes.c_int
+        L.lobra_token_task_map.argtypes = [vp, vp, vp, vp]
+        L.lobra_status_string.restype = ctypes.c_char_p
+        L.lobra_status_string.argtypes = [ctypes.c_int]
+        L.lobra_version.restype = ctypes.c_int
+        L.lobra_version.argtypes = []
+        _lib = L
+    return _lib
+
+
+def status_string(st) -> str:
+    return lib().lobra_status_string(int(st)).decode()
+
+
+def version() -> int:
+    return lib().lobra_version()
+
+
+def _check(st, where):
+    if st != OK:
+        raise LobraError(st, where)
+
+
+def _i32(a):
+    return np.ascontiguousarray(np.asarray(a, dtype=np.int32))
+
+
+def make_desc(dtype, T, d_in, d_out, rank_off, seg_off, seg_task):
+    """Returns (Desc, keepalive).  `dtype` is "f32"/"bf16" or the enum value."""
+    code = {"f32": F32, "bf16": BF16}.get(dtype, dtype)
+    keep = []
+    d = Desc()
+    d.dtype, d.d_in, d.d_out, d.T = int(code), int(d_in), int(d_out), int(T)
+    n_tasks = 0
+    if rank_off is not None:
+        ro = _i32(rank_off)
+        keep.append(ro)
+        n_tasks = max(int(ro.shape[0]) - 1, 0)
+        d.rank_off = ro.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+    d.n_tasks = n_tasks
+    S = 0
+    if seg_task is not None:
+        so, stk = _i32(seg_off), _i32(seg_task)
+        keep += [so, stk]
+        S = int(stk.shape[0])
+        d.seg_off = so.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+        d.seg_task = stk.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+    d.S = S
+    return d, keep
+
+
+def validate(desc: Desc) -> int:
+    return lib().lobra_mlora_validate(ctypes.byref(desc))
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return ctypes.c_void_p(t)
+    assert t.is_contiguous(), "tensors must be contiguous"
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(int(getattr(stream, "cuda_stream", stream)))
+
+
+class Plan:
+    """Owns a ``lobra_mlora_plan``.  One plan per packed batch, shared by every layer's calls."""
+
+    def __init__(self, dtype, T, d_in, d_out, rank_off, seg_off, seg_task, flags=0):
+        self.desc, self._keep = make_desc(dtype, T, d_in, d_out, rank_off, seg_off, seg_task)
+        self.handle = ctypes.c_void_p()
+        _check(lib().lobra_mlora_plan_create(ctypes.byref(self.desc), int(flags),
+                                             ctypes.byref(self.handle)), "lobra_mlora_plan_create")
+        a, b, c = ctypes.c_size_t(), ctypes.c_size_t(), ctypes.c_size_t()
+        _check(lib().lobra_mlora_plan_sizes(self.handle, ctypes.byref(a), ctypes.byref(b),
+                                            ctypes.byref(c)), "lobra_mlora_plan_sizes")
+        self.h_save_bytes, self.fwd_ws_bytes, self.bwd_ws_bytes = a.value, b.value, c.value
+        self.T, self.d_in, self.d_out = int(T), int(d_in), int(d_out)
+        self.n_tasks = self.desc.n_tasks
+        self.R_tot = int(np.asarray(rank_off)[-1]) if self.n_tasks > 0 else 0
+
+    @classmethod
+    def for_problem(cls, p, flags=0):
+        return cls(p.dtype, p.T, p.d_in, p.d_out, p.rank_off, p.seg_off, p.seg_task, flags)
+
+    def query(self, what) -> np.ndarray:
+        n = ctypes.c_size_t()
+        _check(lib().lobra_mlora_plan_query(self.handle, int(what), None, 0, ctypes.byref(n)),
+               "lobra_mlora_plan_query")
+        out = np.zeros(max(n.value, 1), dtype=np.int32)
+        _check(lib().lobra_mlora_plan_query(
+            self.handle, int(what), out.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)),
+            n.value, ctypes.byref(n)), "lobra_mlora_plan_query")
+        return out[: n.value]
+
+    def close(self):
+        if getattr(self, "handle", None) is not None and self.handle.value:
+            lib().lobra_mlora_plan_destroy(self.handle)
+            self.handle = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def lobra_mlora_fwd(plan: Plan, x, W, A, B, s, y, h_save=None, ws=None, stream=None, check=True):
+    """y = x W + s_t (A_t x) B_t.  Tensors are device tensors; returns the status."""
+    st = lib().lobra_mlora_fwd(plan.handle, _ptr(x), _ptr(W), _ptr(A), _ptr(B), _ptr(s), _ptr(y),
+                               _ptr(h_save), _ptr(ws),
+                               0 if ws is None else ws.numel() * ws.element_size(), _stream(stream))
+    if check:
+        _check(st, "lobra_mlora_fwd")
+    return st
+
+
+def lobra_mlora_bwd(plan: Plan, x, W, A, B, s, dy, h_saved, dx, dA, dB, flags=0, ws=None,
+                    stream=None, check=True):
+    """dx, dA, dB of the layer.  Returns the status."""
+    st = lib().lobra_mlora_bwd(plan.handle, _ptr(x), _ptr(W), _ptr(A), _ptr(B), _ptr(s), _ptr(dy),
+                               _ptr(h_saved), _ptr(dx), _ptr(dA), _ptr(dB), int(flags), _ptr(ws),
+                               0 if ws is None else ws.numel() * ws.element_size(), _stream(stream))
+    if check:
+        _check(st, "lobra_mlora_bwd")
+    return st
+
+
+def lobra_token_task_map(plan: Plan, out_task, out_count, stream=None):
+    _check(lib().lobra_token_task_map(plan.handle, _ptr(out_task), _ptr(out_count), _stream(stream)),
+           "lobra_token_task_map")
+
+
+# ---------------------------------------------------------------------------------------------
+# device-side convenience used by tests, smoke and bench: upload a workload, allocate buffers
+# ---------------------------------------------------------------------------------------------
+class DeviceProblem:
+    """A workloads.Problem resident on the GPU with all outputs and scratch allocated."""
+
+    def __init__(self, p, plan_flags=0, device="cuda:0"):
+        import torch
+        self.p = p
+        self.torch = torch
+        self.dev = torch.device(device)
+        self.plan = Plan.for_problem(p, plan_flags)
+        self.edt = torch.float32 if p.dtype == "f32" else torch.bfloat16
+
+        def up(a):
+            if p.dtype == "f32":
+                return torch.from_numpy(np.ascontiguousarray(a)).to(self.dev)
+            return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).to(self.dev).view(torch.bfloat16)
+        self.x, self.W, self.dy = up(p.x), up(p.W), up(p.dy)
+        self.A = up(p.A) if p.R_tot else None
+        self.B = up(p.B) if p.R_tot else None
+        self.s = torch.from_numpy(np.asarray(p.s, np.float32)).to(self.dev) if p.n_tasks else None
+        self.y = torch.empty((p.T, p.d_out), dtype=self.edt, device=self.dev)
+        self.dx = torch.empty((p.T, p.d_in), dtype=self.edt, device=self.dev)
+        self.dA = torch.zeros((p.R_tot, p.d_in), dtype=torch.float32, device=self.dev)
+        self.dB = torch.zeros((p.R_tot, p.d_out), dtype=torch.float32, device=self.dev)
+        nb = lambda n: torch.empty(max(n, 16), dtype=torch.uint8, device=self.dev)
+        self.h_save = nb(self.plan.h_save_bytes)
+        self.ws = nb(max(self.plan.fwd_ws_bytes, self.plan.bwd_ws_bytes))
+
+    def fwd(self, save_h=True):
+        lobra_mlora_fwd(self.plan, self.x, self.W, self.A, self.B, self.s, self.y,
+                        self.h_save if save_h else None, self.ws)
+
+    def bwd(self, use_saved_h=True, flags=0):
+        lobra_mlora_bwd(self.plan, self.x, self.W, self.A, self.B, self.s, self.dy,
+                        self.h_save if use_saved_h else None, self.dx, self.dA, self.dB,
+                        flags, self.ws)
+
+    def step(self):
+        self.fwd(True)
+        self.bwd(True)
+
+    def base_only(self):
+        """The same x, W, dy, y, dx under a plan without adapters: the base products alone."""
+        torch, p = self.torch, self.p
+        o = DeviceProblem.__new__(DeviceProblem)
+        o.p, o.torch, o.dev, o.edt = p, torch, self.dev, self.edt
+        o.plan = Plan(p.dtype, p.T, p.d_in, p.d_out, None, [0, p.T], [-1])
+        o.x, o.W, o.dy, o.y, o.dx = self.x, self.W, self.dy, self.y, self.dx
+        o.A = o.B = o.s = None
+        o.dA = torch.zeros((0, p.d_in), dtype=torch.float32, device=self.dev)
+        o.dB = torch.zeros((0, p.d_out), dtype=torch.float32, device=self.dev)
+        o.h_save = o.ws = torch.empty(16, dtype=torch.uint8, device=self.dev)
+        return o
+
+    def host(self, t):
+        """Device tensor -> float64 numpy."""
+        return t.detach().to(self.torch.float32).cpu().numpy().astype(np.float64)
+
+
+# ---------------------------------------------------------------------------------------------
+# launch trace: per-kernel durations from HIP events recorded on the stream the kernels run on
+# ---------------------------------------------------------------------------------------------
+KERNEL_NAMES = {1: "shrink", 2: "gemm", 3: "grad_stage1", 4: "grad_stage2", 5: "token_task"}
+
+
+class LaunchTrace:
+    """Attaches hipEvent pairs to a plan; after a synchronize, ``durations()`` lists
+    (kernel name, milliseconds) for every launch made since ``attach()``."""
+
+    def __init__(self, plan: Plan, max_launches=32):
+        self.plan, self.n = plan, int(max_launches)
+        self.hip = ctypes.CDLL("libamdhip64.so")
+        self.hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self.hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+        self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        self.events = (ctypes.c_void_p * (2 * self.n))()
+        for i in range(2 * self.n):
+            e = ctypes.c_void_p()
+            if self.hip.hipEventCreate(ctypes.byref(e)) != 0:
+                raise RuntimeError("hipEventCreate failed")
+            self.events[i] = e
+        self.ids = (ctypes.c_int32 * self.n)()
+        self.count = ctypes.c_int32(0)
+        L = lib()
+        L.lobra_mlora_plan_set_trace.restype = ctypes.c_int
+        L.lobra_mlora_plan_set_trace.argtypes = [
+            ctypes.c_void_p, ctypes.POINTER(ctypes.c_void_p), ctypes.c_int32,
+            ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int32)]
+
+    def attach(self):
+        _check(lib().lobra_mlora_plan_set_trace(self.plan.handle, self.events, self.n, self.ids,
+                                                ctypes.byref(self.count)), "lobra_mlora_plan_set_trace")
+
+    def detach(self):
+        _check(lib().lobra_mlora_plan_set_trace(self.plan.handle, None, 0, None, None),
+               "lobra_mlora_plan_set_trace")
+
+    def durations(self):
+        out = []
+        for i in range(min(self.count.value, self.n)):
+            ms = ctypes.c_float()
+            if self.hip.hipEventElapsedTime(ctypes.byref(ms), self.events[2 * i], self.events[2 * i + 1]) != 0:
+                raise RuntimeError("hipEventElapsedTime failed")
+            out.append((KERNEL_NAMES.get(self.ids[i], "?"), float(ms.value)))
+        return out
+
+    def close(self):
+        self.detach()
+        for i in range(2 * self.n):
+            self.hip.hipEventDestroy(self.events[i])

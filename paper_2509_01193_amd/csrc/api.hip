@@ -1,0 +1,321 @@
+// extern "C" entry points declared in include/lobra_mlora.h: argument checks, plan life cycle,
+// and the sequence of kernel launches of one forward / backward call.
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <cstring>
+#include <new>
+
+#include "kernels.h"
+#include "lobra_mlora.h"
+#include "plan.h"
+
+using namespace lobra;
+
+namespace {
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+PlanDev device_view(const Plan& p)
+{
+    const int32_t* b = static_cast<const int32_t*>(p.dev_blob);
+    PlanDev d;
+    d.cseg_off = b + p.o_cseg_off;
+    d.cseg_task = b + p.o_cseg_task;
+    d.rowblk_seg = b + p.o_rowblk;
+    d.tb = reinterpret_cast<const TokenBlock*>(b + p.o_tb);
+    d.chunks = reinterpret_cast<const GradChunk*>(b + p.o_chunks);
+    d.task_chunk_off = b + p.o_task_chunk;
+    d.rank_off = b + p.o_rank_off;
+    d.task_tb_off = b + p.o_task_tb;
+    d.T = int32_t(p.desc.T);
+    d.d_in = p.desc.d_in;
+    d.d_out = p.desc.d_out;
+    d.n_tasks = p.desc.n_tasks;
+    d.nseg = int32_t(p.cseg_task.size());
+    d.ntb = int32_t(p.tb.size());
+    d.nchunks = int32_t(p.chunks.size());
+    d.r_max = p.r_max;
+    d.r_pad = p.r_pad;
+    d.R_tot = p.R_tot;
+    return d;
+}
+
+// A plan can run only on the device it was uploaded to.
+lobra_status runnable(const lobra_mlora_plan* plan)
+{
+    if (!plan) return LOBRA_ERR_PLAN;
+    if (!plan->dev_blob) return LOBRA_ERR_PLAN;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return LOBRA_ERR_HIP;
+    if (dev != plan->device) return LOBRA_ERR_PLAN;
+    return LOBRA_OK;
+}
+
+#define LOBRA_HIP(expr)                                   \
+    do {                                                  \
+        if ((expr) != hipSuccess) return LOBRA_ERR_HIP;   \
+    } while (0)
+
+// One kernel launch, bracketed by the plan's trace events when a trace is attached.
+#define LOBRA_LAUNCH(plan_ref, stream, kernel_id, expr)                                          \
+    do {                                                                                         \
+        const Plan& tp_ = (plan_ref);                                                            \
+        const int32_t ti_ = tp_.trace_events ? tp_.trace_next++ : -1;                            \
+        const bool tr_ = ti_ >= 0 && ti_ < tp_.trace_pairs;                                      \
+        if (tp_.trace_count) *tp_.trace_count = tp_.trace_next;                                  \
+        if (tr_) {                                                                               \
+            if (tp_.trace_ids) tp_.trace_ids[ti_] = (kernel_id);                                 \
+            LOBRA_HIP(hipEventRecord(static_cast<hipEvent_t>(tp_.trace_events[2 * ti_]), stream)); \
+        }                                                                                        \
+        LOBRA_HIP(expr);                                                                         \
+        if (tr_)                                                                                 \
+            LOBRA_HIP(hipEventRecord(static_cast<hipEvent_t>(tp_.trace_events[2 * ti_ + 1]), stream)); \
+    } while (0)
+
+}  // namespace
+
+extern "C" {
+
+lobra_status lobra_mlora_validate(const lobra_mlora_desc* desc) { return validate(desc); }
+
+lobra_status lobra_mlora_plan_create(const lobra_mlora_desc* desc, uint32_t plan_flags,
+                                     lobra_mlora_plan** out)
+{
+    if (!out) return LOBRA_ERR_NULL;
+    lobra_status st = validate(desc);
+    if (st != LOBRA_OK) return st;
+    lobra_mlora_plan* p = new (std::nothrow) lobra_mlora_plan();
+    if (!p) return LOBRA_ERR_NOMEM;
+    st = build_host_plan(desc, plan_flags, p);
+    if (st != LOBRA_OK) {
+        delete p;
+        return st;
+    }
+    if (!(plan_flags & LOBRA_PLAN_HOST_ONLY)) {
+        std::vector<int32_t> blob;
+        try {
+            blob = pack_blob(p);
+        } catch (const std::bad_alloc&) {
+            delete p;
+            return LOBRA_ERR_NOMEM;
+        }
+        p->blob_bytes = blob.size() * sizeof(int32_t);
+        if (hipGetDevice(&p->device) != hipSuccess) {
+            delete p;
+            return LOBRA_ERR_HIP;
+        }
+        if (hipMalloc(&p->dev_blob, p->blob_bytes) != hipSuccess) {
+            delete p;
+            return LOBRA_ERR_NOMEM;
+        }
+        if (hipMemcpy(p->dev_blob, blob.data(), p->blob_bytes, hipMemcpyHostToDevice) != hipSuccess) {
+            (void)hipFree(p->dev_blob);
+            delete p;
+            return LOBRA_ERR_HIP;
+        }
+    }
+    *out = p;
+    return LOBRA_OK;
+}
+
+lobra_status lobra_mlora_plan_destroy(lobra_mlora_plan* plan)
+{
+    if (!plan) return LOBRA_OK;
+    lobra_status st = LOBRA_OK;
+    if (plan->dev_blob && hipFree(plan->dev_blob) != hipSuccess) st = LOBRA_ERR_HIP;
+    delete plan;
+    return st;
+}
+
+lobra_status lobra_mlora_plan_sizes(const lobra_mlora_plan* plan, size_t* h_save_bytes,
+                                    size_t* fwd_ws_bytes, size_t* bwd_ws_bytes)
+{
+    if (!plan) return LOBRA_ERR_PLAN;
+    if (h_save_bytes) *h_save_bytes = plan->h_save_bytes;
+    if (fwd_ws_bytes) *fwd_ws_bytes = plan->fwd_ws_bytes;
+    if (bwd_ws_bytes) *bwd_ws_bytes = plan->bwd_ws_bytes;
+    return LOBRA_OK;
+}
+
+lobra_status lobra_mlora_plan_query(const lobra_mlora_plan* plan, int32_t what, int32_t* out,
+                                    size_t capacity, size_t* count)
+{
+    if (!plan) return LOBRA_ERR_PLAN;
+    if (!count) return LOBRA_ERR_NULL;
+    std::vector<int32_t> tmp;
+    const int32_t* src = nullptr;
+    size_t n = 0;
+    switch (what) {
+    case LOBRA_Q_SEGMENTS:
+        for (size_t k = 0; k < plan->cseg_task.size(); ++k) {
+            tmp.push_back(plan->cseg_off[k]);
+            tmp.push_back(plan->cseg_off[k + 1]);
+            tmp.push_back(plan->cseg_task[k]);
+        }
+        src = tmp.data();
+        n = tmp.size();
+        break;
+    case LOBRA_Q_ROWBLOCK_SEG:
+        src = plan->rowblk_seg.data();
+        n = plan->rowblk_seg.size();
+        break;
+    case LOBRA_Q_TOKEN_BLOCKS:
+        src = reinterpret_cast<const int32_t*>(plan->tb.data());
+        n = plan->tb.size() * 4;
+        break;
+    case LOBRA_Q_GRAD_CHUNKS:
+        src = reinterpret_cast<const int32_t*>(plan->chunks.data());
+        n = plan->chunks.size() * 4;
+        break;
+    case LOBRA_Q_TASK_CHUNKS:
+        src = plan->task_chunk_off.data();
+        n = plan->task_chunk_off.size();
+        break;
+    default:
+        return LOBRA_ERR_SHAPE;
+    }
+    *count = n;
+    if (out && n) std::memcpy(out, src, sizeof(int32_t) * (n < capacity ? n : capacity));
+    return LOBRA_OK;
+}
+
+lobra_status lobra_mlora_fwd(const lobra_mlora_plan* plan, const void* x, const void* W,
+                             const void* A, const void* B, const float* s, void* y,
+                             void* h_save, void* ws, size_t ws_bytes, void* hip_stream)
+{
+    lobra_status rs = runnable(plan);
+    if (rs != LOBRA_OK) return rs;
+    const Plan& p = *plan;
+    if (p.desc.T == 0) return LOBRA_OK;
+    const bool adapters = !p.tb.empty();
+    if (!x || !W || !y) return LOBRA_ERR_NULL;
+    if (adapters && (!A || !B || !s)) return LOBRA_ERR_NULL;
+    if (!aligned16(x) || !aligned16(W) || !aligned16(y) || !aligned16(A) || !aligned16(B) ||
+        !aligned16(h_save) || !aligned16(ws))
+        return LOBRA_ERR_ALIGN;
+    void* hbuf = h_save;
+    if (adapters && !hbuf) {
+        if (!ws || ws_bytes < p.fwd_ws_bytes) return LOBRA_ERR_WORKSPACE;
+        hbuf = ws;
+    }
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const PlanDev pd = device_view(p);
+    const int dt = p.desc.dtype;
+    if (!p.mfma) {
+        if (adapters)
+            LOBRA_LAUNCH(p, st, LOBRA_K_SHRINK,
+                         plain_shrink(pd, dt, x, A, s, static_cast<float*>(hbuf), pd.d_in, st));
+        LOBRA_LAUNCH(p, st, LOBRA_K_GEMM,
+                     plain_gemm(pd, dt, false, x, W, static_cast<const float*>(hbuf), B, y, pd.d_in,
+                                pd.d_out, pd.d_out, st));
+        return LOBRA_OK;
+    }
+    return LOBRA_ERR_DTYPE;
+}
+
+lobra_status lobra_mlora_bwd(const lobra_mlora_plan* plan, const void* x, const void* W,
+                             const void* A, const void* B, const float* s, const void* dy,
+                             const void* h_saved, void* dx, float* dA, float* dB,
+                             uint32_t flags, void* ws, size_t ws_bytes, void* hip_stream)
+{
+    lobra_status rs = runnable(plan);
+    if (rs != LOBRA_OK) return rs;
+    const Plan& p = *plan;
+    const bool adapters = !p.tb.empty();
+    const bool want_dx = !(flags & LOBRA_FLAG_NO_DX);
+    const bool accumulate = (flags & LOBRA_FLAG_ACCUMULATE_GRADS) != 0;
+    if (p.R_tot > 0 && (!dA || !dB)) return LOBRA_ERR_NULL;
+    if (p.desc.T > 0) {
+        if (!W || !dy) return LOBRA_ERR_NULL;
+        if (want_dx && !dx) return LOBRA_ERR_NULL;
+        if (adapters && (!x || !A || !B || !s)) return LOBRA_ERR_NULL;
+    }
+    if (!aligned16(x) || !aligned16(W) || !aligned16(A) || !aligned16(B) || !aligned16(dy) ||
+        !aligned16(h_saved) || !aligned16(dx) || !aligned16(dA) || !aligned16(dB) || !aligned16(ws))
+        return LOBRA_ERR_ALIGN;
+    if (p.bwd_ws_bytes > 0 && adapters && (!ws || ws_bytes < p.bwd_ws_bytes)) return LOBRA_ERR_WORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const PlanDev pd = device_view(p);
+    const int dt = p.desc.dtype;
+    char* wsb = static_cast<char*>(ws);
+    if (!p.mfma) {
+        float* G = adapters ? reinterpret_cast<float*>(wsb + p.bwd_off_g) : nullptr;
+        const float* H = static_cast<const float*>(h_saved);
+        float* part = adapters ? reinterpret_cast<float*>(wsb + p.bwd_off_part) : nullptr;
+        if (adapters) {
+            if (!H) {
+                float* Hr = reinterpret_cast<float*>(wsb + p.bwd_off_h);
+                LOBRA_LAUNCH(p, st, LOBRA_K_SHRINK, plain_shrink(pd, dt, x, A, s, Hr, pd.d_in, st));
+                H = Hr;
+            }
+            LOBRA_LAUNCH(p, st, LOBRA_K_SHRINK, plain_shrink(pd, dt, dy, B, s, G, pd.d_out, st));
+        }
+        if (want_dx && p.desc.T > 0)
+            LOBRA_LAUNCH(p, st, LOBRA_K_GEMM,
+                         plain_gemm(pd, dt, true, dy, W, G, A, dx, pd.d_out, pd.d_in, pd.d_out, st));
+        if (p.R_tot > 0) {
+            if (adapters)
+                LOBRA_LAUNCH(p, st, LOBRA_K_GRAD_STAGE1,
+                             plain_grad_stage1(pd, dt, H, dy, part, pd.d_out, st));
+            LOBRA_LAUNCH(p, st, LOBRA_K_GRAD_STAGE2,
+                         reduce_partials(pd, part, dB, pd.d_out, accumulate, st));
+            if (adapters)
+                LOBRA_LAUNCH(p, st, LOBRA_K_GRAD_STAGE1,
+                             plain_grad_stage1(pd, dt, G, x, part, pd.d_in, st));
+            LOBRA_LAUNCH(p, st, LOBRA_K_GRAD_STAGE2,
+                         reduce_partials(pd, part, dA, pd.d_in, accumulate, st));
+        }
+        return LOBRA_OK;
+    }
+    return LOBRA_ERR_DTYPE;
+}
+
+lobra_status lobra_token_task_map(const lobra_mlora_plan* plan, int32_t* out_task,
+                                  int64_t* out_count, void* hip_stream)
+{
+    lobra_status rs = runnable(plan);
+    if (rs != LOBRA_OK) return rs;
+    const PlanDev pd = device_view(*plan);
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    LOBRA_LAUNCH(*plan, st, LOBRA_K_TOKEN_TASK, token_task_map(pd, out_task, out_count, st));
+    return LOBRA_OK;
+}
+
+lobra_status lobra_mlora_plan_set_trace(lobra_mlora_plan* plan, void* const* events, int32_t n_pairs,
+                                        int32_t* kernel_ids, int32_t* n_launched)
+{
+    if (!plan) return LOBRA_ERR_PLAN;
+    if (n_pairs < 0) return LOBRA_ERR_SHAPE;
+    const bool on = events && n_pairs > 0;
+    plan->trace_events = on ? events : nullptr;
+    plan->trace_pairs = on ? n_pairs : 0;
+    plan->trace_ids = on ? kernel_ids : nullptr;
+    plan->trace_count = on ? n_launched : nullptr;
+    plan->trace_next = 0;
+    if (on && n_launched) *n_launched = 0;
+    return LOBRA_OK;
+}
+
+const char* lobra_status_string(lobra_status st)
+{
+    switch (st) {
+    case LOBRA_OK: return "ok";
+    case LOBRA_ERR_NULL: return "a required pointer is NULL";
+    case LOBRA_ERR_SHAPE: return "shape out of range";
+    case LOBRA_ERR_DTYPE: return "unsupported dtype";
+    case LOBRA_ERR_SEGMENTS: return "malformed segment offsets";
+    case LOBRA_ERR_TASK_ID: return "segment task id out of range";
+    case LOBRA_ERR_RANK: return "adapter rank out of range";
+    case LOBRA_ERR_WORKSPACE: return "workspace missing or too small";
+    case LOBRA_ERR_ALIGN: return "pointer or row length not 16-byte aligned";
+    case LOBRA_ERR_HIP: return "HIP runtime error";
+    case LOBRA_ERR_PLAN: return "plan missing, host-only, or built for another device";
+    case LOBRA_ERR_NOMEM: return "out of memory";
+    }
+    return "unknown status";
+}
+
+int lobra_version(void) { return 100; }
+
+}  // extern "C"

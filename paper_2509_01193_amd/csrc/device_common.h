@@ -1,0 +1,56 @@
+// Shared by the HIP translation units: the device view of a plan and small helpers.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <cstdint>
+
+#include "plan.h"
+
+namespace lobra {
+
+// Device pointers into the plan blob, passed to kernels by value.
+struct PlanDev {
+    const int32_t* cseg_off;       // [nseg+1]
+    const int32_t* cseg_task;      // [nseg]
+    const int32_t* rowblk_seg;     // [ceil(T/32)]
+    const TokenBlock* tb;          // [ntb]
+    const GradChunk* chunks;       // [nchunks]
+    const int32_t* task_chunk_off; // [n_tasks+1]
+    const int32_t* rank_off;       // [n_tasks+1]
+    const int32_t* task_tb_off;    // [n_tasks+1]
+    int32_t T, d_in, d_out, n_tasks, nseg, ntb, nchunks, r_max, r_pad, R_tot;
+};
+
+// Index of the compacted segment that holds `row` (0 <= row < T): start from the table entry
+// of the row's 32-row block and walk forward.
+__device__ __forceinline__ int32_t segment_of_row(const PlanDev& pd, int32_t row)
+{
+    int32_t k = pd.rowblk_seg[row / kRowBlock];
+    while (pd.cseg_off[k + 1] <= row) ++k;
+    return k;
+}
+
+__device__ __forceinline__ float bf16_bits_to_float(uint16_t b)
+{
+    return __uint_as_float(uint32_t(b) << 16);
+}
+
+// Round to nearest even; NaN stays NaN.
+__device__ __forceinline__ uint16_t float_to_bf16_bits(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return uint16_t((u >> 16) | 0x40u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return uint16_t(u >> 16);
+}
+
+template <typename E> struct Elem;
+template <> struct Elem<float> {
+    static __device__ __forceinline__ float load(const float* p, size_t i) { return p[i]; }
+    static __device__ __forceinline__ void store(float* p, size_t i, float v) { p[i] = v; }
+};
+template <> struct Elem<uint16_t> {
+    static __device__ __forceinline__ float load(const uint16_t* p, size_t i) { return bf16_bits_to_float(p[i]); }
+    static __device__ __forceinline__ void store(uint16_t* p, size_t i, float v) { p[i] = float_to_bf16_bits(v); }
+};
+
+}  // namespace lobra

@@ -1,0 +1,28 @@
+// Launchers of the HIP kernels.  Each returns the hipError_t of its launches; none synchronises.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include "device_common.h"
+
+namespace lobra {
+
+// ---- plain fp32-FMA kernels (fp32 path; bf16 storage as a cross-check) ---------------------
+// P[row, :r_t] = s_t * Z[row, :] M_t^T for every token of an adapter segment (fp32, stride r_max).
+hipError_t plain_shrink(const PlanDev& pd, int dtype, const void* Z, const void* M, const float* s,
+                        float* P, int32_t D, hipStream_t st);
+// C[T, N] = Z[T, K] * op(W) + P[:, :r_t] * M_t ;  transW = false: op(W)[k][n] = W[k*ldw + n]
+// (forward), true: op(W)[k][n] = W[n*ldw + k] (backward).
+hipError_t plain_gemm(const PlanDev& pd, int dtype, bool transW, const void* Z, const void* W,
+                      const float* P, const void* M, void* C, int32_t K, int32_t N, int32_t ldw,
+                      hipStream_t st);
+// Stage 1 of dM_t = sum over the tokens of task t of P[i, :]^T Z[i, :]: one partial sum per
+// reduction chunk, written to part[chunk.part_row0 + rho, :].
+hipError_t plain_grad_stage1(const PlanDev& pd, int dtype, const float* P, const void* Z, float* part,
+                             int32_t D, hipStream_t st);
+// Stage 2 (also used by the MFMA path): out[R, :] (+)= sum of the partial sums of task(R), in
+// chunk order, so that the result does not depend on scheduling.
+hipError_t reduce_partials(const PlanDev& pd, const float* part, float* out, int32_t D,
+                           bool accumulate, hipStream_t st);
+hipError_t token_task_map(const PlanDev& pd, int32_t* out_task, int64_t* out_count, hipStream_t st);
+
+}  // namespace lobra

@@ -1,0 +1,258 @@
+// Plain fp32-FMA kernels: the fp32 path of the library, and (on bf16 storage) a slow
+// cross-check of the MFMA kernels.  Straightforward tiling, no matrix cores.
+//
+// They implement the four products of the LoRA layer (paper section 2.1: X W + X (down)(up),
+// applied per task to a fused batch, section 1) and their derivatives:
+//   shrink      P = s_t Z M_t^T            (Z = x, M = A: s_t A_t x_i;  Z = dy, M = B: s_t B_t dy_i)
+//   gemm        C = Z op(W) + P M_t        (y = x W + P B_t;  dx = dy W^T + P A_t)
+//   gradreduce  dM_t = sum_i P_i^T Z_i     (dB_t from P = s h, Z = dy;  dA_t from P = s g, Z = x)
+#include "kernels.h"
+
+namespace lobra {
+
+// -------------------------------------------------------------------------------------------
+// shrink: one workgroup per token block, one wave per row, lanes strided over D
+// -------------------------------------------------------------------------------------------
+template <typename E>
+__global__ __launch_bounds__(256) void plain_shrink_kernel(PlanDev pd, const E* __restrict__ Z,
+                                                           const E* __restrict__ M,
+                                                           const float* __restrict__ s,
+                                                           float* __restrict__ P, int32_t D)
+{
+    const TokenBlock b = pd.tb[blockIdx.x];
+    const int32_t r = pd.rank_off[b.task + 1] - pd.rank_off[b.task];
+    const float st = s[b.task];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int32_t rr = wave; rr < b.nrows; rr += 4) {
+        const size_t row = size_t(b.row0 + rr);
+        for (int32_t p0 = 0; p0 < pd.r_max; p0 += 8) {
+            float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+            if (p0 < r) {
+                for (int32_t k = lane; k < D; k += 64) {
+                    const float z = Elem<E>::load(Z, row * D + k);
+#pragma unroll
+                    for (int q = 0; q < 8; ++q)
+                        if (p0 + q < r)
+                            acc[q] = fmaf(z, Elem<E>::load(M, size_t(b.rank_row0 + p0 + q) * D + k), acc[q]);
+                }
+#pragma unroll
+                for (int q = 0; q < 8; ++q)
+                    for (int off = 32; off > 0; off >>= 1) acc[q] += __shfl_xor(acc[q], off, 64);
+            }
+            if (lane < 8 && p0 + lane < pd.r_max) {
+                float v = 0.f;
+#pragma unroll
+                for (int q = 0; q < 8; ++q)
+                    if (q == lane) v = acc[q];
+                P[row * pd.r_max + p0 + lane] = (p0 + lane < r) ? st * v : 0.f;
+            }
+        }
+    }
+}
+
+hipError_t plain_shrink(const PlanDev& pd, int dtype, const void* Z, const void* M, const float* s,
+                        float* P, int32_t D, hipStream_t st)
+{
+    if (pd.ntb == 0) return hipSuccess;
+    if (dtype == LOBRA_F32)
+        plain_shrink_kernel<float><<<pd.ntb, 256, 0, st>>>(pd, (const float*)Z, (const float*)M, s, P, D);
+    else
+        plain_shrink_kernel<uint16_t><<<pd.ntb, 256, 0, st>>>(pd, (const uint16_t*)Z, (const uint16_t*)M, s, P, D);
+    return hipGetLastError();
+}
+
+// -------------------------------------------------------------------------------------------
+// gemm: 64 x 64 tile, K step 16, 4 x 4 outputs per thread, adapter term added per element
+// -------------------------------------------------------------------------------------------
+template <typename E, bool TRANSW>
+__global__ __launch_bounds__(256) void plain_gemm_kernel(PlanDev pd, const E* __restrict__ Z,
+                                                         const E* __restrict__ W,
+                                                         const float* __restrict__ P,
+                                                         const E* __restrict__ M, E* __restrict__ C,
+                                                         int32_t K, int32_t N, int32_t ldw)
+{
+    __shared__ float Zs[16][64 + 4];
+    __shared__ float Ws[16][64 + 4];
+    const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
+    const int32_t row0 = blockIdx.y * 64, col0 = blockIdx.x * 64;
+    const int32_t T = pd.T;
+    float acc[4][4] = {};
+    for (int32_t k0 = 0; k0 < K; k0 += 16) {
+        for (int e = tid; e < 64 * 16; e += 256) {
+            {   // Z tile: 64 rows x 16 k, k fastest in memory
+                const int kk = e & 15, m = e >> 4;
+                const int32_t row = row0 + m, k = k0 + kk;
+                Zs[kk][m] = (row < T && k < K) ? Elem<E>::load(Z, size_t(row) * K + k) : 0.f;
+            }
+            if (TRANSW) {   // op(W)[k][n] = W[n*ldw + k]: k fastest
+                const int kk = e & 15, nn = e >> 4;
+                const int32_t n = col0 + nn, k = k0 + kk;
+                Ws[kk][nn] = (n < N && k < K) ? Elem<E>::load(W, size_t(n) * ldw + k) : 0.f;
+            } else {        // op(W)[k][n] = W[k*ldw + n]: n fastest
+                const int nn = e & 63, kk = e >> 6;
+                const int32_t n = col0 + nn, k = k0 + kk;
+                Ws[kk][nn] = (n < N && k < K) ? Elem<E>::load(W, size_t(k) * ldw + n) : 0.f;
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int kk = 0; kk < 16; ++kk) {
+            float a[4], b[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) a[i] = Zs[kk][ty * 4 + i];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) b[j] = Ws[kk][tx * 4 + j];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
+        }
+        __syncthreads();
+    }
+    for (int i = 0; i < 4; ++i) {
+        const int32_t row = row0 + ty * 4 + i;
+        if (row >= T) continue;
+        const int32_t t = pd.cseg_task[segment_of_row(pd, row)];
+        if (t >= 0) {
+            const int32_t r0 = pd.rank_off[t], r = pd.rank_off[t + 1] - r0;
+            for (int32_t p = 0; p < r; ++p) {
+                const float pv = P[size_t(row) * pd.r_max + p];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int32_t col = col0 + tx * 4 + j;
+                    if (col < N) acc[i][j] = fmaf(pv, Elem<E>::load(M, size_t(r0 + p) * N + col), acc[i][j]);
+                }
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int32_t col = col0 + tx * 4 + j;
+            if (col < N) Elem<E>::store(C, size_t(row) * N + col, acc[i][j]);
+        }
+    }
+}
+
+hipError_t plain_gemm(const PlanDev& pd, int dtype, bool transW, const void* Z, const void* W,
+                      const float* P, const void* M, void* C, int32_t K, int32_t N, int32_t ldw,
+                      hipStream_t st)
+{
+    if (pd.T == 0) return hipSuccess;
+    const dim3 grid((N + 63) / 64, (pd.T + 63) / 64);
+    if (grid.y > 65535u) return hipErrorInvalidValue;
+#define LOBRA_LAUNCH(E, TR) \
+    plain_gemm_kernel<E, TR><<<grid, 256, 0, st>>>(pd, (const E*)Z, (const E*)W, P, (const E*)M, (E*)C, K, N, ldw)
+    if (dtype == LOBRA_F32) {
+        if (transW) LOBRA_LAUNCH(float, true); else LOBRA_LAUNCH(float, false);
+    } else {
+        if (transW) LOBRA_LAUNCH(uint16_t, true); else LOBRA_LAUNCH(uint16_t, false);
+    }
+#undef LOBRA_LAUNCH
+    return hipGetLastError();
+}
+
+// -------------------------------------------------------------------------------------------
+// gradreduce stage 1: one workgroup per (chunk, 256 columns), one thread per column
+// -------------------------------------------------------------------------------------------
+template <typename E>
+__global__ __launch_bounds__(256) void plain_gradreduce_kernel(PlanDev pd, const float* __restrict__ P,
+                                                               const E* __restrict__ Z,
+                                                               float* __restrict__ part, int32_t D)
+{
+    const GradChunk c = pd.chunks[blockIdx.x];
+    const int32_t r = pd.rank_off[c.task + 1] - pd.rank_off[c.task];
+    const int32_t col = blockIdx.y * 256 + threadIdx.x;
+    const bool live = col < D;
+    for (int32_t p0 = 0; p0 < r; p0 += 16) {
+        float acc[16] = {};
+        for (int32_t bi = c.tb_begin; bi < c.tb_end; ++bi) {
+            const TokenBlock b = pd.tb[bi];
+            for (int32_t rr = 0; rr < b.nrows; ++rr) {
+                const size_t row = size_t(b.row0 + rr);
+                const float z = live ? Elem<E>::load(Z, row * D + col) : 0.f;
+#pragma unroll
+                for (int q = 0; q < 16; ++q)
+                    if (p0 + q < r) acc[q] = fmaf(P[row * pd.r_max + p0 + q], z, acc[q]);
+            }
+        }
+        if (live)
+#pragma unroll
+            for (int q = 0; q < 16; ++q)
+                if (p0 + q < r) part[size_t(c.part_row0 + p0 + q) * D + col] = acc[q];
+    }
+}
+
+// stage 2: out[R, col] (+)= sum over the chunks of task(R), in chunk order
+__global__ __launch_bounds__(256) void reduce_partials_kernel(PlanDev pd, const float* __restrict__ part,
+                                                              float* __restrict__ out, int32_t D,
+                                                              int accumulate)
+{
+    const int32_t R = blockIdx.x;
+    int32_t t = 0;
+    while (pd.rank_off[t + 1] <= R) ++t;
+    const int32_t p = R - pd.rank_off[t];
+    const int32_t c0 = pd.task_chunk_off[t], c1 = pd.task_chunk_off[t + 1];
+    for (int32_t col = blockIdx.y * 1024 + threadIdx.x; col < min(D, (int32_t)(blockIdx.y + 1) * 1024); col += 256) {
+        float acc = 0.f;
+        for (int32_t c = c0; c < c1; ++c) acc += part[size_t(pd.chunks[c].part_row0 + p) * D + col];
+        const size_t o = size_t(R) * D + col;
+        out[o] = accumulate ? out[o] + acc : acc;
+    }
+}
+
+hipError_t reduce_partials(const PlanDev& pd, const float* part, float* out, int32_t D,
+                           bool accumulate, hipStream_t st)
+{
+    if (pd.R_tot == 0) return hipSuccess;
+    const dim3 grid(pd.R_tot, (D + 1023) / 1024);
+    if (grid.y > 65535u) return hipErrorInvalidValue;
+    reduce_partials_kernel<<<grid, 256, 0, st>>>(pd, part, out, D, accumulate ? 1 : 0);
+    return hipGetLastError();
+}
+
+hipError_t plain_grad_stage1(const PlanDev& pd, int dtype, const float* P, const void* Z, float* part,
+                             int32_t D, hipStream_t st)
+{
+    if (pd.nchunks == 0) return hipSuccess;
+    const dim3 grid(pd.nchunks, (D + 255) / 256);
+    if (grid.y > 65535u) return hipErrorInvalidValue;
+    if (dtype == LOBRA_F32)
+        plain_gradreduce_kernel<float><<<grid, 256, 0, st>>>(pd, P, (const float*)Z, part, D);
+    else
+        plain_gradreduce_kernel<uint16_t><<<grid, 256, 0, st>>>(pd, P, (const uint16_t*)Z, part, D);
+    return hipGetLastError();
+}
+
+// -------------------------------------------------------------------------------------------
+// index probe
+// -------------------------------------------------------------------------------------------
+__global__ void zero_counts_kernel(unsigned long long* cnt, int32_t n)
+{
+    const int32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) cnt[i] = 0ull;
+}
+
+__global__ __launch_bounds__(256) void token_task_kernel(PlanDev pd, int32_t* __restrict__ out_task,
+                                                         unsigned long long* __restrict__ cnt)
+{
+    const int32_t row = blockIdx.x * 256 + threadIdx.x;
+    if (row >= pd.T) return;
+    const int32_t t = pd.cseg_task[segment_of_row(pd, row)];
+    if (out_task) out_task[row] = t;
+    if (cnt && t >= 0) atomicAdd(&cnt[t], 1ull);   // integer sum: order does not matter
+}
+
+hipError_t token_task_map(const PlanDev& pd, int32_t* out_task, int64_t* out_count, hipStream_t st)
+{
+    if (out_count && pd.n_tasks > 0) {
+        zero_counts_kernel<<<(pd.n_tasks + 255) / 256, 256, 0, st>>>((unsigned long long*)out_count, pd.n_tasks);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    if (pd.T > 0) {
+        token_task_kernel<<<(pd.T + 255) / 256, 256, 0, st>>>(pd, out_task, (unsigned long long*)out_count);
+        return hipGetLastError();
+    }
+    return hipSuccess;
+}
+
+}  // namespace lobra

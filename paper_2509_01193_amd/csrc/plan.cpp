@@ -1,0 +1,179 @@
+// Validation of the problem descriptor and construction of the host-side work lists.
+// The lists turn the packed batch's segment table (paper section 1: a fused batch holds the
+// sequences of several tasks, each tagged with its task) into what the kernels iterate over.
+#include "plan.h"
+
+#include <algorithm>
+#include <cstring>
+#include <new>
+
+namespace lobra {
+
+static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+lobra_status validate(const lobra_mlora_desc* d)
+{
+    if (!d) return LOBRA_ERR_NULL;
+    if (d->dtype != LOBRA_F32 && d->dtype != LOBRA_BF16) return LOBRA_ERR_DTYPE;
+    if (d->T < 0 || d->T >= (int64_t(1) << 31)) return LOBRA_ERR_SHAPE;
+    if (d->d_in < 1 || d->d_out < 1 || d->n_tasks < 0 || d->S < 0) return LOBRA_ERR_SHAPE;
+    if (d->S == 0 && d->T != 0) return LOBRA_ERR_SEGMENTS;
+    if (d->dtype == LOBRA_BF16 && (d->d_in % 8 != 0 || d->d_out % 8 != 0)) return LOBRA_ERR_ALIGN;
+    if (d->n_tasks > 0) {
+        if (!d->rank_off) return LOBRA_ERR_NULL;
+        if (d->rank_off[0] != 0) return LOBRA_ERR_RANK;
+        for (int32_t t = 0; t < d->n_tasks; ++t) {
+            const int64_t r = int64_t(d->rank_off[t + 1]) - d->rank_off[t];
+            if (r < 1 || r > LOBRA_MAX_RANK) return LOBRA_ERR_RANK;
+        }
+    }
+    if (d->S > 0) {
+        if (!d->seg_off || !d->seg_task) return LOBRA_ERR_NULL;
+        if (d->seg_off[0] != 0) return LOBRA_ERR_SEGMENTS;
+        for (int32_t k = 0; k < d->S; ++k)
+            if (d->seg_off[k + 1] < d->seg_off[k]) return LOBRA_ERR_SEGMENTS;
+        if (int64_t(d->seg_off[d->S]) != d->T) return LOBRA_ERR_SEGMENTS;
+        for (int32_t k = 0; k < d->S; ++k)
+            if (d->seg_task[k] < -1 || d->seg_task[k] >= d->n_tasks) return LOBRA_ERR_TASK_ID;
+    }
+    return LOBRA_OK;
+}
+
+lobra_status build_host_plan(const lobra_mlora_desc* d, uint32_t flags, Plan* p)
+{
+    try {
+        p->desc = *d;
+        p->flags = flags;
+        p->mfma = kMfmaKernels && d->dtype == LOBRA_BF16 && !(flags & LOBRA_PLAN_PLAIN_KERNELS);
+        const int32_t n = d->n_tasks;
+        p->rank_off.assign(size_t(n) + 1, 0);
+        for (int32_t t = 0; t <= n && n > 0; ++t) p->rank_off[t] = d->rank_off[t];
+        p->R_tot = p->rank_off[n];
+        p->r_max = 0;
+        for (int32_t t = 0; t < n; ++t)
+            p->r_max = std::max(p->r_max, p->rank_off[t + 1] - p->rank_off[t]);
+        p->r_pad = (p->r_max + 15) / 16 * 16;
+        p->seg_off_in.assign(d->seg_off ? d->seg_off : nullptr,
+                             d->seg_off ? d->seg_off + d->S + 1 : nullptr);
+        p->seg_task_in.assign(d->seg_task ? d->seg_task : nullptr,
+                              d->seg_task ? d->seg_task + d->S : nullptr);
+        p->desc.rank_off = p->rank_off.data();
+        p->desc.seg_off = p->seg_off_in.data();
+        p->desc.seg_task = p->seg_task_in.data();
+
+        // 1. compacted table: no empty segments, no two neighbours with the same task
+        p->cseg_off.assign(1, 0);
+        p->cseg_task.clear();
+        for (int32_t k = 0; k < d->S; ++k) {
+            const int32_t len = d->seg_off[k + 1] - d->seg_off[k];
+            if (len == 0) continue;
+            if (!p->cseg_task.empty() && p->cseg_task.back() == d->seg_task[k]) {
+                p->cseg_off.back() += len;
+            } else {
+                p->cseg_task.push_back(d->seg_task[k]);
+                p->cseg_off.push_back(p->cseg_off.back() + len);
+            }
+        }
+        const int32_t nseg = int32_t(p->cseg_task.size());
+        const int32_t T = int32_t(d->T);
+
+        // 2. first segment of every 32-row block
+        const int32_t nrb = (T + kRowBlock - 1) / kRowBlock;
+        p->rowblk_seg.assign(size_t(nrb), 0);
+        for (int32_t b = 0, k = 0; b < nrb; ++b) {
+            while (p->cseg_off[k + 1] <= b * kRowBlock) ++k;
+            p->rowblk_seg[b] = k;
+        }
+
+        // 3. token blocks, grouped by task (counting sort keeps token order inside a task)
+        p->task_tb_off.assign(size_t(n) + 1, 0);
+        for (int32_t k = 0; k < nseg; ++k) {
+            const int32_t t = p->cseg_task[k];
+            if (t < 0) continue;
+            const int32_t len = p->cseg_off[k + 1] - p->cseg_off[k];
+            p->task_tb_off[t + 1] += (len + kTokenBlock - 1) / kTokenBlock;
+        }
+        for (int32_t t = 0; t < n; ++t) p->task_tb_off[t + 1] += p->task_tb_off[t];
+        p->tb.assign(size_t(p->task_tb_off[n]), TokenBlock{0, 0, 0, 0});
+        {
+            std::vector<int32_t> cur(p->task_tb_off.begin(), p->task_tb_off.end() - (n >= 0 ? 1 : 0));
+            for (int32_t k = 0; k < nseg; ++k) {
+                const int32_t t = p->cseg_task[k];
+                if (t < 0) continue;
+                for (int32_t r0 = p->cseg_off[k]; r0 < p->cseg_off[k + 1]; r0 += kTokenBlock) {
+                    const int32_t nr = std::min(kTokenBlock, p->cseg_off[k + 1] - r0);
+                    p->tb[size_t(cur[t]++)] = TokenBlock{r0, nr, t, p->rank_off[t]};
+                }
+            }
+        }
+
+        // 4. reduction chunks: runs of token blocks of one task.  The chunk length is chosen so
+        //    that (chunks x 128-column tiles) gives roughly a thousand workgroups, within
+        //    [4, 64] token blocks; fewer, longer chunks mean less partial-sum traffic.
+        const int64_t coltiles = (std::min(d->d_in, d->d_out) + 127) / 128;
+        int64_t cb = (int64_t(T) * coltiles / 1024 + kTokenBlock - 1) / kTokenBlock;
+        cb = std::max<int64_t>(4, std::min<int64_t>(64, cb));
+        p->chunk_blocks = int32_t(cb);
+        p->chunks.clear();
+        p->task_chunk_off.assign(size_t(n) + 1, 0);
+        p->part_rows = 0;
+        for (int32_t t = 0; t < n; ++t) {
+            const int32_t r = p->rank_off[t + 1] - p->rank_off[t];
+            for (int32_t b = p->task_tb_off[t]; b < p->task_tb_off[t + 1]; b += p->chunk_blocks) {
+                const int32_t e = std::min(b + p->chunk_blocks, p->task_tb_off[t + 1]);
+                p->chunks.push_back(GradChunk{b, e, t, p->part_rows});
+                p->part_rows += r;
+            }
+            p->task_chunk_off[t + 1] = int32_t(p->chunks.size());
+        }
+
+        // 5. buffer sizes
+        BufferLayout& L = p->p_layout;
+        const size_t ntb = p->tb.size();
+        if (ntb == 0) {
+            L = BufferLayout{};
+        } else if (p->mfma) {
+            L.p_tok = 0;
+            L.p_blk = align_up(size_t(T) * p->r_pad * 2, 256);
+            L.total = L.p_blk + align_up(ntb * size_t(p->r_pad) * kTokenBlock * 2, 256);
+        } else {
+            L.p_tok = 0;
+            L.p_blk = 0;
+            L.total = align_up(size_t(T) * p->r_max * 4, 256);
+        }
+        p->h_save_bytes = L.total;
+        p->fwd_ws_bytes = L.total;
+        p->bwd_off_g = 0;
+        p->bwd_off_h = L.total;
+        p->bwd_off_part = 2 * L.total;
+        p->bwd_ws_bytes = p->bwd_off_part +
+            align_up(size_t(p->part_rows) * size_t(std::max(d->d_in, d->d_out)) * 4, 256);
+    } catch (const std::bad_alloc&) {
+        return LOBRA_ERR_NOMEM;
+    }
+    return LOBRA_OK;
+}
+
+std::vector<int32_t> pack_blob(Plan* p)
+{
+    std::vector<int32_t> blob;
+    auto put = [&](const int32_t* src, size_t n) {
+        while (blob.size() % 4) blob.push_back(0);   // 16-byte alignment of every list
+        const size_t off = blob.size();
+        blob.insert(blob.end(), src, src + n);
+        if (n == 0) blob.push_back(0);               // keep every list pointer valid
+        return off;
+    };
+    p->o_cseg_off = put(p->cseg_off.data(), p->cseg_off.size());
+    p->o_cseg_task = put(p->cseg_task.data(), p->cseg_task.size());
+    p->o_rowblk = put(p->rowblk_seg.data(), p->rowblk_seg.size());
+    p->o_tb = put(reinterpret_cast<const int32_t*>(p->tb.data()), p->tb.size() * 4);
+    p->o_chunks = put(reinterpret_cast<const int32_t*>(p->chunks.data()), p->chunks.size() * 4);
+    p->o_task_chunk = put(p->task_chunk_off.data(), p->task_chunk_off.size());
+    p->o_rank_off = put(p->rank_off.data(), p->rank_off.size());
+    p->o_task_tb = put(p->task_tb_off.data(), p->task_tb_off.size());
+    while (blob.size() % 4) blob.push_back(0);
+    return blob;
+}
+
+}  // namespace lobra

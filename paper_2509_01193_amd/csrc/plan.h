@@ -1,0 +1,70 @@
+// Host side of a batch plan: validation of the descriptor and the work lists that the
+// kernels walk.  Pure C++ (no HIP), so that it can be built and tested without a GPU.
+#pragma once
+#include <cstddef>
+#include <cstdint>
+#include <vector>
+
+#include "lobra_mlora.h"
+
+namespace lobra {
+
+constexpr int kTokenBlock = 32;   // tokens per token block (one MFMA K step of the reductions)
+constexpr int kRowBlock = 32;     // granularity of the row -> segment lookup table
+constexpr bool kMfmaKernels = false;  // bf16 storage runs on the MFMA kernels
+
+struct TokenBlock { int32_t row0, nrows, task, rank_row0; };
+struct GradChunk  { int32_t tb_begin, tb_end, task, part_row0; };
+
+// Byte offsets of the sub-buffers inside h_save and the workspaces.
+struct BufferLayout {
+    size_t p_tok = 0;     // token-major projected activations  [T][pstride]
+    size_t p_blk = 0;     // block-transposed copy              [n_tb][rpad][32]  (MFMA path)
+    size_t total = 0;
+};
+
+struct Plan {
+    lobra_mlora_desc desc{};            // table pointers point into the vectors below
+    uint32_t flags = 0;
+    bool mfma = false;                  // bf16 storage and MFMA kernels
+    int32_t r_max = 0, r_pad = 0, R_tot = 0;
+    std::vector<int32_t> rank_off;      // [n_tasks+1]
+    std::vector<int32_t> seg_off_in, seg_task_in;   // the caller's table, as given
+    std::vector<int32_t> cseg_off, cseg_task;       // compacted table
+    std::vector<int32_t> rowblk_seg;    // [ceil(T/32)]
+    std::vector<TokenBlock> tb;         // grouped by task, token order inside a task
+    std::vector<int32_t> task_tb_off;   // [n_tasks+1]
+    std::vector<GradChunk> chunks;      // grouped by task
+    std::vector<int32_t> task_chunk_off;// [n_tasks+1]
+    int32_t part_rows = 0;              // rows of the partial-sum buffer = sum over chunks of r_t
+    int32_t chunk_blocks = 0;           // token blocks per reduction chunk
+
+    BufferLayout p_layout;              // layout of h_save (and of the G buffer in bwd)
+    size_t h_save_bytes = 0, fwd_ws_bytes = 0, bwd_ws_bytes = 0;
+    size_t bwd_off_g = 0, bwd_off_h = 0, bwd_off_part = 0;
+
+    // optional launch trace (see lobra_mlora_plan_set_trace)
+    mutable void* const* trace_events = nullptr;
+    mutable int32_t trace_pairs = 0;
+    mutable int32_t* trace_ids = nullptr;
+    mutable int32_t* trace_count = nullptr;
+    mutable int32_t trace_next = 0;
+
+    // device copy (absent for host-only plans)
+    int device = -1;
+    void* dev_blob = nullptr;
+    size_t blob_bytes = 0;
+    // offsets (in int32 units) of the lists inside the blob
+    size_t o_cseg_off = 0, o_cseg_task = 0, o_rowblk = 0, o_tb = 0, o_chunks = 0,
+           o_task_chunk = 0, o_rank_off = 0, o_task_tb = 0;
+};
+
+lobra_status validate(const lobra_mlora_desc* d);
+// Fills every host field of `p` (not the device copy).  `d` has been validated.
+lobra_status build_host_plan(const lobra_mlora_desc* d, uint32_t flags, Plan* p);
+// Packs the lists into one int32 blob; sets the o_* offsets.
+std::vector<int32_t> pack_blob(Plan* p);
+
+}  // namespace lobra
+
+struct lobra_mlora_plan : lobra::Plan {};

@@ -1,0 +1,233 @@
+"""GPU parity: the HIP library against the fp64 oracle, element by element, through the C ABI.
+
+Tolerances (per output tensor Z in {y, dx, dA, dB}): max|Z_gpu - Z_ref| / max|Z_ref|
+  <= 1e-5 on the fp32 path, <= 2e-2 on the bf16 path (bf16 storage, fp32 accumulation);
+the token -> task indexing is compared bit for bit.
+"""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2509_01193_amd import binding as bd
+from paper_2509_01193_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-5, "bf16": 2e-2}
+
+
+def relerr(got, ref):
+    den = np.abs(ref).max()
+    return float(np.abs(got - ref).max() / (den if den > 0 else 1.0))
+
+
+def make_oracle(p):
+    return oracle.Oracle(p.x, p.W, p.A, p.B, p.s, p.dy, p.rank_off, p.seg_off, p.seg_task)
+
+
+def sample_rows(p, n_random, seed=0):
+    """First and last two rows of every segment, every row of short segments, plus random rows."""
+    rows = set()
+    for k in range(p.S):
+        lo, hi = int(p.seg_off[k]), int(p.seg_off[k + 1])
+        if hi - lo <= 64:
+            rows.update(range(lo, hi))
+        else:
+            rows.update((lo, lo + 1, hi - 2, hi - 1))
+    rows.update((0, p.T - 1))
+    rng = np.random.default_rng(seed)
+    rows.update(rng.integers(0, p.T, n_random).tolist())
+    return np.asarray(sorted(r for r in rows if 0 <= r < p.T), np.int64)
+
+
+def check_problem(p, rows=None, plan_flags=0, tol=None, label=""):
+    """Runs fwd+bwd on the GPU and compares all four outputs with the oracle."""
+    import torch
+    tol = tol or TOL[p.dtype]
+    dp = bd.DeviceProblem(p, plan_flags)
+    dp.step()
+    torch.cuda.synchronize()
+    o = make_oracle(p)
+    if rows is None:
+        y, dx = dp.host(dp.y), dp.host(dp.dx)
+    else:
+        idx = torch.from_numpy(rows).to(dp.dev)
+        y, dx = dp.host(dp.y.index_select(0, idx)), dp.host(dp.dx.index_select(0, idx))
+    errs = {"y": relerr(y, o.y(rows)), "dx": relerr(dx, o.dx(rows))}
+    if p.R_tot:
+        dA, dB = o.grads()
+        errs["dA"] = relerr(dp.host(dp.dA), dA)
+        errs["dB"] = relerr(dp.host(dp.dB), dB)
+    print("%s %s errs=%s" % (label, p.name, {k: "%.2e" % v for k, v in errs.items()}), flush=True)
+    for k, v in errs.items():
+        assert v <= tol, (p.name, k, v, tol)
+    return dp, errs
+
+
+def check_index_probe(p):
+    import torch
+    dp_plan = bd.Plan.for_problem(p)
+    out_task = torch.full((max(p.T, 1),), -7, dtype=torch.int32, device="cuda:0")
+    out_cnt = torch.full((max(p.n_tasks, 1),), -7, dtype=torch.int64, device="cuda:0")
+    bd.lobra_token_task_map(dp_plan, out_task, out_cnt)
+    torch.cuda.synchronize()
+    ref = oracle.token_task(p.T, p.seg_off, p.seg_task, p.n_tasks)
+    assert np.array_equal(out_task.cpu().numpy()[: p.T], ref)
+    if p.n_tasks:
+        assert np.array_equal(out_cnt.cpu().numpy(), np.bincount(ref[ref >= 0], minlength=p.n_tasks))
+    dp_plan.close()
+
+
+# ---------------------------------------------------------------------------------------------
+def test_config1_fp32_full():
+    p = wl.make_config(1)
+    check_index_probe(p)
+    check_problem(p)
+
+
+SHRUNK = {2: (264, 328), 3: (192, 344), 4: (136, 200), 5: (328, 264)}
+
+
+@pytest.mark.parametrize("cfg", [2, 3, 4, 5])
+@pytest.mark.parametrize("order", ["shuffled", "sorted"])
+def test_token_structure_of_each_workload_on_a_narrow_layer(cfg, order):
+    """Real token counts and segment tables, layer shrunk so the oracle covers every element."""
+    d_in, d_out = SHRUNK[cfg]
+    p = wl.make_config(cfg, order, d_in=d_in, d_out=d_out)
+    check_index_probe(p)
+    check_problem(p, label=order)
+
+
+def test_config3_reversed_rank_pairing():
+    p = wl.make_config(3, "shuffled", d_in=192, d_out=344, reverse_ranks=True)
+    check_problem(p)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_adapter_term_alone_w_zero(dtype):
+    """W = 0 leaves only the adapter path under the tolerance; B_t scaled by (t+1) separates tasks."""
+    p = wl.make_config(2, "shuffled", d_in=512, d_out=384)
+    if dtype == "f32":
+        for k in ("x", "W", "A", "B", "dy"):
+            setattr(p, k, wl.bf16_bits_to_f32(getattr(p, k)))
+        p.dtype = "f32"
+    p.W = np.zeros_like(p.W)
+    ro = p.rank_off
+    for t in range(p.n_tasks):
+        blk = wl.bf16_bits_to_f32(p.B[ro[t]:ro[t + 1]]) if dtype == "bf16" else p.B[ro[t]:ro[t + 1]]
+        blk = blk * np.float32(t + 1)
+        p.B[ro[t]:ro[t + 1]] = wl.f32_to_bf16_bits(blk) if dtype == "bf16" else blk
+    check_problem(p, label="W=0 " + dtype)
+
+
+def adversarial_tables():
+    rng = np.random.default_rng(42)
+    out = {}
+    # boundaries at every residue of the tile sizes, one-token and empty segments, no-adapter spans
+    lens = [1, 0, 31, 1, 33, 255, 2, 257, 0, 16, 16, 16, 16, 300, 1, 1, 1, 511, 17]
+    out["residues"] = (np.concatenate([[0], np.cumsum(lens)]), rng.integers(-1, 4, len(lens)))
+    out["alternate16"] = (np.arange(0, 16 * 41, 16), np.arange(40) % 4)
+    out["single"] = (np.asarray([0, 777]), np.asarray([2]))
+    out["task_without_tokens"] = (np.asarray([0, 100, 300, 301]), np.asarray([0, 3, 0]))
+    out["no_adapter_only"] = (np.asarray([0, 130]), np.asarray([-1]))
+    out["one_token_each"] = (np.arange(0, 70), np.arange(69) % 3)
+    return out
+
+
+@pytest.mark.parametrize("name", sorted(adversarial_tables()))
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_adversarial_segment_tables(name, dtype):
+    seg_off, seg_task = adversarial_tables()[name]
+    p = wl.make_custom(name, dtype, 136, 264, [8, 16, 5, 64], seg_off, seg_task, 99,
+                       s=[2.0, 0.5, -1.0, 3.0])
+    check_index_probe(p)
+    dp, _ = check_problem(p, label=dtype)
+    if name == "task_without_tokens":
+        ro = p.rank_off
+        for t in (1, 2):
+            assert not dp.dA[ro[t]:ro[t + 1]].any().item() and not dp.dB[ro[t]:ro[t + 1]].any().item()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_flags_saved_h_determinism_and_canaries(dtype):
+    import torch
+    p = wl.make_config(2, "shuffled", d_in=264, d_out=328)
+    if dtype == "f32":
+        for k in ("x", "W", "A", "B", "dy"):
+            setattr(p, k, wl.bf16_bits_to_f32(getattr(p, k)))
+        p.dtype = "f32"
+    dp = bd.DeviceProblem(p)
+    # outputs live inside larger buffers whose margins must stay untouched
+    pad = 1024
+
+    def padded(t):
+        big = torch.full((t.numel() + 2 * pad,), 7.0, dtype=t.dtype, device=t.device)
+        return big, big[pad:pad + t.numel()].view(t.shape)
+    bigs = {}
+    for name in ("y", "dx", "dA", "dB"):
+        bigs[name], view = padded(getattr(dp, name))
+        setattr(dp, name, view)
+    dp.step()
+    torch.cuda.synchronize()
+    first = {n: getattr(dp, n).clone() for n in ("y", "dx", "dA", "dB")}
+    for name, big in bigs.items():
+        assert (big[:pad] == 7.0).all().item() and (big[-pad:] == 7.0).all().item(), name
+    # same call again: bit-identical (fixed reduction order)
+    dp.step()
+    torch.cuda.synchronize()
+    for n, v in first.items():
+        assert torch.equal(getattr(dp, n), v), n
+    # recomputing h in bwd instead of using the saved copy gives the same bits
+    dp.fwd(save_h=False)
+    dp.bwd(use_saved_h=False)
+    torch.cuda.synchronize()
+    for n, v in first.items():
+        assert torch.equal(getattr(dp, n), v), n
+    # accumulate: dA, dB doubled; NO_DX leaves dx alone
+    dp.dx.fill_(3.0)
+    dp.bwd(flags=bd.FLAG_ACCUMULATE_GRADS | bd.FLAG_NO_DX)
+    torch.cuda.synchronize()
+    assert torch.equal(dp.dA, 2 * first["dA"]) and torch.equal(dp.dB, 2 * first["dB"])
+    assert (dp.dx == 3.0).all().item()
+
+
+def test_empty_batch_and_argument_errors():
+    import torch
+    p = wl.make_custom("empty", "bf16", 64, 64, [8], [0], [], 5)
+    dp = bd.DeviceProblem(p)
+    dp.dA.fill_(1.0)
+    dp.step()
+    torch.cuda.synchronize()
+    assert not dp.dA.any().item()                 # no tokens: gradients are zero
+    p = wl.make_config(1)
+    dp = bd.DeviceProblem(p)
+    st = bd.lobra_mlora_fwd(dp.plan, None, dp.W, dp.A, dp.B, dp.s, dp.y, check=False)
+    assert st == -1
+    st = bd.lobra_mlora_fwd(dp.plan, dp.x, dp.W, dp.A, dp.B, dp.s, dp.y, None, None, check=False)
+    assert st == -7                               # needs scratch when h_save is not given
+    st = bd.lobra_mlora_bwd(dp.plan, dp.x, dp.W, dp.A, dp.B, dp.s, dp.dy, None, dp.dx, dp.dA, dp.dB,
+                            0, dp.ws[:64], check=False)
+    assert st == -7
+    off = dp.x.view(-1)[1:1 + dp.x.numel() - 4]
+    st = bd.lib().lobra_mlora_fwd(dp.plan.handle, off.data_ptr(), dp.W.data_ptr(), dp.A.data_ptr(),
+                                  dp.B.data_ptr(), dp.s.data_ptr(), dp.y.data_ptr(), None,
+                                  dp.ws.data_ptr(), dp.ws.numel(), None)
+    assert st == -8
+
+
+# ---------------------------------------------------------------------------------------------
+# full-size workloads in the launch configuration bench.py times: sampled rows of y and dx that
+# the oracle computes one by one, dA and dB in full
+# ---------------------------------------------------------------------------------------------
+FULL_ROWS = {2: 1024, 3: 768, 4: 96, 5: 256}
+
+
+@pytest.mark.parametrize("cfg", [2, 3, 5, 4])
+def test_full_size_workload_sampled_rows(cfg):
+    p = wl.make_config(cfg, "shuffled")
+    rows = sample_rows(p, FULL_ROWS[cfg])
+    # the last rows sit beyond 2^32 bytes in y/dy at workload 4
+    dp, errs = check_problem(p, rows=rows, label="full rows=%d" % len(rows))
+    del dp
+    import torch
+    torch.cuda.empty_cache()

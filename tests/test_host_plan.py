@@ -1,0 +1,153 @@
+"""CPU tests of the C-ABI library's host side: exported symbols, argument errors, work lists.
+
+No kernel is launched here.  The work lists are compared bit for bit with a brute-force walk
+over the token -> task map that the oracle computes from the same segment table.
+"""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2509_01193_amd import binding as bd
+from paper_2509_01193_amd import workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "lobra_mlora.h")).read()
+    declared = set(re.findall(r"\b(lobra_[a-z_]+)\s*\(", hdr))
+    assert declared == set(bd.EXPORTS)
+    L = bd.lib()
+    for name in declared:
+        assert hasattr(L, name), name
+    assert bd.version() >= 100
+    assert bd.status_string(0) == "ok" and "segment" in bd.status_string(-4)
+
+
+def _desc(**kw):
+    base = dict(dtype="f32", T=10, d_in=8, d_out=8, rank_off=[0, 2, 5], seg_off=[0, 4, 10], seg_task=[0, 1])
+    base.update(kw)
+    return bd.make_desc(**base)
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(), 0),
+    (dict(dtype=7), -3),
+    (dict(T=-1), -2),
+    (dict(d_in=0), -2),
+    (dict(seg_off=[1, 4, 10]), -4),
+    (dict(seg_off=[0, 11, 10]), -4),
+    (dict(seg_off=[0, 4, 9]), -4),
+    (dict(seg_task=[0, 2]), -5),
+    (dict(seg_task=[-2, 1]), -5),
+    (dict(rank_off=[0, 0, 5]), -6),
+    (dict(rank_off=[1, 2, 5]), -6),
+    (dict(rank_off=[0, 2, 2 + 129]), -6),
+    (dict(dtype="bf16", d_in=12), -8),
+    (dict(dtype="bf16", d_in=16, d_out=24), 0),
+    (dict(seg_task=[-1, -1]), 0),
+])
+def test_validate_status_codes(kw, code):
+    d, keep = _desc(**kw)
+    assert bd.validate(d) == code
+
+
+def test_validate_null_tables_and_empty_batch():
+    d, _ = bd.make_desc("f32", 0, 8, 8, None, None, None)
+    assert bd.validate(d) == 0                       # T = 0, S = 0, no tasks
+    d, _ = bd.make_desc("f32", 5, 8, 8, None, None, None)
+    assert bd.validate(d) == -4                      # tokens but no segment
+    d, keep = _desc()
+    d.seg_task = None
+    assert bd.validate(d) == -1
+    assert bd.lib().lobra_mlora_validate(None) == -1
+
+
+def test_host_only_plan_cannot_run():
+    p = wl.make_config(1, fill=False)
+    plan = bd.Plan.for_problem(p, bd.PLAN_HOST_ONLY)
+    st = bd.lib().lobra_mlora_fwd(plan.handle, None, None, None, None, None, None, None, None, 0, None)
+    assert st == -10
+    assert bd.lib().lobra_mlora_fwd(None, None, None, None, None, None, None, None, None, 0, None) == -10
+    assert bd.lib().lobra_mlora_plan_destroy(None) == 0
+
+
+def brute_force_lists(p):
+    tok = oracle.token_task(p.T, p.seg_off, p.seg_task, p.n_tasks)
+    # maximal runs of equal task
+    segs, i = [], 0
+    while i < p.T:
+        j = i
+        while j < p.T and tok[j] == tok[i]:
+            j += 1
+        segs.append((i, j, int(tok[i])))
+        i = j
+    return tok, segs
+
+
+def check_plan(p):
+    plan = bd.Plan.for_problem(p, bd.PLAN_HOST_ONLY)
+    tok, segs = brute_force_lists(p)
+    got = plan.query(bd.Q_SEGMENTS).reshape(-1, 3)
+    assert [tuple(r) for r in got.tolist()] == segs
+    rb = plan.query(bd.Q_ROWBLOCK_SEG)
+    assert len(rb) == (p.T + 31) // 32
+    for b, k in enumerate(rb):
+        assert segs[k][0] <= 32 * b < segs[k][1]
+    tb = plan.query(bd.Q_TOKEN_BLOCKS).reshape(-1, 4)
+    ro = p.rank_off
+    covered = np.zeros(p.T, np.int32)
+    last_task, last_row = -1, -1
+    for row0, nrows, task, rr0 in tb.tolist():
+        assert 1 <= nrows <= 32 and 0 <= task < p.n_tasks and rr0 == ro[task]
+        assert (tok[row0:row0 + nrows] == task).all()
+        covered[row0:row0 + nrows] += 1
+        assert task > last_task or (task == last_task and row0 > last_row)   # by task, then by token
+        last_task, last_row = task, row0
+    assert (covered == (tok >= 0)).all()          # every adapter token in exactly one block
+    # a block never spans two segments, and only a segment's last block may be short
+    starts = {s[0] for s in segs}
+    ends = {s[1] for s in segs}
+    for row0, nrows, task, _ in tb.tolist():
+        assert nrows == 32 or (row0 + nrows) in ends
+        assert not any(row0 < s < row0 + nrows for s in starts)
+    ch = plan.query(bd.Q_GRAD_CHUNKS).reshape(-1, 4)
+    tco = plan.query(bd.Q_TASK_CHUNKS)
+    assert len(tco) == p.n_tasks + 1 and tco[0] == 0 and tco[-1] == len(ch)
+    nxt, prow = 0, 0
+    for c, (b0, b1, task, pr0) in enumerate(ch.tolist()):
+        assert b0 == nxt and b1 > b0 and pr0 == prow
+        assert (tb[b0:b1, 2] == task).all()
+        assert tco[task] <= c < tco[task + 1]
+        nxt, prow = b1, prow + int(p.ranks[task])
+    assert nxt == len(tb)
+    a, b, c = plan.h_save_bytes, plan.fwd_ws_bytes, plan.bwd_ws_bytes
+    assert c >= prow * max(p.d_in, p.d_out) * 4
+    plan.close()
+    return len(tb), len(ch)
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
+@pytest.mark.parametrize("order", ["shuffled", "sorted"])
+def test_work_lists_of_the_five_workloads(cfg, order):
+    check_plan(wl.make_config(cfg, order, fill=False))
+
+
+def test_work_lists_adversarial_tables():
+    rng = np.random.default_rng(0)
+    for trial in range(40):
+        S = int(rng.integers(1, 40))
+        lens = rng.choice([0, 1, 2, 15, 16, 17, 31, 32, 33, 64, 100], S)
+        seg_task = rng.integers(-1, 5, S)
+        seg_off = np.concatenate([[0], np.cumsum(lens)])
+        p = wl.make_custom("adv", "bf16", 64, 128, [8, 16, 3, 64, 128], seg_off, seg_task, trial, fill=False)
+        check_plan(p)
+    # one-token segments alternating between tasks, and an all-empty table
+    p = wl.make_custom("alt", "f32", 8, 8, [2, 2], np.arange(0, 101), np.arange(100) % 2, 1, fill=False)
+    assert check_plan(p) == (100, 2 * -(-50 // 4))
+    p = wl.make_custom("none", "f32", 8, 8, [2, 2], [0, 0, 0], [0, 1], 1, fill=False)
+    assert check_plan(p) == (0, 0)
