@@ -211,7 +211,15 @@ lobra_status lobra_mlora_fwd(const lobra_mlora_plan* plan, const void* x, const 
                                 pd.d_out, pd.d_out, st));
         return LOBRA_OK;
     }
-    return LOBRA_ERR_DTYPE;
+    // bf16 MFMA path
+    char* hb = static_cast<char*>(hbuf);
+    if (adapters)
+        LOBRA_LAUNCH(p, st, LOBRA_K_SHRINK,
+                     shrink_mfma(pd, x, A, s, hb + p.p_layout.p_tok, hb + p.p_layout.p_blk, pd.d_in, st));
+    LOBRA_LAUNCH(p, st, LOBRA_K_GEMM,
+                 gemm_mfma(pd, false, x, W, adapters ? hb + p.p_layout.p_tok : nullptr, B, y, pd.d_in,
+                           pd.d_out, pd.d_out, st));
+    return LOBRA_OK;
 }
 
 lobra_status lobra_mlora_bwd(const lobra_mlora_plan* plan, const void* x, const void* W,
@@ -257,18 +265,46 @@ lobra_status lobra_mlora_bwd(const lobra_mlora_plan* plan, const void* x, const 
         if (p.R_tot > 0) {
             if (adapters)
                 LOBRA_LAUNCH(p, st, LOBRA_K_GRAD_STAGE1,
-                             plain_grad_stage1(pd, dt, H, dy, part, pd.d_out, st));
+                             plain_grad_stage1(pd, dt, false, H, dy, part, pd.d_out, st));
             LOBRA_LAUNCH(p, st, LOBRA_K_GRAD_STAGE2,
                          reduce_partials(pd, part, dB, pd.d_out, accumulate, st));
             if (adapters)
                 LOBRA_LAUNCH(p, st, LOBRA_K_GRAD_STAGE1,
-                             plain_grad_stage1(pd, dt, G, x, part, pd.d_in, st));
+                             plain_grad_stage1(pd, dt, false, G, x, part, pd.d_in, st));
             LOBRA_LAUNCH(p, st, LOBRA_K_GRAD_STAGE2,
                          reduce_partials(pd, part, dA, pd.d_in, accumulate, st));
         }
         return LOBRA_OK;
     }
-    return LOBRA_ERR_DTYPE;
+    // bf16 MFMA path
+    char* G = adapters ? wsb + p.bwd_off_g : nullptr;
+    const char* H = static_cast<const char*>(h_saved);
+    float* part = adapters ? reinterpret_cast<float*>(wsb + p.bwd_off_part) : nullptr;
+    if (adapters) {
+        if (!H) {
+            char* Hr = wsb + p.bwd_off_h;
+            LOBRA_LAUNCH(p, st, LOBRA_K_SHRINK,
+                         shrink_mfma(pd, x, A, s, Hr + p.p_layout.p_tok, Hr + p.p_layout.p_blk, pd.d_in, st));
+            H = Hr;
+        }
+        LOBRA_LAUNCH(p, st, LOBRA_K_SHRINK,
+                     shrink_mfma(pd, dy, B, s, G + p.p_layout.p_tok, G + p.p_layout.p_blk, pd.d_out, st));
+    }
+    if (want_dx && p.desc.T > 0)
+        LOBRA_LAUNCH(p, st, LOBRA_K_GEMM,
+                     gemm_mfma(pd, true, dy, W, adapters ? G + p.p_layout.p_tok : nullptr, A, dx, pd.d_out,
+                               pd.d_in, pd.d_out, st));
+    if (p.R_tot > 0) {
+        if (adapters)
+            LOBRA_LAUNCH(p, st, LOBRA_K_GRAD_STAGE1,
+                         plain_grad_stage1(pd, dt, true, H + p.p_layout.p_tok, dy, part, pd.d_out, st));
+        LOBRA_LAUNCH(p, st, LOBRA_K_GRAD_STAGE2, reduce_partials(pd, part, dB, pd.d_out, accumulate, st));
+        if (adapters)
+            LOBRA_LAUNCH(p, st, LOBRA_K_GRAD_STAGE1,
+                         plain_grad_stage1(pd, dt, true, G + p.p_layout.p_tok, x, part, pd.d_in, st));
+        LOBRA_LAUNCH(p, st, LOBRA_K_GRAD_STAGE2, reduce_partials(pd, part, dA, pd.d_in, accumulate, st));
+    }
+    return LOBRA_OK;
 }
 
 lobra_status lobra_token_task_map(const lobra_mlora_plan* plan, int32_t* out_task,

@@ -17,12 +17,21 @@ hipError_t plain_gemm(const PlanDev& pd, int dtype, bool transW, const void* Z, 
                       hipStream_t st);
 // Stage 1 of dM_t = sum over the tokens of task t of P[i, :]^T Z[i, :]: one partial sum per
 // reduction chunk, written to part[chunk.part_row0 + rho, :].
-hipError_t plain_grad_stage1(const PlanDev& pd, int dtype, const float* P, const void* Z, float* part,
-                             int32_t D, hipStream_t st);
+// P is fp32 [T][r_max], or (p_bf16) bf16 [T][r_pad].
+hipError_t plain_grad_stage1(const PlanDev& pd, int dtype, bool p_bf16, const void* P, const void* Z,
+                             float* part, int32_t D, hipStream_t st);
 // Stage 2 (also used by the MFMA path): out[R, :] (+)= sum of the partial sums of task(R), in
 // chunk order, so that the result does not depend on scheduling.
 hipError_t reduce_partials(const PlanDev& pd, const float* part, float* out, int32_t D,
                            bool accumulate, hipStream_t st);
+// ---- bf16 MFMA kernels ------------------------------------------------------------------------
+// C[T, N] = Z[T, K] * op(W) + P * M_t with P bf16 [T][r_pad] (already scaled by s_t, zero beyond r_t).
+hipError_t gemm_mfma(const PlanDev& pd, bool transW, const void* Z, const void* W, const void* P,
+                     const void* M, void* C, int32_t K, int32_t N, int32_t ldw, hipStream_t st);
+// P = s_t Z M_t^T in bf16, written token-major [T][r_pad] and block-transposed [ntb][r_pad][32].
+hipError_t shrink_mfma(const PlanDev& pd, const void* Z, const void* M, const float* s,
+                       void* P_tok, void* P_blk, int32_t D, hipStream_t st);
+
 hipError_t token_task_map(const PlanDev& pd, int32_t* out_task, int64_t* out_count, hipStream_t st);
 
 }  // namespace lobra

@@ -153,9 +153,9 @@ hipError_t plain_gemm(const PlanDev& pd, int dtype, bool transW, const void* Z, 
 // -------------------------------------------------------------------------------------------
 // gradreduce stage 1: one workgroup per (chunk, 256 columns), one thread per column
 // -------------------------------------------------------------------------------------------
-template <typename E>
-__global__ __launch_bounds__(256) void plain_gradreduce_kernel(PlanDev pd, const float* __restrict__ P,
-                                                               const E* __restrict__ Z,
+template <typename E, typename PE>
+__global__ __launch_bounds__(256) void plain_gradreduce_kernel(PlanDev pd, const PE* __restrict__ P,
+                                                               int32_t pstride, const E* __restrict__ Z,
                                                                float* __restrict__ part, int32_t D)
 {
     const GradChunk c = pd.chunks[blockIdx.x];
@@ -171,7 +171,7 @@ __global__ __launch_bounds__(256) void plain_gradreduce_kernel(PlanDev pd, const
                 const float z = live ? Elem<E>::load(Z, row * D + col) : 0.f;
 #pragma unroll
                 for (int q = 0; q < 16; ++q)
-                    if (p0 + q < r) acc[q] = fmaf(P[row * pd.r_max + p0 + q], z, acc[q]);
+                    if (p0 + q < r) acc[q] = fmaf(Elem<PE>::load(P, row * pstride + p0 + q), z, acc[q]);
             }
         }
         if (live)
@@ -209,16 +209,18 @@ hipError_t reduce_partials(const PlanDev& pd, const float* part, float* out, int
     return hipGetLastError();
 }
 
-hipError_t plain_grad_stage1(const PlanDev& pd, int dtype, const float* P, const void* Z, float* part,
-                             int32_t D, hipStream_t st)
+hipError_t plain_grad_stage1(const PlanDev& pd, int dtype, bool p_bf16, const void* P, const void* Z,
+                             float* part, int32_t D, hipStream_t st)
 {
     if (pd.nchunks == 0) return hipSuccess;
     const dim3 grid(pd.nchunks, (D + 255) / 256);
     if (grid.y > 65535u) return hipErrorInvalidValue;
     if (dtype == LOBRA_F32)
-        plain_gradreduce_kernel<float><<<grid, 256, 0, st>>>(pd, P, (const float*)Z, part, D);
+        plain_gradreduce_kernel<float, float><<<grid, 256, 0, st>>>(pd, (const float*)P, pd.r_max, (const float*)Z, part, D);
+    else if (!p_bf16)
+        plain_gradreduce_kernel<uint16_t, float><<<grid, 256, 0, st>>>(pd, (const float*)P, pd.r_max, (const uint16_t*)Z, part, D);
     else
-        plain_gradreduce_kernel<uint16_t><<<grid, 256, 0, st>>>(pd, P, (const uint16_t*)Z, part, D);
+        plain_gradreduce_kernel<uint16_t, uint16_t><<<grid, 256, 0, st>>>(pd, (const uint16_t*)P, pd.r_pad, (const uint16_t*)Z, part, D);
     return hipGetLastError();
 }
 

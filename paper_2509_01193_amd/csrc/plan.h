@@ -11,7 +11,7 @@ namespace lobra {
 
 constexpr int kTokenBlock = 32;   // tokens per token block (one MFMA K step of the reductions)
 constexpr int kRowBlock = 32;     // granularity of the row -> segment lookup table
-constexpr bool kMfmaKernels = false;  // bf16 storage runs on the MFMA kernels
+constexpr bool kMfmaKernels = true;   // bf16 storage runs on the MFMA kernels
 
 struct TokenBlock { int32_t row0, nrows, task, rank_row0; };
 struct GradChunk  { int32_t tb_begin, tb_end, task, part_row0; };

@@ -1,0 +1,144 @@
+// HBM-bound rank-r kernels of the bf16 path (gfx950 MFMA, operands streamed straight from
+// global memory into MFMA registers: the skinny operand needs no LDS tile at all).
+//
+//   shrink_mfma      P = s_t Z M_t^T   (Z = x, M = A gives s_t A_t x_i; Z = dy, M = B gives s_t B_t dy_i)
+//   grad_mfma        stage 1 of dM_t = sum_i P_i^T Z_i over a reduction chunk (dB from P = s h,
+//                    Z = dy; dA from P = s g, Z = x), partial sums per chunk
+// (paper section 2.1: the two low-rank factors of X (down)(up) and their gradients; section 1:
+// each task of the fused batch has its own pair.)
+#include "kernels.h"
+
+namespace lobra {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+namespace {
+__device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v)
+{
+    union { u32x4 u; bf16x8 b; } c;
+    c.u = v;
+    return c.b;
+}
+}  // namespace
+
+// -------------------------------------------------------------------------------------------------
+// shrink: one workgroup per token block (<= 32 tokens of one task), 4 waves split K.
+// v_mfma_f32_16x16x32_bf16 with the MFMA "A" operand = 16 rank rows of M_t and the "B" operand =
+// 16 token rows of Z, so a lane ends up with 4 consecutive ranks of one token.  K is walked in
+// slabs of 128: lane (row, kg) loads the 32 consecutive elements slab + 32 kg .. + 31 of its row as
+// four 16-byte pieces, and piece q of every lane forms MFMA q.  Any assignment of k values to MFMA
+// slots is valid as long as both operands use the same one; this one makes the four lanes of a
+// row read 256 contiguous bytes.
+// -------------------------------------------------------------------------------------------------
+template <int NRB>   // rank blocks of 16 handled (r_t <= 16 NRB)
+__global__ __launch_bounds__(256) void shrink_mfma_kernel(PlanDev pd, const uint16_t* __restrict__ Z,
+                                                          const uint16_t* __restrict__ M,
+                                                          const float* __restrict__ s,
+                                                          uint16_t* __restrict__ P_tok,
+                                                          uint16_t* __restrict__ P_blk, int32_t D,
+                                                          int32_t tb_begin)
+{
+    __shared__ float red[4][2][NRB][64][4];   // [wave][token half][rank block][lane][4]
+    const int32_t bi = tb_begin + blockIdx.x;
+    const TokenBlock b = pd.tb[bi];
+    const int32_t r = pd.rank_off[b.task + 1] - b.rank_row0;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int j = lane & 15, kg = lane >> 4;
+    const u32x4 zero4 = {0u, 0u, 0u, 0u};
+
+    f32x4 acc[2][NRB];
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int rb = 0; rb < NRB; ++rb) acc[h][rb] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    // rows beyond the block repeat its last row (their results are never stored)
+    const uint16_t* zrow[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+        zrow[h] = Z + size_t(b.row0 + min(16 * h + j, b.nrows - 1)) * D;
+    const bool two_halves = b.nrows > 16;
+
+    for (int32_t slab = wave * 128; slab < D; slab += 512) {
+        const int32_t k = slab + 32 * kg;
+        u32x4 zv[2][4], mv[NRB][4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const bool kin = k + 8 * q < D;
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+                zv[h][q] = (kin && (h == 0 || two_halves))
+                               ? *reinterpret_cast<const u32x4*>(zrow[h] + k + 8 * q) : zero4;
+#pragma unroll
+            for (int rb = 0; rb < NRB; ++rb)
+                mv[rb][q] = (kin && 16 * rb + j < r)
+                                ? *reinterpret_cast<const u32x4*>(M + size_t(b.rank_row0 + 16 * rb + j) * D + k + 8 * q)
+                                : zero4;
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+#pragma unroll
+                for (int rb = 0; rb < NRB; ++rb)
+                    acc[h][rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(mv[rb][q]), as_bf16x8(zv[h][q]),
+                                                                         acc[h][rb], 0, 0, 0);
+    }
+    // cross-wave sum through LDS, then lane (token j, rank group kg) of wave 0/1 stores half h
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int rb = 0; rb < NRB; ++rb)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) red[wave][h][rb][lane][v] = acc[h][rb][v];
+    __syncthreads();
+    if (wave < 2) {
+        const int h = wave;
+        const int32_t tok = 16 * h + j;
+        const float st = s[b.task];
+#pragma unroll
+        for (int rb = 0; rb < NRB; ++rb) {
+            bf16x4 o;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const float sum = (red[0][h][rb][lane][v] + red[1][h][rb][lane][v]) +
+                                  (red[2][h][rb][lane][v] + red[3][h][rb][lane][v]);
+                const int32_t p = 16 * rb + 4 * kg + v;
+                o[v] = (__bf16)((p < r && tok < b.nrows) ? st * sum : 0.f);
+            }
+            const int32_t p0 = 16 * rb + 4 * kg;
+            if (p0 < pd.r_pad) {
+                if (tok < b.nrows)
+                    *reinterpret_cast<bf16x4*>(P_tok + size_t(b.row0 + tok) * pd.r_pad + p0) = o;
+                // block-transposed copy [block][rank][32 tokens]; tokens beyond the block hold 0
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    union { __bf16 b; uint16_t u; } c;
+                    c.b = o[v];
+                    P_blk[(size_t(bi) * pd.r_pad + p0 + v) * kTokenBlock + tok] = c.u;
+                }
+            }
+        }
+    }
+}
+
+hipError_t shrink_mfma(const PlanDev& pd, const void* Z, const void* M, const float* s,
+                       void* P_tok, void* P_blk, int32_t D, hipStream_t st)
+{
+    if (pd.ntb == 0) return hipSuccess;
+    const int nrb = pd.r_pad / 16;
+#define LOBRA_SHRINK(NRB)                                                                              \
+    shrink_mfma_kernel<NRB><<<pd.ntb, 256, 0, st>>>(pd, (const uint16_t*)Z, (const uint16_t*)M, s,     \
+                                                    (uint16_t*)P_tok, (uint16_t*)P_blk, D, 0)
+    if (nrb <= 1) LOBRA_SHRINK(1);
+    else if (nrb <= 2) LOBRA_SHRINK(2);
+    else if (nrb <= 4) LOBRA_SHRINK(4);
+    else LOBRA_SHRINK(8);
+#undef LOBRA_SHRINK
+    return hipGetLastError();
+}
+
+}  // namespace lobra
