@@ -297,11 +297,11 @@ lobra_status lobra_mlora_bwd(const lobra_mlora_plan* plan, const void* x, const 
     if (p.R_tot > 0) {
         if (adapters)
             LOBRA_LAUNCH(p, st, LOBRA_K_GRAD_STAGE1,
-                         plain_grad_stage1(pd, dt, true, H + p.p_layout.p_tok, dy, part, pd.d_out, st));
+                         grad_mfma(pd, H + p.p_layout.p_blk, dy, part, pd.d_out, st));
         LOBRA_LAUNCH(p, st, LOBRA_K_GRAD_STAGE2, reduce_partials(pd, part, dB, pd.d_out, accumulate, st));
         if (adapters)
             LOBRA_LAUNCH(p, st, LOBRA_K_GRAD_STAGE1,
-                         plain_grad_stage1(pd, dt, true, G + p.p_layout.p_tok, x, part, pd.d_in, st));
+                         grad_mfma(pd, G + p.p_layout.p_blk, x, part, pd.d_in, st));
         LOBRA_LAUNCH(p, st, LOBRA_K_GRAD_STAGE2, reduce_partials(pd, part, dA, pd.d_in, accumulate, st));
     }
     return LOBRA_OK;

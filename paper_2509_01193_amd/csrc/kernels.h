@@ -32,6 +32,10 @@ hipError_t gemm_mfma(const PlanDev& pd, bool transW, const void* Z, const void* 
 hipError_t shrink_mfma(const PlanDev& pd, const void* Z, const void* M, const float* s,
                        void* P_tok, void* P_blk, int32_t D, hipStream_t st);
 
+// Stage 1 of dM_t = sum_i P_i^T Z_i from the block-transposed P; partial sums per reduction chunk.
+hipError_t grad_mfma(const PlanDev& pd, const void* P_blk, const void* Z, float* part, int32_t D,
+                     hipStream_t st);
+
 hipError_t token_task_map(const PlanDev& pd, int32_t* out_task, int64_t* out_count, hipStream_t st);
 
 }  // namespace lobra

@@ -141,4 +141,126 @@ hipError_t shrink_mfma(const PlanDev& pd, const void* Z, const void* M, const fl
     return hipGetLastError();
 }
 
+// -------------------------------------------------------------------------------------------------
+// grad stage 1: partial dM over one reduction chunk and 128 columns per workgroup of 4 waves.
+// Wave w takes the chunk's token blocks w, w+4, ...  For one block, lane (c, g) loads the 8 token
+// rows 8g .. 8g+7 at the 8 columns 8c .. 8c+7 (16 bytes per row, so a row is read in 256-byte runs),
+// transposes the 8 x 8 patch in registers (v_perm_b32) into 8 MFMA "B" operands - operand jj holds
+// 8 tokens of column 8c + jj - and multiplies each with the "A" operand P_blk[rank][32 tokens].
+// MFMA jj therefore produces the columns {8c + jj}, and a lane ends up with 8 consecutive columns.
+// The four waves' sums are combined through LDS in two rounds (fixed order: ((w0+w2)+(w1+w3))).
+// -------------------------------------------------------------------------------------------------
+template <int NRB>
+__global__ __launch_bounds__(256) void grad_mfma_kernel(PlanDev pd, const uint16_t* __restrict__ P_blk,
+                                                        const uint16_t* __restrict__ Z,
+                                                        float* __restrict__ part, int32_t D)
+{
+    __shared__ float red[2][NRB][8][64][4];
+    const GradChunk ch = pd.chunks[blockIdx.x];
+    const int32_t r = pd.rank_off[ch.task + 1] - pd.rank_off[ch.task];
+    const int32_t rb0 = blockIdx.z * NRB;                 // first rank block of this pass
+    if (16 * rb0 >= r) return;                            // uniform: nothing to do for this task
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int c = lane & 15, g = lane >> 4;
+    const int32_t col = blockIdx.y * 128 + 8 * c;
+    const bool col_in = col < D;
+    const u32x4 zero4 = {0u, 0u, 0u, 0u};
+
+    f32x4 acc[NRB][8];
+#pragma unroll
+    for (int rb = 0; rb < NRB; ++rb)
+#pragma unroll
+        for (int jj = 0; jj < 8; ++jj) acc[rb][jj] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    for (int32_t bi = ch.tb_begin + wave; bi < ch.tb_end; bi += 4) {
+        const TokenBlock b = pd.tb[bi];
+        u32x4 zin[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            // rows beyond the block repeat its last row; their P entries are zero
+            const int32_t row = b.row0 + min(8 * g + q, b.nrows - 1);
+            zin[q] = col_in ? *reinterpret_cast<const u32x4*>(Z + size_t(row) * D + col) : zero4;
+        }
+        u32x4 pf[NRB];
+#pragma unroll
+        for (int rb = 0; rb < NRB; ++rb)
+            pf[rb] = (16 * (rb0 + rb) < pd.r_pad)
+                         ? *reinterpret_cast<const u32x4*>(
+                               P_blk + (size_t(bi) * pd.r_pad + 16 * (rb0 + rb) + c) * kTokenBlock + 8 * g)
+                         : zero4;
+#pragma unroll
+        for (int jj = 0; jj < 8; ++jj) {
+            u32x4 f;
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                f[e] = __builtin_amdgcn_perm(zin[2 * e + 1][jj >> 1], zin[2 * e][jj >> 1],
+                                             (jj & 1) ? 0x07060302u : 0x05040100u);
+#pragma unroll
+            for (int rb = 0; rb < NRB; ++rb)
+                acc[rb][jj] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(pf[rb]), as_bf16x8(f),
+                                                                      acc[rb][jj], 0, 0, 0);
+        }
+    }
+    // round 1: waves 2, 3 hand their sums to waves 0, 1; round 2: wave 1 hands its sum to wave 0
+    if (wave >= 2)
+#pragma unroll
+        for (int rb = 0; rb < NRB; ++rb)
+#pragma unroll
+            for (int jj = 0; jj < 8; ++jj)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) red[wave - 2][rb][jj][lane][v] = acc[rb][jj][v];
+    __syncthreads();
+    if (wave < 2)
+#pragma unroll
+        for (int rb = 0; rb < NRB; ++rb)
+#pragma unroll
+            for (int jj = 0; jj < 8; ++jj)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) acc[rb][jj][v] += red[wave][rb][jj][lane][v];
+    __syncthreads();
+    if (wave == 1)
+#pragma unroll
+        for (int rb = 0; rb < NRB; ++rb)
+#pragma unroll
+            for (int jj = 0; jj < 8; ++jj)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) red[0][rb][jj][lane][v] = acc[rb][jj][v];
+    __syncthreads();
+    if (wave == 0 && col_in) {
+#pragma unroll
+        for (int rb = 0; rb < NRB; ++rb)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int32_t p = 16 * (rb0 + rb) + 4 * g + v;
+                if (p >= r) continue;
+                f32x4 lo, hi;
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj) {
+                    lo[jj] = acc[rb][jj][v] + red[0][rb][jj][lane][v];
+                    hi[jj] = acc[rb][jj + 4][v] + red[0][rb][jj + 4][lane][v];
+                }
+                float* dst = part + size_t(ch.part_row0 + p) * D + col;
+                *reinterpret_cast<f32x4*>(dst) = lo;
+                *reinterpret_cast<f32x4*>(dst + 4) = hi;
+            }
+    }
+}
+
+hipError_t grad_mfma(const PlanDev& pd, const void* P_blk, const void* Z, float* part, int32_t D,
+                     hipStream_t st)
+{
+    if (pd.nchunks == 0) return hipSuccess;
+    const int nrb = pd.r_pad / 16;
+    const int NRB = nrb <= 1 ? 1 : (nrb <= 2 ? 2 : 4);
+    const dim3 grid(pd.nchunks, (D + 127) / 128, (nrb + NRB - 1) / NRB);
+    if (grid.y > 65535u) return hipErrorInvalidValue;
+    if (NRB == 1)
+        grad_mfma_kernel<1><<<grid, 256, 0, st>>>(pd, (const uint16_t*)P_blk, (const uint16_t*)Z, part, D);
+    else if (NRB == 2)
+        grad_mfma_kernel<2><<<grid, 256, 0, st>>>(pd, (const uint16_t*)P_blk, (const uint16_t*)Z, part, D);
+    else
+        grad_mfma_kernel<4><<<grid, 256, 0, st>>>(pd, (const uint16_t*)P_blk, (const uint16_t*)Z, part, D);
+    return hipGetLastError();
+}
+
 }  // namespace lobra
