@@ -64,6 +64,9 @@ def main():
     ap.add_argument("--order", default="shuffled", choices=["shuffled", "sorted"])
     ap.add_argument("--oracle-rows", type=int, default=1536)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--pmc-probe", action="store_true",
+                    help="for rocprofv3 --pmc runs: 2 steps and one plain device copy of x (a kernel of "
+                         "known traffic that calibrates FETCH_SIZE / WRITE_SIZE), then exit")
     a = ap.parse_args()
     if a.gpus != 1:
         sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
@@ -80,6 +83,15 @@ def main():
     t0 = time.perf_counter()
     dp = bd.DeviceProblem(p)
     torch.cuda.synchronize()
+
+    if a.pmc_probe:
+        dp.step()
+        dp.step()
+        ref = torch.empty_like(dp.x)
+        ref.copy_(dp.x)          # reads and writes x.numel() * 2 bytes
+        torch.cuda.synchronize()
+        print(json.dumps({"pmc_probe": True, "copy_bytes_each_way": dp.x.numel() * dp.x.element_size()}))
+        return
 
     def timed(fn, steps, warmup):
         for _ in range(warmup):
