@@ -11,7 +11,8 @@ import os
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "liblobra_mlora.so")
+# LOBRA_MLORA_LIB points at another build of the same library (kernel tuning variants).
+LIB_PATH = os.environ.get("LOBRA_MLORA_LIB") or os.path.join(_HERE, "liblobra_mlora.so")
 
 OK = 0
 F32, BF16 = 0, 1

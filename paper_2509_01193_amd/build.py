@@ -35,17 +35,21 @@ def headers():
     return hs
 
 
-def build(force: bool = True, verbose: bool = False) -> str:
-    """Compile every source (always, when force) and link the shared library."""
-    os.makedirs(OBJ, exist_ok=True)
+def build(force: bool = True, verbose: bool = False, defines=(), out: str = LIB, objdir: str = OBJ) -> str:
+    """Compile every source (always, when force) and link the shared library.
+
+    `defines` (e.g. ["LOBRA_GEMM_WM=2"]), `out` and `objdir` build a tuning variant next to the
+    default library."""
+    os.makedirs(objdir, exist_ok=True)
     newest_h = max(os.path.getmtime(h) for h in headers())
 
     def compile_one(src):
-        obj = os.path.join(OBJ, os.path.basename(src) + ".o")
+        obj = os.path.join(objdir, os.path.basename(src) + ".o")
         if (not force and os.path.exists(obj)
                 and os.path.getmtime(obj) >= max(os.path.getmtime(src), newest_h)):
             return obj
-        cmd = [HIPCC] + FLAGS + (["-x", "hip"] if src.endswith(".hip") else []) + ["-c", src, "-o", obj]
+        cmd = ([HIPCC] + FLAGS + ["-D" + d for d in defines]
+               + (["-x", "hip"] if src.endswith(".hip") else []) + ["-c", src, "-o", obj])
         if verbose:
             print(" ".join(cmd), flush=True)
         r = subprocess.run(cmd, capture_output=True, text=True)
@@ -57,13 +61,13 @@ def build(force: bool = True, verbose: bool = False) -> str:
 
     with ThreadPoolExecutor(4) as ex:
         objs = list(ex.map(compile_one, sources()))
-    tmp = LIB + ".tmp%d" % os.getpid()
+    tmp = out + ".tmp%d" % os.getpid()
     cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp] + objs
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("link failed:\n%s\n%s" % (r.stdout, r.stderr))
-    os.replace(tmp, LIB)
-    return LIB
+    os.replace(tmp, out)
+    return out
 
 
 if __name__ == "__main__":

@@ -5,8 +5,8 @@
 // (paper section 2.1: X W + X (down)(up); section 1: one shared base product for the fused batch,
 // a per-task adapter product on top of it).
 //
-// Tiling: 256 x 256 x 64 per workgroup of 4 waves (2 x 2), every wave owns 128 x 128 as 4 x 4
-// v_mfma_f32_32x32x16_bf16 blocks (256 fp32 accumulators per lane), LDS double buffered,
+// Tiling: 256 x 256 x 64 per workgroup of WM x WN waves, every wave owns (256/WM) x (256/WN) as
+// blocks of v_mfma_f32_32x32x16_bf16 with fp32 accumulators in AGPRs, LDS double buffered,
 // global -> register -> LDS prefetch of the next K tile while the current one is multiplied.
 // The MFMA "A" operand is fed from W and the "B" operand from Z, so a lane ends up with four
 // consecutive output columns of one row, which packs into 8-byte LDS writes in the epilogue.
@@ -17,8 +17,24 @@
 //   W tile when N is fastest (forward): [64 k][256 + 32 n]; the MFMA operand (8 consecutive k
 //       of one column) is gathered with two ds_read_b64_tr_b16, the row pitch of 576 bytes puts
 //       the 4 k-rows of one pass in different bank quarters.
-//   C staging in the epilogue: per wave [128 rows][128 + 8 cols] bf16.
+//   C staging in the epilogue: per wave [rows][cols + 8] bf16.
 #include "kernels.h"
+
+#ifndef LOBRA_GEMM_DMA
+#define LOBRA_GEMM_DMA 1
+#endif
+#ifndef LOBRA_GEMM_DBK
+#define LOBRA_GEMM_DBK 64
+#endif
+#ifndef LOBRA_GEMM_DST
+#define LOBRA_GEMM_DST 2
+#endif
+#ifndef LOBRA_GEMM_WM
+#define LOBRA_GEMM_WM 2
+#endif
+#ifndef LOBRA_GEMM_WN
+#define LOBRA_GEMM_WN 4
+#endif
 
 namespace lobra {
 
@@ -27,7 +43,6 @@ typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 namespace {
 
@@ -36,13 +51,17 @@ constexpr int ZT_BYTES = BM * BK * 2;               // 32 KiB
 constexpr int WKN_PITCH = BN + 32;                  // elements
 constexpr int WT_KN_BYTES = BK * WKN_PITCH * 2;     // 36 KiB
 constexpr int WT_NK_BYTES = BN * BK * 2;            // 32 KiB
-constexpr int CS_PITCH = 128 + 8;                   // elements, per-wave C staging
-constexpr int CS_BYTES = 4 * 128 * CS_PITCH * 2;    // 136 KiB
 
-template <bool W_KN> constexpr int lds_bytes()
+// direct-to-LDS variant: K tile of DBK, DST stages of (Z tile + W tile)
+constexpr int DBK = LOBRA_GEMM_DBK, DST = LOBRA_GEMM_DST;
+constexpr int DZT_BYTES = BM * DBK * 2, DSTAGE_BYTES = 2 * DZT_BYTES;
+static_assert((DBK == 32 || DBK == 64) && DST >= 2 && DST <= 4 && DST * DSTAGE_BYTES <= 160 * 1024, "LDS budget");
+
+template <bool W_KN, int WN, bool DMA> constexpr int lds_bytes()
 {
-    const int loop = 2 * ZT_BYTES + 2 * (W_KN ? WT_KN_BYTES : WT_NK_BYTES);
-    return loop > CS_BYTES ? loop : CS_BYTES;
+    const int loop = DMA ? DST * DSTAGE_BYTES : 2 * ZT_BYTES + 2 * (W_KN ? WT_KN_BYTES : WT_NK_BYTES);
+    const int cs = BM * (BN + 8 * WN) * 2;          // all waves' C staging
+    return loop > cs ? loop : cs;
 }
 
 __device__ __forceinline__ int swz(int row, int chunk) { return chunk ^ ((row >> 1) & 7); }
@@ -54,18 +73,55 @@ __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v)
     return c.b;
 }
 
+__device__ __forceinline__ u32x4 ldg16(const unsigned char* base, uint32_t off)
+{
+    return *reinterpret_cast<const u32x4*>(base + off);
+}
+
+// One wave-wide global -> LDS copy of 64 x 16 bytes without passing through registers
+// (global_load_lds_dwordx4): lane i fetches 16 bytes at gbase + voff and they land at LDS byte
+// address lds_addr + 16 i.  lds_addr and gbase are wave-uniform.  The instruction counts on vmcnt;
+// the compiler does not see it, so the caller places the matching s_waitcnt vmcnt itself.
+__device__ __forceinline__ void dma16(uint32_t lds_addr, const unsigned char* gbase, uint32_t voff)
+{
+    const uint32_t la = __builtin_amdgcn_readfirstlane(lds_addr);
+    const uint64_t gp = reinterpret_cast<uint64_t>(gbase);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane(uint32_t(gp));
+    const uint32_t hi = __builtin_amdgcn_readfirstlane(uint32_t(gp >> 32));
+    const uint64_t gu = (uint64_t(hi) << 32) | lo;
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :
+                 : "s"(la), "v"(voff), "s"(gu)
+                 : "memory");
+}
+
+template <int N> __device__ __forceinline__ void wait_vmcnt()
+{
+    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
+}
+
 }  // namespace
 
-template <bool W_KN>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
+template <bool W_KN, int WM, int WN, bool DMA>
+__global__ __launch_bounds__(64 * WM * WN)
 void gemm_mfma_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const uint16_t* __restrict__ W,
                       const uint16_t* __restrict__ P, const uint16_t* __restrict__ M,
                       uint16_t* __restrict__ C, int32_t K, int32_t N, int32_t ldw,
                       int32_t tiles_m, int32_t tiles_n)
 {
+    constexpr int NT = 64 * WM * WN;                // threads
+    constexpr int TM = BM / WM, TN = BN / WN;       // wave tile
+    constexpr int MB = TM / 32, NB = TN / 32;       // 32 x 32 blocks per wave
+    constexpr int ZL = 2048 / NT;                   // 16-byte chunks per thread and tile
+    constexpr int ZROWS = NT / 8;                   // rows covered by one pass of the [rows][64 k] loader
+    constexpr int WKROWS = NT / 32;                 // k rows covered by one pass of the [64 k][256 n] loader
+    constexpr int WT_BYTES = W_KN ? WT_KN_BYTES : WT_NK_BYTES;
+    constexpr int CS_PITCH = TN + 8;
+
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave / WN, wn = wave % WN;
+    const int l32 = lane & 31, lh = lane >> 5;
     const int32_t T = pd.T;
 
     // ---- workgroup -> tile: consecutive ids go to different XCDs, so give each XCD a contiguous
@@ -87,147 +143,270 @@ void gemm_mfma_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const uint16_t
     }
     const int32_t row0 = tile_m * BM, col0 = tile_n * BN;
 
-    constexpr int WT_BYTES = W_KN ? WT_KN_BYTES : WT_NK_BYTES;
     auto zs = [&](int buf) { return lds + buf * ZT_BYTES; };
     auto ws = [&](int buf) { return lds + 2 * ZT_BYTES + buf * WT_BYTES; };
 
-    f32x16 acc[4][4];
+    f32x16 acc[MB][NB];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < MB; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < NB; ++j)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    u32x4 zreg[8], wreg[8];
     const u32x4 zero4 = {0u, 0u, 0u, 0u};
-
-    auto gload = [&](int32_t k0) {
-        {   // Z tile: thread -> chunk tid % 8 of rows tid / 8 + 32 i
-            const int c = tid & 7, rb = tid >> 3;
-            const int32_t k = k0 + 8 * c;
+    if constexpr (DMA) {
+        // ---- direct-to-LDS pipeline: K tiles of DBK, DST LDS stages, loads issued DST-1 tiles ahead
+        // Stage layout: Z [256 rows][DBK k] (DBK*2 bytes per row, 16-byte chunk c stored at c ^ f(row)),
+        // then W either [256 n][DBK k] in the same layout (backward) or [DBK k][256 n] (forward, 512
+        // bytes per k row, 16-byte chunk c stored at c ^ ((k & 3) << 2) so that the 4 k rows of one
+        // transpose read sit in different bank quarters).  f spreads the 16 rows of one ds_read_b128
+        // pass over all banks: (row >> 2) & 3 for 64-byte rows, (row >> 1) & 7 for 128-byte rows.
+        // A wave-wide copy fills 1 KiB of LDS in lane order, so the swizzle is applied to the global
+        // address each lane fetches from.
+        constexpr int NW = WM * WN;
+        constexpr int CPRW = DBK / 8;               // 16-byte chunks per row of the [rows][DBK] layout
+        constexpr int RPB = 64 / CPRW;              // rows per 1 KiB block
+        constexpr int NBZ = (DBK / 2) / NW;         // 1 KiB blocks per wave, for Z and for W each
+        const uint32_t lds0 = uint32_t(uintptr_t((__attribute__((address_space(3))) unsigned char*)lds));
+        auto fz = [](int row) { return DBK == 32 ? (row >> 2) & 3 : (row >> 1) & 7; };
+        uint32_t zvo[NBZ], wvo[NBZ];
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const int32_t row = row0 + rb + 32 * i;
-                zreg[i] = (row < T && k < K)
-                              ? *reinterpret_cast<const u32x4*>(Z + size_t(row) * K + k) : zero4;
-            }
-        }
-        if (W_KN) {   // W tile [64 k][256 n]: thread -> n chunk tid % 32 of k rows tid / 32 + 8 i
-            const int nc = tid & 31, kb = tid >> 5;
-            const int32_t n = col0 + 8 * nc;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const int32_t k = k0 + kb + 8 * i;
-                wreg[i] = (k < K && n < N)
-                              ? *reinterpret_cast<const u32x4*>(W + size_t(k) * ldw + n) : zero4;
-            }
-        } else {      // W tile [256 n][64 k]
-            const int c = tid & 7, rb = tid >> 3;
-            const int32_t k = k0 + 8 * c;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const int32_t n = col0 + rb + 32 * i;
-                wreg[i] = (n < N && k < K)
-                              ? *reinterpret_cast<const u32x4*>(W + size_t(n) * ldw + k) : zero4;
-            }
-        }
-    };
-    auto lstore = [&](int buf) {
-        {
-            const int c = tid & 7, rb = tid >> 3;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const int row = rb + 32 * i;
-                *reinterpret_cast<u32x4*>(zs(buf) + row * (BK * 2) + swz(row, c) * 16) = zreg[i];
-            }
-        }
-        if (W_KN) {
-            const int nc = tid & 31, kb = tid >> 5;
-#pragma unroll
-            for (int i = 0; i < 8; ++i)
-                *reinterpret_cast<u32x4*>(ws(buf) + (kb + 8 * i) * (WKN_PITCH * 2) + nc * 16) = wreg[i];
-        } else {
-            const int c = tid & 7, rb = tid >> 3;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const int row = rb + 32 * i;
-                *reinterpret_cast<u32x4*>(ws(buf) + row * (BK * 2) + swz(row, c) * 16) = wreg[i];
-            }
-        }
-    };
-    // one K tile: 4 K steps of 16, each 4 + 4 operand fragments and 16 MFMAs
-    auto compute = [&](int buf) {
-        const int l32 = lane & 31, lh = lane >> 5;
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            bf16x8 zf[4], wf[4];
-#pragma unroll
-            for (int mb = 0; mb < 4; ++mb) {
-                const int row = wm * 128 + mb * 32 + l32;
-                zf[mb] = *reinterpret_cast<const bf16x8*>(zs(buf) + row * (BK * 2) + swz(row, 2 * ks + lh) * 16);
+        for (int j = 0; j < NBZ; ++j) {
+            const int blk = wave + NW * j;
+            {
+                const int row = RPB * blk + lane / CPRW;
+                const int c = (lane % CPRW) ^ fz(row);
+                zvo[j] = (uint32_t(min(row, T - 1 - row0)) * uint32_t(K) + 8u * c) * 2u;
+                if (!W_KN) wvo[j] = (uint32_t(min(row, N - 1 - col0)) * uint32_t(ldw) + 8u * c) * 2u;
             }
             if (W_KN) {
-                const int s = lane & 15, g = lane >> 4;
-                const int krow = 16 * ks + 8 * (g >> 1) + (s >> 2);
+                const int krow = 2 * blk + (lane >> 5);
+                const int c = (lane & 31) ^ ((krow & 3) << 2);
+                wvo[j] = (uint32_t(krow) * uint32_t(ldw) + uint32_t(min(8 * c, N - 8 - col0))) * 2u;
+            }
+        }
+        const unsigned char* zbase = reinterpret_cast<const unsigned char*>(Z + size_t(row0) * K);
+        const unsigned char* wbase = reinterpret_cast<const unsigned char*>(W_KN ? W + col0 : W + size_t(col0) * ldw);
+        auto issue = [&](int32_t kt) {              // all of this wave's copies for K tile kt
+            const uint32_t st = lds0 + uint32_t(kt % DST) * DSTAGE_BYTES;
+#if defined(LOBRA_GEMM_EXP) && LOBRA_GEMM_EXP == 6      // timing experiment: every K tile re-reads tile 0..3
+            const int32_t kq = kt & 3;
+#else
+            const int32_t kq = kt;
+#endif
+            const unsigned char* zb = zbase + size_t(kq) * (DBK * 2);
+            const unsigned char* wb = W_KN ? wbase + size_t(kq) * DBK * ldw * 2 : wbase + size_t(kq) * (DBK * 2);
 #pragma unroll
-                for (int nb = 0; nb < 4; ++nb) {
-                    const int n = wn * 128 + nb * 32 + 16 * (g & 1) + 4 * (s & 3);
-                    const unsigned char* p0 = ws(buf) + krow * (WKN_PITCH * 2) + n * 2;
-                    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                        (s16x4 __attribute__((address_space(3)))*)(p0));
-                    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                        (s16x4 __attribute__((address_space(3)))*)(p0 + 4 * (WKN_PITCH * 2)));
-                    union { s16x4 h[2]; bf16x8 b; } c;
-                    c.h[0] = lo;
-                    c.h[1] = hi;
-                    wf[nb] = c.b;
-                }
-            } else {
+            for (int j = 0; j < NBZ; ++j) dma16(st + (wave + NW * j) * 1024, zb, zvo[j]);
 #pragma unroll
-                for (int nb = 0; nb < 4; ++nb) {
-                    const int row = wn * 128 + nb * 32 + l32;
-                    wf[nb] = *reinterpret_cast<const bf16x8*>(ws(buf) + row * (BK * 2) + swz(row, 2 * ks + lh) * 16);
+            for (int j = 0; j < NBZ; ++j) dma16(st + DZT_BYTES + (wave + NW * j) * 1024, wb, wvo[j]);
+        };
+        auto compute = [&](int stage) {
+            const unsigned char* zs = lds + stage * DSTAGE_BYTES;
+            const unsigned char* ws = zs + DZT_BYTES;
+#pragma unroll
+            for (int ks = 0; ks < DBK / 16; ++ks) {
+                bf16x8 zf[MB], wf[NB];
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb) {
+                    const int row = wm * TM + mb * 32 + l32;
+                    zf[mb] = *reinterpret_cast<const bf16x8*>(zs + row * (DBK * 2) + ((2 * ks + lh) ^ fz(row)) * 16);
                 }
+                if (W_KN) {
+                    const int s = lane & 15, g = lane >> 4;
+                    const int krow = 16 * ks + 8 * (g >> 1) + (s >> 2);
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb) {
+                        const int n = wn * TN + nb * 32 + 16 * (g & 1) + 4 * (s & 3);
+                        const int c = (n >> 3) ^ ((krow & 3) << 2);
+                        const unsigned char* p0 = ws + krow * 512 + c * 16 + (n & 7) * 2;
+                        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                            (s16x4 __attribute__((address_space(3)))*)(p0));
+                        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                            (s16x4 __attribute__((address_space(3)))*)(p0 + 4 * 512));
+                        union { s16x4 h[2]; bf16x8 b; } cv;
+                        cv.h[0] = lo;
+                        cv.h[1] = hi;
+                        wf[nb] = cv.b;
+                    }
+                } else {
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb) {
+                        const int row = wn * TN + nb * 32 + l32;
+                        wf[nb] = *reinterpret_cast<const bf16x8*>(ws + row * (DBK * 2) + ((2 * ks + lh) ^ fz(row)) * 16);
+                    }
+                }
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb)
+                        acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[nb], zf[mb], acc[mb][nb], 0, 0, 0);
+            }
+        };
+        constexpr int NPW = 2 * NBZ;                // copies per wave and K tile
+        const int32_t KT = K / DBK;                 // the launcher guarantees K % DBK == 0
+        for (int32_t s0 = 0; s0 < DST - 1; ++s0)
+            if (s0 < KT) issue(s0);
+        for (int32_t kt = 0; kt < KT; ++kt) {
+            // this wave's copies of tile kt have landed once at most the copies of the (up to DST-2)
+            // tiles issued after it are still outstanding; the barrier then covers the other waves'
+            // copies and tells that everybody is done reading the stage that is refilled next
+#if !defined(LOBRA_GEMM_EXP) || LOBRA_GEMM_EXP < 3     // EXP >= 3: timing experiments only, wrong results
+            if (DST >= 4 && kt + 2 < KT) wait_vmcnt<(DST >= 4 ? 2 : 0) * NPW>();
+            else if (DST >= 3 && kt + 1 < KT) wait_vmcnt<(DST >= 3 ? 1 : 0) * NPW>();
+            else wait_vmcnt<0>();
+#endif
+#if !defined(LOBRA_GEMM_EXP) || LOBRA_GEMM_EXP != 5
+            __builtin_amdgcn_s_barrier();
+#endif
+#if !defined(LOBRA_GEMM_EXP) || LOBRA_GEMM_EXP < 4
+            if (kt + DST - 1 < KT) issue(kt + DST - 1);
+#endif
+            compute(kt % DST);
+        }
+        wait_vmcnt<0>();
+        __syncthreads();
+    } else {
+        u32x4 zreg[ZL], wreg[ZL];
+
+        // Per-thread byte offsets inside the tile's rows (loop invariant).  Rows of Z beyond T and columns
+        // of W beyond N are clamped to the last valid one: they only feed output rows / columns that are
+        // never stored.  The K tail (K % 64) is zero-filled by the guarded loader below.
+        const int lc = tid & 7, lr = tid >> 3;          // [rows][64 k] loader: chunk, first row
+        const int wnc = tid & 31, wkr = tid >> 5;       // [64 k][256 n] loader: n chunk, first k row
+        uint32_t zoff[ZL], woff[ZL];
+#pragma unroll
+        for (int i = 0; i < ZL; ++i) {
+            zoff[i] = (uint32_t(min(lr + ZROWS * i, T - 1 - row0)) * uint32_t(K) + 8u * lc) * 2u;
+            if (W_KN)
+                woff[i] = (uint32_t(wkr + WKROWS * i) * uint32_t(ldw) + uint32_t(min(8 * wnc, N - 8 - col0))) * 2u;
+            else
+                woff[i] = (uint32_t(min(lr + ZROWS * i, N - 1 - col0)) * uint32_t(ldw) + 8u * lc) * 2u;
+        }
+        const unsigned char* zbase = reinterpret_cast<const unsigned char*>(Z + size_t(row0) * K);
+        const unsigned char* wbase = reinterpret_cast<const unsigned char*>(W_KN ? W + col0 : W + size_t(col0) * ldw);
+
+        auto gload = [&](int32_t k0) {                  // full K tile, no guards
+            const unsigned char* zb = zbase + size_t(k0) * 2;
+            const unsigned char* wb = W_KN ? wbase + size_t(k0) * ldw * 2 : wbase + size_t(k0) * 2;
+#pragma unroll
+            for (int i = 0; i < ZL; ++i) zreg[i] = ldg16(zb, zoff[i]);
+#pragma unroll
+            for (int i = 0; i < ZL; ++i) wreg[i] = ldg16(wb, woff[i]);
+        };
+        auto gload_tail = [&](int32_t k0) {             // last, partial K tile: zero beyond K
+            const unsigned char* zb = zbase + size_t(k0) * 2;
+            const unsigned char* wb = W_KN ? wbase + size_t(k0) * ldw * 2 : wbase + size_t(k0) * 2;
+#pragma unroll
+            for (int i = 0; i < ZL; ++i) zreg[i] = (k0 + 8 * lc < K) ? ldg16(zb, zoff[i]) : zero4;
+#pragma unroll
+            for (int i = 0; i < ZL; ++i) {
+                const bool in = W_KN ? (k0 + wkr + WKROWS * i < K) : (k0 + 8 * lc < K);
+                wreg[i] = in ? ldg16(wb, woff[i]) : zero4;
+            }
+        };
+        auto lstore = [&](int buf) {
+#pragma unroll
+            for (int i = 0; i < ZL; ++i) {
+                const int row = lr + ZROWS * i;
+                *reinterpret_cast<u32x4*>(zs(buf) + row * (BK * 2) + swz(row, lc) * 16) = zreg[i];
             }
 #pragma unroll
-            for (int mb = 0; mb < 4; ++mb)
+            for (int i = 0; i < ZL; ++i) {
+                if (W_KN) {
+                    *reinterpret_cast<u32x4*>(ws(buf) + (wkr + WKROWS * i) * (WKN_PITCH * 2) + wnc * 16) = wreg[i];
+                } else {
+                    const int row = lr + ZROWS * i;
+                    *reinterpret_cast<u32x4*>(ws(buf) + row * (BK * 2) + swz(row, lc) * 16) = wreg[i];
+                }
+            }
+        };
+        // one K tile: 4 K steps of 16, each MB + NB operand fragments and MB * NB MFMAs
+        auto compute = [&](int buf) {
 #pragma unroll
-                for (int nb = 0; nb < 4; ++nb)
-                    acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[nb], zf[mb], acc[mb][nb], 0, 0, 0);
-        }
-    };
+            for (int ks = 0; ks < 4; ++ks) {
+                bf16x8 zf[MB], wf[NB];
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb) {
+                    const int row = wm * TM + mb * 32 + l32;
+                    zf[mb] = *reinterpret_cast<const bf16x8*>(zs(buf) + row * (BK * 2) + swz(row, 2 * ks + lh) * 16);
+                }
+                if (W_KN) {
+                    const int s = lane & 15, g = lane >> 4;
+                    const int krow = 16 * ks + 8 * (g >> 1) + (s >> 2);
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb) {
+                        const int n = wn * TN + nb * 32 + 16 * (g & 1) + 4 * (s & 3);
+                        const unsigned char* p0 = ws(buf) + krow * (WKN_PITCH * 2) + n * 2;
+                        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                            (s16x4 __attribute__((address_space(3)))*)(p0));
+                        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                            (s16x4 __attribute__((address_space(3)))*)(p0 + 4 * (WKN_PITCH * 2)));
+                        union { s16x4 h[2]; bf16x8 b; } c;
+                        c.h[0] = lo;
+                        c.h[1] = hi;
+                        wf[nb] = c.b;
+                    }
+                } else {
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb) {
+                        const int row = wn * TN + nb * 32 + l32;
+                        wf[nb] = *reinterpret_cast<const bf16x8*>(ws(buf) + row * (BK * 2) + swz(row, 2 * ks + lh) * 16);
+                    }
+                }
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb)
+                        acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[nb], zf[mb], acc[mb][nb], 0, 0, 0);
+            }
+        };
 
-    // ---- main loop ----------------------------------------------------------------------------
-    const int32_t KT = (K + BK - 1) / BK;
-    gload(0);
-    lstore(0);
-    __syncthreads();
-    for (int32_t kt = 0; kt < KT; ++kt) {
-        const int buf = kt & 1;
-        if (kt + 1 < KT) gload((kt + 1) * BK);
-        compute(buf);
-        if (kt + 1 < KT) lstore(buf ^ 1);
+        // ---- main loop ----------------------------------------------------------------------------
+        const int32_t KT = (K + BK - 1) / BK;           // K tiles
+        const int32_t KF = K / BK;                      // full K tiles
+        if (KF > 0) gload(0); else gload_tail(0);
+        lstore(0);
         __syncthreads();
+#if defined(LOBRA_GEMM_EXP) && LOBRA_GEMM_EXP >= 1   // timing experiments only: wrong results
+        for (int32_t kt = 0; kt < KT; ++kt) {
+            const int buf = kt & 1;
+            compute(buf);
+#if LOBRA_GEMM_EXP == 1
+            if (kt + 1 < KT) lstore(buf ^ 1);
+            __syncthreads();
+#endif
+        }
+#else
+        for (int32_t kt = 0; kt < KT; ++kt) {
+            const int buf = kt & 1;
+            if (kt + 1 < KF) gload((kt + 1) * BK);
+            else if (kt + 1 < KT) gload_tail((kt + 1) * BK);
+            compute(buf);
+            if (kt + 1 < KT) lstore(buf ^ 1);
+            __syncthreads();
+        }
+#endif
+
     }
 
     // ---- fused up projection: one extra K step of 16 ranks per (segment in this tile, rank block)
     {
-        const int l32 = lane & 31, lh = lane >> 5;
         const int32_t row_end = min(row0 + BM, T);
+        const int32_t wrow0 = row0 + wm * TM;       // the wave's rows are wrow0 .. wrow0 + TM - 1
         int32_t sg = pd.rowblk_seg[row0 / kRowBlock];
         for (; sg < pd.nseg && pd.cseg_off[sg] < row_end; ++sg) {
             const int32_t t = pd.cseg_task[sg];
             if (t < 0) continue;
             const int32_t lo = max(pd.cseg_off[sg], row0), hi = min(pd.cseg_off[sg + 1], row_end);
             const int32_t r0 = pd.rank_off[t], r = pd.rank_off[t + 1] - r0;
-            // the wave's rows are row0 + wm*128 .. +127
-            if (hi <= row0 + wm * 128 || lo >= row0 + wm * 128 + 128) continue;
+            if (hi <= wrow0 || lo >= wrow0 + TM) continue;
             for (int32_t kk = 0; kk < r; kk += 16) {
-                bf16x8 wf[4];
+                bf16x8 wf[NB];
 #pragma unroll
-                for (int nb = 0; nb < 4; ++nb) {
-                    const int32_t n = col0 + wn * 128 + nb * 32 + l32;
+                for (int nb = 0; nb < NB; ++nb) {
+                    const int32_t n = col0 + wn * TN + nb * 32 + l32;
                     union { uint16_t h[8]; bf16x8 b; } c;
 #pragma unroll
                     for (int q = 0; q < 8; ++q) {
@@ -237,29 +416,28 @@ void gemm_mfma_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const uint16_t
                     wf[nb] = c.b;
                 }
 #pragma unroll
-                for (int mb = 0; mb < 4; ++mb) {
-                    const int32_t rb = row0 + wm * 128 + mb * 32;
+                for (int mb = 0; mb < MB; ++mb) {
+                    const int32_t rb = wrow0 + mb * 32;
                     if (hi <= rb || lo >= rb + 32) continue;        // wave-uniform
                     const int32_t row = rb + l32;
                     const u32x4 pv = (row >= lo && row < hi)
                         ? *reinterpret_cast<const u32x4*>(P + size_t(row) * pd.r_pad + kk + 8 * lh) : zero4;
                     const bf16x8 pf = as_bf16x8(pv);
 #pragma unroll
-                    for (int nb = 0; nb < 4; ++nb)
+                    for (int nb = 0; nb < NB; ++nb)
                         acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[nb], pf, acc[mb][nb], 0, 0, 0);
                 }
             }
         }
     }
 
-    // ---- epilogue: fp32 -> bf16, stage the wave's 128 x 128 block in LDS, store 16 bytes per lane
+    // ---- epilogue: fp32 -> bf16, stage the wave's block in LDS, store 16 bytes per lane
     {
-        unsigned char* cs = lds + wave * (128 * CS_PITCH * 2);
-        const int l32 = lane & 31, lh = lane >> 5;
+        unsigned char* cs = lds + wave * (TM * CS_PITCH * 2);
 #pragma unroll
-        for (int mb = 0; mb < 4; ++mb)
+        for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-            for (int nb = 0; nb < 4; ++nb)
+            for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
                     bf16x4 o;
@@ -269,16 +447,37 @@ void gemm_mfma_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const uint16_t
                     *reinterpret_cast<bf16x4*>(cs + (m * CS_PITCH + n) * 2) = o;
                 }
         __syncthreads();
-        const int cchunk = lane & 15, rsub = lane >> 4;
-        const int32_t col = col0 + wn * 128 + cchunk * 8;
+        constexpr int CPR = TN / 8;                  // 16-byte chunks per row of the wave tile
+        constexpr int RPI = 64 / CPR;                // rows per store instruction
+        const int cchunk = lane % CPR, rsub = lane / CPR;
+        const int32_t col = col0 + wn * TN + cchunk * 8;
 #pragma unroll 4
-        for (int i = 0; i < 32; ++i) {
-            const int m = i * 4 + rsub;
-            const int32_t row = row0 + wm * 128 + m;
+        for (int i = 0; i < TM / RPI; ++i) {
+            const int m = i * RPI + rsub;
+            const int32_t row = row0 + wm * TM + m;
             const u32x4 v = *reinterpret_cast<const u32x4*>(cs + (m * CS_PITCH + cchunk * 8) * 2);
             if (row < T && col < N) *reinterpret_cast<u32x4*>(C + size_t(row) * N + col) = v;
         }
     }
+}
+
+template <bool W_KN, int WM, int WN, bool DMA>
+static hipError_t launch_gemm(const PlanDev& pd, const void* Z, const void* W, const void* P,
+                              const void* M, void* C, int32_t K, int32_t N, int32_t ldw,
+                              int32_t tiles_m, int32_t tiles_n, hipStream_t st)
+{
+    constexpr int bytes = lds_bytes<W_KN, WN, DMA>();
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mfma_kernel<W_KN, WM, WN, DMA>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    gemm_mfma_kernel<W_KN, WM, WN, DMA><<<dim3(uint32_t(tiles_m) * uint32_t(tiles_n)), 64 * WM * WN, bytes, st>>>(
+        pd, (const uint16_t*)Z, (const uint16_t*)W, (const uint16_t*)P, (const uint16_t*)M, (uint16_t*)C,
+        K, N, ldw, tiles_m, tiles_n);
+    return hipGetLastError();
 }
 
 hipError_t gemm_mfma(const PlanDev& pd, bool transW, const void* Z, const void* W, const void* P,
@@ -286,34 +485,19 @@ hipError_t gemm_mfma(const PlanDev& pd, bool transW, const void* Z, const void* 
 {
     if (pd.T == 0) return hipSuccess;
     const int32_t tiles_m = (pd.T + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
-    const int64_t ntiles = int64_t(tiles_m) * tiles_n;
-    if (ntiles > 0x7fffffff) return hipErrorInvalidValue;
-    static bool attr_set[2] = {false, false};
-    hipError_t e;
+    if (int64_t(tiles_m) * tiles_n > 0x7fffffff) return hipErrorInvalidValue;
+    // 32-bit byte offsets inside a tile: 256 rows of K (or ldw) elements, 64 rows of ldw elements
+    if (int64_t(K) * 512 >= (int64_t(1) << 32) || int64_t(ldw) * 512 >= (int64_t(1) << 32))
+        return hipErrorInvalidValue;
+    if (N < 8 || K < 8) return hipErrorInvalidValue;
+    // the direct-to-LDS pipeline needs whole K tiles of 32; other K take the register-staged kernel
+    const bool dma = LOBRA_GEMM_DMA && K % DBK == 0;
     if (!transW) {
-        constexpr int bytes = lds_bytes<true>();
-        if (!attr_set[0]) {
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mfma_kernel<true>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
-            if (e != hipSuccess) return e;
-            attr_set[0] = true;
-        }
-        gemm_mfma_kernel<true><<<dim3(uint32_t(ntiles)), 256, bytes, st>>>(
-            pd, (const uint16_t*)Z, (const uint16_t*)W, (const uint16_t*)P, (const uint16_t*)M,
-            (uint16_t*)C, K, N, ldw, tiles_m, tiles_n);
-    } else {
-        constexpr int bytes = lds_bytes<false>();
-        if (!attr_set[1]) {
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mfma_kernel<false>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
-            if (e != hipSuccess) return e;
-            attr_set[1] = true;
-        }
-        gemm_mfma_kernel<false><<<dim3(uint32_t(ntiles)), 256, bytes, st>>>(
-            pd, (const uint16_t*)Z, (const uint16_t*)W, (const uint16_t*)P, (const uint16_t*)M,
-            (uint16_t*)C, K, N, ldw, tiles_m, tiles_n);
+        if (dma) return launch_gemm<true, LOBRA_GEMM_WM, LOBRA_GEMM_WN, true>(pd, Z, W, P, M, C, K, N, ldw, tiles_m, tiles_n, st);
+        return launch_gemm<true, LOBRA_GEMM_WM, LOBRA_GEMM_WN, false>(pd, Z, W, P, M, C, K, N, ldw, tiles_m, tiles_n, st);
     }
-    return hipGetLastError();
+    if (dma) return launch_gemm<false, LOBRA_GEMM_WM, LOBRA_GEMM_WN, true>(pd, Z, W, P, M, C, K, N, ldw, tiles_m, tiles_n, st);
+    return launch_gemm<false, LOBRA_GEMM_WM, LOBRA_GEMM_WN, false>(pd, Z, W, P, M, C, K, N, ldw, tiles_m, tiles_n, st);
 }
 
 }  // namespace lobra

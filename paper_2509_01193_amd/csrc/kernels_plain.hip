@@ -181,7 +181,8 @@ __global__ __launch_bounds__(256) void plain_gradreduce_kernel(PlanDev pd, const
     }
 }
 
-// stage 2: out[R, col] (+)= sum over the chunks of task(R), in chunk order
+// stage 2: out[R, col] (+)= sum over the chunks of task(R), in chunk order.  One workgroup per
+// (rank row, 1024 columns), one float4 per thread, four chunk loads in flight.
 __global__ __launch_bounds__(256) void reduce_partials_kernel(PlanDev pd, const float* __restrict__ part,
                                                               float* __restrict__ out, int32_t D,
                                                               int accumulate)
@@ -191,11 +192,37 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(PlanDev pd, const 
     while (pd.rank_off[t + 1] <= R) ++t;
     const int32_t p = R - pd.rank_off[t];
     const int32_t c0 = pd.task_chunk_off[t], c1 = pd.task_chunk_off[t + 1];
-    for (int32_t col = blockIdx.y * 1024 + threadIdx.x; col < min(D, (int32_t)(blockIdx.y + 1) * 1024); col += 256) {
-        float acc = 0.f;
-        for (int32_t c = c0; c < c1; ++c) acc += part[size_t(pd.chunks[c].part_row0 + p) * D + col];
-        const size_t o = size_t(R) * D + col;
-        out[o] = accumulate ? out[o] + acc : acc;
+    const int32_t col = blockIdx.y * 1024 + threadIdx.x * 4;
+    if (col >= D) return;
+    const int nv = min(4, D - col);                 // D need not be a multiple of 4 on the fp32 path
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    auto row_ptr = [&](int32_t c) { return part + size_t(pd.chunks[c].part_row0 + p) * D + col; };
+    if (nv == 4 && (D & 3) == 0) {
+        typedef float f4 __attribute__((ext_vector_type(4)));
+        int32_t c = c0;
+        for (; c + 4 <= c1; c += 4) {
+            const f4 v0 = *reinterpret_cast<const f4*>(row_ptr(c));
+            const f4 v1 = *reinterpret_cast<const f4*>(row_ptr(c + 1));
+            const f4 v2 = *reinterpret_cast<const f4*>(row_ptr(c + 2));
+            const f4 v3 = *reinterpret_cast<const f4*>(row_ptr(c + 3));
+#pragma unroll
+            for (int q = 0; q < 4; ++q) acc[q] = (((acc[q] + v0[q]) + v1[q]) + v2[q]) + v3[q];
+        }
+        for (; c < c1; ++c) {
+            const f4 v = *reinterpret_cast<const f4*>(row_ptr(c));
+#pragma unroll
+            for (int q = 0; q < 4; ++q) acc[q] += v[q];
+        }
+        float* o = out + size_t(R) * D + col;
+        f4 res;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) res[q] = accumulate ? o[q] + acc[q] : acc[q];
+        *reinterpret_cast<f4*>(o) = res;
+    } else {
+        for (int32_t c = c0; c < c1; ++c)
+            for (int q = 0; q < nv; ++q) acc[q] += row_ptr(c)[q];
+        float* o = out + size_t(R) * D + col;
+        for (int q = 0; q < nv; ++q) o[q] = accumulate ? o[q] + acc[q] : acc[q];
     }
 }
 

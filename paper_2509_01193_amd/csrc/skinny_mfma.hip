@@ -28,20 +28,22 @@ __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v)
 // shrink: one workgroup per token block (<= 32 tokens of one task), 4 waves split K.
 // v_mfma_f32_16x16x32_bf16 with the MFMA "A" operand = 16 rank rows of M_t and the "B" operand =
 // 16 token rows of Z, so a lane ends up with 4 consecutive ranks of one token.  K is walked in
-// slabs of 128: lane (row, kg) loads the 32 consecutive elements slab + 32 kg .. + 31 of its row as
-// four 16-byte pieces, and piece q of every lane forms MFMA q.  Any assignment of k values to MFMA
-// slots is valid as long as both operands use the same one; this one makes the four lanes of a
-// row read 256 contiguous bytes.
+// slabs of 128 = 4 MFMA steps of 32: in step q lane (row, kg) loads the 8 elements
+// slab + 32 q + 8 kg .. + 7 of its row, so the four lanes of a row read one 64-byte sector per
+// load instruction and a whole 256-byte run per slab.
 // -------------------------------------------------------------------------------------------------
-template <int NRB>   // rank blocks of 16 handled (r_t <= 16 NRB)
-__global__ __launch_bounds__(256) void shrink_mfma_kernel(PlanDev pd, const uint16_t* __restrict__ Z,
+#ifndef LOBRA_SHRINK_WAVES
+#define LOBRA_SHRINK_WAVES 4
+#endif
+template <int NRB, int NWV>   // rank blocks of 16 handled (r_t <= 16 NRB); waves that split K
+__global__ __launch_bounds__(64 * NWV) void shrink_mfma_kernel(PlanDev pd, const uint16_t* __restrict__ Z,
                                                           const uint16_t* __restrict__ M,
                                                           const float* __restrict__ s,
                                                           uint16_t* __restrict__ P_tok,
                                                           uint16_t* __restrict__ P_blk, int32_t D,
                                                           int32_t tb_begin)
 {
-    __shared__ float red[4][2][NRB][64][4];   // [wave][token half][rank block][lane][4]
+    __shared__ float red[NWV][2][NRB][64][4];   // [wave][token half][rank block][lane][4]
     const int32_t bi = tb_begin + blockIdx.x;
     const TokenBlock b = pd.tb[bi];
     const int32_t r = pd.rank_off[b.task + 1] - b.rank_row0;
@@ -62,30 +64,51 @@ __global__ __launch_bounds__(256) void shrink_mfma_kernel(PlanDev pd, const uint
         zrow[h] = Z + size_t(b.row0 + min(16 * h + j, b.nrows - 1)) * D;
     const bool two_halves = b.nrows > 16;
 
-    for (int32_t slab = wave * 128; slab < D; slab += 512) {
-        const int32_t k = slab + 32 * kg;
-        u32x4 zv[2][4], mv[NRB][4];
+    // operands of one slab: 4 steps x (2 token halves of Z, NRB rank blocks of M)
+    struct Slab { u32x4 zv[2][4], mv[NRB][4]; };
+    auto load = [&](Slab& sl, int32_t slab) {
+        const int32_t k = slab + 8 * kg;
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            const bool kin = k + 8 * q < D;
+            const bool kin = k + 32 * q < D;
 #pragma unroll
             for (int h = 0; h < 2; ++h)
-                zv[h][q] = (kin && (h == 0 || two_halves))
-                               ? *reinterpret_cast<const u32x4*>(zrow[h] + k + 8 * q) : zero4;
+                sl.zv[h][q] = (kin && (h == 0 || two_halves))
+                                  ? *reinterpret_cast<const u32x4*>(zrow[h] + k + 32 * q) : zero4;
 #pragma unroll
             for (int rb = 0; rb < NRB; ++rb)
-                mv[rb][q] = (kin && 16 * rb + j < r)
-                                ? *reinterpret_cast<const u32x4*>(M + size_t(b.rank_row0 + 16 * rb + j) * D + k + 8 * q)
-                                : zero4;
+                sl.mv[rb][q] = (kin && 16 * rb + j < r)
+                                   ? *reinterpret_cast<const u32x4*>(M + size_t(b.rank_row0 + 16 * rb + j) * D + k + 32 * q)
+                                   : zero4;
         }
+    };
+    auto mac = [&](const Slab& sl) {
 #pragma unroll
         for (int q = 0; q < 4; ++q)
 #pragma unroll
             for (int h = 0; h < 2; ++h)
 #pragma unroll
                 for (int rb = 0; rb < NRB; ++rb)
-                    acc[h][rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(mv[rb][q]), as_bf16x8(zv[h][q]),
+                    acc[h][rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(sl.mv[rb][q]), as_bf16x8(sl.zv[h][q]),
                                                                          acc[h][rb], 0, 0, 0);
+    };
+    if constexpr (NRB <= 2) {
+        // two slabs in flight per wave: the loads of the next slab are issued before the MFMAs of this one
+        Slab cur, nxt;
+        int32_t slab = wave * 128;
+        if (slab < D) load(cur, slab);
+        for (; slab < D; slab += 128 * NWV) {
+            const bool more = slab + 128 * NWV < D;
+            if (more) load(nxt, slab + 128 * NWV);
+            mac(cur);
+            if (more) cur = nxt;
+        }
+    } else {
+        for (int32_t slab = wave * 128; slab < D; slab += 128 * NWV) {
+            Slab cur;
+            load(cur, slab);
+            mac(cur);
+        }
     }
     // cross-wave sum through LDS, then lane (token j, rank group kg) of wave 0/1 stores half h
 #pragma unroll
@@ -104,8 +127,9 @@ __global__ __launch_bounds__(256) void shrink_mfma_kernel(PlanDev pd, const uint
             bf16x4 o;
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                const float sum = (red[0][h][rb][lane][v] + red[1][h][rb][lane][v]) +
-                                  (red[2][h][rb][lane][v] + red[3][h][rb][lane][v]);
+                float sum = 0.f;
+#pragma unroll
+                for (int w = 0; w < NWV; ++w) sum += red[w][h][rb][lane][v];   // fixed order
                 const int32_t p = 16 * rb + 4 * kg + v;
                 o[v] = (__bf16)((p < r && tok < b.nrows) ? st * sum : 0.f);
             }
@@ -130,13 +154,13 @@ hipError_t shrink_mfma(const PlanDev& pd, const void* Z, const void* M, const fl
 {
     if (pd.ntb == 0) return hipSuccess;
     const int nrb = pd.r_pad / 16;
-#define LOBRA_SHRINK(NRB)                                                                              \
-    shrink_mfma_kernel<NRB><<<pd.ntb, 256, 0, st>>>(pd, (const uint16_t*)Z, (const uint16_t*)M, s,     \
-                                                    (uint16_t*)P_tok, (uint16_t*)P_blk, D, 0)
-    if (nrb <= 1) LOBRA_SHRINK(1);
-    else if (nrb <= 2) LOBRA_SHRINK(2);
-    else if (nrb <= 4) LOBRA_SHRINK(4);
-    else LOBRA_SHRINK(8);
+#define LOBRA_SHRINK(NRB, NWV)                                                                         \
+    shrink_mfma_kernel<NRB, NWV><<<pd.ntb, 64 * NWV, 0, st>>>(pd, (const uint16_t*)Z, (const uint16_t*)M, \
+                                                              s, (uint16_t*)P_tok, (uint16_t*)P_blk, D, 0)
+    if (nrb <= 1) LOBRA_SHRINK(1, LOBRA_SHRINK_WAVES);
+    else if (nrb <= 2) LOBRA_SHRINK(2, LOBRA_SHRINK_WAVES);
+    else if (nrb <= 4) LOBRA_SHRINK(4, 4);
+    else LOBRA_SHRINK(8, 4);
 #undef LOBRA_SHRINK
     return hipGetLastError();
 }

@@ -98,6 +98,18 @@ def test_token_structure_of_each_workload_on_a_narrow_layer(cfg, order):
     check_problem(p, label=order)
 
 
+# layer widths that are multiples of 64 take the direct-to-LDS GEMM pipeline (the widths above take
+# the register-staged one); N = 448 / 576 leaves a ragged last column tile, T a ragged last row tile
+SHRUNK_64 = {2: (320, 448), 3: (192, 576), 4: (128, 320), 5: (448, 320)}
+
+
+@pytest.mark.parametrize("cfg", [2, 3, 4, 5])
+def test_token_structure_on_a_narrow_layer_whole_k_tiles(cfg):
+    d_in, d_out = SHRUNK_64[cfg]
+    p = wl.make_config(cfg, "shuffled", d_in=d_in, d_out=d_out)
+    check_problem(p, label="k64")
+
+
 def test_config3_reversed_rank_pairing():
     p = wl.make_config(3, "shuffled", d_in=192, d_out=344, reverse_ranks=True)
     check_problem(p)
@@ -213,6 +225,23 @@ def test_empty_batch_and_argument_errors():
                                   dp.B.data_ptr(), dp.s.data_ptr(), dp.y.data_ptr(), None,
                                   dp.ws.data_ptr(), dp.ws.numel(), None)
     assert st == -8
+
+
+def test_mfma_kernels_against_plain_kernels_every_element_full_size():
+    """Workload 2 at full size: the MFMA path against the plain fp32-FMA kernels on the same bf16
+    storage, all elements (the oracle covers sampled rows of this size in the test below)."""
+    import torch
+    p = wl.make_config(2, "shuffled")
+    a = bd.DeviceProblem(p)
+    a.step()
+    b = bd.DeviceProblem(p, bd.PLAN_PLAIN_KERNELS)
+    b.step()
+    torch.cuda.synchronize()
+    for name in ("y", "dx", "dA", "dB"):
+        x, y = getattr(a, name).float(), getattr(b, name).float()
+        err = ((x - y).abs().max() / y.abs().max()).item()
+        print("mfma vs plain %s: %.2e" % (name, err), flush=True)
+        assert err <= 1e-2, (name, err)
 
 
 # ---------------------------------------------------------------------------------------------
