@@ -29,6 +29,12 @@
 #ifndef LOBRA_GEMM_DST
 #define LOBRA_GEMM_DST 2
 #endif
+#ifndef LOBRA_GEMM_GM
+#define LOBRA_GEMM_GM 8
+#endif
+#ifndef LOBRA_GEMM_NT_STORE
+#define LOBRA_GEMM_NT_STORE 1
+#endif
 #ifndef LOBRA_GEMM_WM
 #define LOBRA_GEMM_WM 2
 #endif
@@ -133,7 +139,7 @@ void gemm_mfma_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const uint16_t
         const int32_t xcd = wg & 7, idx = wg >> 3;
         const int32_t per = ntiles >> 3, rem = ntiles & 7;
         const int32_t id = xcd * per + (xcd < rem ? xcd : rem) + idx;   // XCD x holds per + (x < rem)
-        constexpr int GM = 8;
+        constexpr int GM = LOBRA_GEMM_GM;
         const int32_t group = id / (GM * tiles_n);
         const int32_t first_m = group * GM;
         const int32_t gsz = min(tiles_m - first_m, GM);
@@ -456,7 +462,10 @@ void gemm_mfma_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const uint16_t
             const int m = i * RPI + rsub;
             const int32_t row = row0 + wm * TM + m;
             const u32x4 v = *reinterpret_cast<const u32x4*>(cs + (m * CS_PITCH + cchunk * 8) * 2);
-            if (row < T && col < N) *reinterpret_cast<u32x4*>(C + size_t(row) * N + col) = v;
+            if (row < T && col < N) {
+                if (LOBRA_GEMM_NT_STORE) __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(C + size_t(row) * N + col));
+                else *reinterpret_cast<u32x4*>(C + size_t(row) * N + col) = v;
+            }
         }
     }
 }
