@@ -110,6 +110,18 @@ def test_token_structure_on_a_narrow_layer_whole_k_tiles(cfg):
     check_problem(p, label="k64")
 
 
+@pytest.mark.parametrize("dims", [(8, 8), (16, 24), (64, 64), (72, 8), (8, 1032), (1024, 64), (2048, 256)])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_extreme_layer_widths(dims, dtype):
+    """Smallest legal widths, one K tile, K tails of 8, a single column chunk, long K."""
+    d_in, d_out = dims
+    lens = [3, 40, 0, 259, 1, 64, 130]
+    p = wl.make_custom("widths", dtype, d_in, d_out, [1, 16, 128, 7],
+                       np.concatenate([[0], np.cumsum(lens)]), [0, 1, 2, 2, -1, 3, 1], 7,
+                       s=[2.0, 1.0, 0.25, -3.0], std_x=0.5, std_w=0.1, std_a=0.1, std_b=0.1)
+    check_problem(p, label="%s %dx%d" % (dtype, d_in, d_out))
+
+
 def test_config3_reversed_rank_pairing():
     p = wl.make_config(3, "shuffled", d_in=192, d_out=344, reverse_ranks=True)
     check_problem(p)
