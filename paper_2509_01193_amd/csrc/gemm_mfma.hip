@@ -397,8 +397,13 @@ void gemm_mfma_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const uint16_t
 
     }
 
-    // ---- fused up projection: one extra K step of 16 ranks per (segment in this tile, rank block)
+    // ---- fused up projection: for every adapter segment that crosses this tile, ceil(r_t / 16) extra
+    //      K steps acc += M_t^T[:, cols] * P[rows, :]^T with the rows outside the segment masked to zero.
+    //      The M_t slice [r_t][256 cols] is staged in LDS (free now) in the [k][n] layout of the forward W
+    //      tile and gathered with the transpose read; P comes straight from global memory, 16 bytes per lane.
+    //      The segment loop and its barriers are uniform over the workgroup.
     {
+        constexpr int NT2 = 64 * WM * WN;
         const int32_t row_end = min(row0 + BM, T);
         const int32_t wrow0 = row0 + wm * TM;       // the wave's rows are wrow0 .. wrow0 + TM - 1
         int32_t sg = pd.rowblk_seg[row0 / kRowBlock];
@@ -407,34 +412,53 @@ void gemm_mfma_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const uint16_t
             if (t < 0) continue;
             const int32_t lo = max(pd.cseg_off[sg], row0), hi = min(pd.cseg_off[sg + 1], row_end);
             const int32_t r0 = pd.rank_off[t], r = pd.rank_off[t + 1] - r0;
-            if (hi <= wrow0 || lo >= wrow0 + TM) continue;
-            for (int32_t kk = 0; kk < r; kk += 16) {
+            const int32_t rp = (r + 15) & ~15;
+            __syncthreads();                        // everybody is done with what the LDS held before
+            for (int32_t ch = tid; ch < rp * 32; ch += NT2) {
+                const int32_t kr = ch >> 5, c = ch & 31;
+                const int32_t n = col0 + 8 * c;
+                const u32x4 v = (kr < r && n < N) ? *reinterpret_cast<const u32x4*>(M + size_t(r0 + kr) * N + n) : zero4;
+                *reinterpret_cast<u32x4*>(lds + kr * 512 + ((c ^ ((kr & 3) << 2)) << 4)) = v;
+            }
+            __syncthreads();
+            if (hi <= wrow0 || lo >= wrow0 + TM) continue;     // wave-uniform; the barriers are above
+            const int s16 = lane & 15, g16 = lane >> 4;
+            for (int32_t kk = 0; kk < rp; kk += 16) {
+                u32x4 pv[MB];
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb) {
+                    const int32_t row = wrow0 + mb * 32 + l32;
+                    pv[mb] = (row >= lo && row < hi)
+                        ? *reinterpret_cast<const u32x4*>(P + size_t(row) * pd.r_pad + kk + 8 * lh) : zero4;
+                }
                 bf16x8 wf[NB];
+                const int krow = kk + 8 * (g16 >> 1) + (s16 >> 2);
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb) {
-                    const int32_t n = col0 + wn * TN + nb * 32 + l32;
-                    union { uint16_t h[8]; bf16x8 b; } c;
-#pragma unroll
-                    for (int q = 0; q < 8; ++q) {
-                        const int32_t p = kk + 8 * lh + q;
-                        c.h[q] = (p < r && n < N) ? M[size_t(r0 + p) * N + n] : uint16_t(0);
-                    }
-                    wf[nb] = c.b;
+                    const int n = wn * TN + nb * 32 + 16 * (g16 & 1) + 4 * (s16 & 3);
+                    const int c = (n >> 3) ^ ((krow & 3) << 2);
+                    const unsigned char* p0 = lds + krow * 512 + c * 16 + (n & 7) * 2;
+                    const s16x4 vlo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                        (s16x4 __attribute__((address_space(3)))*)(p0));
+                    const s16x4 vhi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                        (s16x4 __attribute__((address_space(3)))*)(p0 + 4 * 512));
+                    union { s16x4 h[2]; bf16x8 b; } cv;
+                    cv.h[0] = vlo;
+                    cv.h[1] = vhi;
+                    wf[nb] = cv.b;
                 }
 #pragma unroll
                 for (int mb = 0; mb < MB; ++mb) {
                     const int32_t rb = wrow0 + mb * 32;
                     if (hi <= rb || lo >= rb + 32) continue;        // wave-uniform
-                    const int32_t row = rb + l32;
-                    const u32x4 pv = (row >= lo && row < hi)
-                        ? *reinterpret_cast<const u32x4*>(P + size_t(row) * pd.r_pad + kk + 8 * lh) : zero4;
-                    const bf16x8 pf = as_bf16x8(pv);
+                    const bf16x8 pf = as_bf16x8(pv[mb]);
 #pragma unroll
                     for (int nb = 0; nb < NB; ++nb)
                         acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[nb], pf, acc[mb][nb], 0, 0, 0);
                 }
             }
         }
+        __syncthreads();                            // the C staging below reuses the same LDS
     }
 
     // ---- epilogue: fp32 -> bf16, stage the wave's block in LDS, store 16 bytes per lane
