@@ -143,13 +143,11 @@ def main():
                 "mfma_only_sustained_tflops": MFMA_ONLY_SUSTAINED_TFLOPS if p.dtype == "bf16" else None}
     esz = 2 if p.dtype == "bf16" else 4
     skinny = {}
-    if "shrink" in kern:   # x once (fwd) and dy once (bwd): mean bytes per launch
-        b = 0.5 * esz * p.T * (p.d_in + p.d_out)
-        skinny["shrink_GBs"] = b / (kern["shrink"]["avg_ms"] * 1e-3) / 1e9
-    if "grad_stage1" in kern:
-        b = 0.5 * esz * p.T * (p.d_in + p.d_out)
-        skinny["grad_stage1_GBs"] = b / (kern["grad_stage1"]["avg_ms"] * 1e-3) / 1e9
-
+    # each of the two rank-r stages reads x once and dy once per step
+    for name in ("shrink", "grad_stage1"):
+        if name in kern and kern[name]["launches_per_step"] > 0:
+            per_launch = float(esz) * p.T * (p.d_in + p.d_out) / kern[name]["launches_per_step"]
+            skinny[name + "_GBs"] = per_launch / (kern[name]["avg_ms"] * 1e-3) / 1e9
     out = {
         "metric": "multi-LoRA linear fwd+bwd tokens/s", "value": p.T / (ms_wall * 1e-3), "unit": "tokens/s",
         "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms_wall,

@@ -247,10 +247,11 @@ lobra_status lobra_mlora_bwd(const lobra_mlora_plan* plan, const void* x, const 
     const PlanDev pd = device_view(p);
     const int dt = p.desc.dtype;
     char* wsb = static_cast<char*>(ws);
+    float* part_b = adapters ? reinterpret_cast<float*>(wsb + p.bwd_off_part_b) : nullptr;
+    float* part_a = adapters ? reinterpret_cast<float*>(wsb + p.bwd_off_part_a) : nullptr;
     if (!p.mfma) {
         float* G = adapters ? reinterpret_cast<float*>(wsb + p.bwd_off_g) : nullptr;
         const float* H = static_cast<const float*>(h_saved);
-        float* part = adapters ? reinterpret_cast<float*>(wsb + p.bwd_off_part) : nullptr;
         if (adapters) {
             if (!H) {
                 float* Hr = reinterpret_cast<float*>(wsb + p.bwd_off_h);
@@ -263,23 +264,20 @@ lobra_status lobra_mlora_bwd(const lobra_mlora_plan* plan, const void* x, const 
             LOBRA_LAUNCH(p, st, LOBRA_K_GEMM,
                          plain_gemm(pd, dt, true, dy, W, G, A, dx, pd.d_out, pd.d_in, pd.d_out, st));
         if (p.R_tot > 0) {
-            if (adapters)
+            if (adapters) {
                 LOBRA_LAUNCH(p, st, LOBRA_K_GRAD_STAGE1,
-                             plain_grad_stage1(pd, dt, false, H, dy, part, pd.d_out, st));
-            LOBRA_LAUNCH(p, st, LOBRA_K_GRAD_STAGE2,
-                         reduce_partials(pd, part, dB, pd.d_out, accumulate, st));
-            if (adapters)
+                             plain_grad_stage1(pd, dt, false, H, dy, part_b, pd.d_out, st));
                 LOBRA_LAUNCH(p, st, LOBRA_K_GRAD_STAGE1,
-                             plain_grad_stage1(pd, dt, false, G, x, part, pd.d_in, st));
-            LOBRA_LAUNCH(p, st, LOBRA_K_GRAD_STAGE2,
-                         reduce_partials(pd, part, dA, pd.d_in, accumulate, st));
+                             plain_grad_stage1(pd, dt, false, G, x, part_a, pd.d_in, st));
+            }
+            const GradJob jb{H, dy, part_b, dB, pd.d_out}, ja{G, x, part_a, dA, pd.d_in};
+            LOBRA_LAUNCH(p, st, LOBRA_K_GRAD_STAGE2, reduce_partials(pd, jb, ja, accumulate, st));
         }
         return LOBRA_OK;
     }
     // bf16 MFMA path
     char* G = adapters ? wsb + p.bwd_off_g : nullptr;
     const char* H = static_cast<const char*>(h_saved);
-    float* part = adapters ? reinterpret_cast<float*>(wsb + p.bwd_off_part) : nullptr;
     if (adapters) {
         if (!H) {
             char* Hr = wsb + p.bwd_off_h;
@@ -295,14 +293,11 @@ lobra_status lobra_mlora_bwd(const lobra_mlora_plan* plan, const void* x, const 
                      gemm_mfma(pd, true, dy, W, adapters ? G + p.p_layout.p_tok : nullptr, A, dx, pd.d_out,
                                pd.d_in, pd.d_out, st));
     if (p.R_tot > 0) {
-        if (adapters)
-            LOBRA_LAUNCH(p, st, LOBRA_K_GRAD_STAGE1,
-                         grad_mfma(pd, H + p.p_layout.p_blk, dy, part, pd.d_out, st));
-        LOBRA_LAUNCH(p, st, LOBRA_K_GRAD_STAGE2, reduce_partials(pd, part, dB, pd.d_out, accumulate, st));
-        if (adapters)
-            LOBRA_LAUNCH(p, st, LOBRA_K_GRAD_STAGE1,
-                         grad_mfma(pd, G + p.p_layout.p_blk, x, part, pd.d_in, st));
-        LOBRA_LAUNCH(p, st, LOBRA_K_GRAD_STAGE2, reduce_partials(pd, part, dA, pd.d_in, accumulate, st));
+        // dB (from s h and dy) and dA (from s g and x) share one launch per stage
+        const GradJob jb{adapters ? H + p.p_layout.p_blk : nullptr, dy, part_b, dB, pd.d_out};
+        const GradJob ja{adapters ? G + p.p_layout.p_blk : nullptr, x, part_a, dA, pd.d_in};
+        if (adapters) LOBRA_LAUNCH(p, st, LOBRA_K_GRAD_STAGE1, grad_mfma(pd, jb, ja, st));
+        LOBRA_LAUNCH(p, st, LOBRA_K_GRAD_STAGE2, reduce_partials(pd, jb, ja, accumulate, st));
     }
     return LOBRA_OK;
 }

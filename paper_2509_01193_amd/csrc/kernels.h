@@ -6,6 +6,15 @@
 
 namespace lobra {
 
+// One gradient reduction dM = sum_i P_i^T Z_i: stage 1 writes `part`, stage 2 writes `out` [R_tot, D].
+struct GradJob {
+    const void* P;   // projected activations (layout depends on the kernel family)
+    const void* Z;   // [T, D]
+    float* part;     // [sum over chunks of r_t, D]
+    float* out;      // [R_tot, D]
+    int32_t D;
+};
+
 // ---- plain fp32-FMA kernels (fp32 path; bf16 storage as a cross-check) ---------------------
 // P[row, :r_t] = s_t * Z[row, :] M_t^T for every token of an adapter segment (fp32, stride r_max).
 hipError_t plain_shrink(const PlanDev& pd, int dtype, const void* Z, const void* M, const float* s,
@@ -22,8 +31,9 @@ hipError_t plain_grad_stage1(const PlanDev& pd, int dtype, bool p_bf16, const vo
                              float* part, int32_t D, hipStream_t st);
 // Stage 2 (also used by the MFMA path): out[R, :] (+)= sum of the partial sums of task(R), in
 // chunk order, so that the result does not depend on scheduling.
-hipError_t reduce_partials(const PlanDev& pd, const float* part, float* out, int32_t D,
-                           bool accumulate, hipStream_t st);
+// One launch for up to two gradients (jb.out == nullptr: only ja).
+hipError_t reduce_partials(const PlanDev& pd, const GradJob& ja, const GradJob& jb, bool accumulate,
+                           hipStream_t st);
 // ---- bf16 MFMA kernels ------------------------------------------------------------------------
 // C[T, N] = Z[T, K] * op(W) + P * M_t with P bf16 [T][r_pad] (already scaled by s_t, zero beyond r_t).
 hipError_t gemm_mfma(const PlanDev& pd, bool transW, const void* Z, const void* W, const void* P,
@@ -33,8 +43,8 @@ hipError_t shrink_mfma(const PlanDev& pd, const void* Z, const void* M, const fl
                        void* P_tok, void* P_blk, int32_t D, hipStream_t st);
 
 // Stage 1 of dM_t = sum_i P_i^T Z_i from the block-transposed P; partial sums per reduction chunk.
-hipError_t grad_mfma(const PlanDev& pd, const void* P_blk, const void* Z, float* part, int32_t D,
-                     hipStream_t st);
+// (P = block-transposed bf16 copy; one launch for up to two gradients, jb.P == nullptr: only ja.)
+hipError_t grad_mfma(const PlanDev& pd, const GradJob& ja, const GradJob& jb, hipStream_t st);
 
 hipError_t token_task_map(const PlanDev& pd, int32_t* out_task, int64_t* out_count, hipStream_t st);
 

@@ -183,16 +183,20 @@ __global__ __launch_bounds__(256) void plain_gradreduce_kernel(PlanDev pd, const
 
 // stage 2: out[R, col] (+)= sum over the chunks of task(R), in chunk order.  One workgroup per
 // (rank row, 1024 columns), one float4 per thread, four chunk loads in flight.
-__global__ __launch_bounds__(256) void reduce_partials_kernel(PlanDev pd, const float* __restrict__ part,
-                                                              float* __restrict__ out, int32_t D,
-                                                              int accumulate)
+__global__ __launch_bounds__(256) void reduce_partials_kernel(PlanDev pd, GradJob ja, GradJob jb,
+                                                              int32_t tiles_a, int accumulate)
 {
+    const bool first = int32_t(blockIdx.y) < tiles_a;
+    const float* __restrict__ part = first ? ja.part : jb.part;
+    float* __restrict__ out = first ? ja.out : jb.out;
+    const int32_t D = first ? ja.D : jb.D;
+    const int32_t coltile = first ? int32_t(blockIdx.y) : int32_t(blockIdx.y) - tiles_a;
     const int32_t R = blockIdx.x;
     int32_t t = 0;
     while (pd.rank_off[t + 1] <= R) ++t;
     const int32_t p = R - pd.rank_off[t];
     const int32_t c0 = pd.task_chunk_off[t], c1 = pd.task_chunk_off[t + 1];
-    const int32_t col = blockIdx.y * 1024 + threadIdx.x * 4;
+    const int32_t col = coltile * 1024 + threadIdx.x * 4;
     if (col >= D) return;
     const int nv = min(4, D - col);                 // D need not be a multiple of 4 on the fp32 path
     float acc[4] = {0.f, 0.f, 0.f, 0.f};
@@ -226,13 +230,14 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(PlanDev pd, const 
     }
 }
 
-hipError_t reduce_partials(const PlanDev& pd, const float* part, float* out, int32_t D,
-                           bool accumulate, hipStream_t st)
+hipError_t reduce_partials(const PlanDev& pd, const GradJob& ja, const GradJob& jb, bool accumulate,
+                           hipStream_t st)
 {
     if (pd.R_tot == 0) return hipSuccess;
-    const dim3 grid(pd.R_tot, (D + 1023) / 1024);
+    const int32_t tiles_a = (ja.D + 1023) / 1024, tiles_b = jb.out ? (jb.D + 1023) / 1024 : 0;
+    const dim3 grid(pd.R_tot, tiles_a + tiles_b);
     if (grid.y > 65535u) return hipErrorInvalidValue;
-    reduce_partials_kernel<<<grid, 256, 0, st>>>(pd, part, out, D, accumulate ? 1 : 0);
+    reduce_partials_kernel<<<grid, 256, 0, st>>>(pd, ja, jb, tiles_a, accumulate ? 1 : 0);
     return hipGetLastError();
 }
 

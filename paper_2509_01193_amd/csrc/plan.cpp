@@ -145,9 +145,9 @@ lobra_status build_host_plan(const lobra_mlora_desc* d, uint32_t flags, Plan* p)
         p->fwd_ws_bytes = L.total;
         p->bwd_off_g = 0;
         p->bwd_off_h = L.total;
-        p->bwd_off_part = 2 * L.total;
-        p->bwd_ws_bytes = p->bwd_off_part +
-            align_up(size_t(p->part_rows) * size_t(std::max(d->d_in, d->d_out)) * 4, 256);
+        p->bwd_off_part_b = 2 * L.total;
+        p->bwd_off_part_a = p->bwd_off_part_b + align_up(size_t(p->part_rows) * size_t(d->d_out) * 4, 256);
+        p->bwd_ws_bytes = p->bwd_off_part_a + align_up(size_t(p->part_rows) * size_t(d->d_in) * 4, 256);
     } catch (const std::bad_alloc&) {
         return LOBRA_ERR_NOMEM;
     }

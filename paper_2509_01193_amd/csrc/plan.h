@@ -41,7 +41,7 @@ struct Plan {
 
     BufferLayout p_layout;              // layout of h_save (and of the G buffer in bwd)
     size_t h_save_bytes = 0, fwd_ws_bytes = 0, bwd_ws_bytes = 0;
-    size_t bwd_off_g = 0, bwd_off_h = 0, bwd_off_part = 0;
+    size_t bwd_off_g = 0, bwd_off_h = 0, bwd_off_part_b = 0, bwd_off_part_a = 0;
 
     // optional launch trace (see lobra_mlora_plan_set_trace)
     mutable void* const* trace_events = nullptr;

@@ -175,10 +175,15 @@ hipError_t shrink_mfma(const PlanDev& pd, const void* Z, const void* M, const fl
 // The four waves' sums are combined through LDS in two rounds (fixed order: ((w0+w2)+(w1+w3))).
 // -------------------------------------------------------------------------------------------------
 template <int NRB>
-__global__ __launch_bounds__(256) void grad_mfma_kernel(PlanDev pd, const uint16_t* __restrict__ P_blk,
-                                                        const uint16_t* __restrict__ Z,
-                                                        float* __restrict__ part, int32_t D)
+__global__ __launch_bounds__(256) void grad_mfma_kernel(PlanDev pd, GradJob ja, GradJob jb, int32_t tiles_a)
 {
+    // one launch serves both gradients: column tiles [0, tiles_a) belong to job a, the rest to job b
+    const bool first = int32_t(blockIdx.y) < tiles_a;
+    const uint16_t* __restrict__ P_blk = static_cast<const uint16_t*>(first ? ja.P : jb.P);
+    const uint16_t* __restrict__ Z = static_cast<const uint16_t*>(first ? ja.Z : jb.Z);
+    float* __restrict__ part = first ? ja.part : jb.part;
+    const int32_t D = first ? ja.D : jb.D;
+    const int32_t coltile = first ? int32_t(blockIdx.y) : int32_t(blockIdx.y) - tiles_a;
     __shared__ float red[2][NRB][8][64][4];
     const GradChunk ch = pd.chunks[blockIdx.x];
     const int32_t r = pd.rank_off[ch.task + 1] - pd.rank_off[ch.task];
@@ -186,7 +191,7 @@ __global__ __launch_bounds__(256) void grad_mfma_kernel(PlanDev pd, const uint16
     if (16 * rb0 >= r) return;                            // uniform: nothing to do for this task
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int c = lane & 15, g = lane >> 4;
-    const int32_t col = blockIdx.y * 128 + 8 * c;
+    const int32_t col = coltile * 128 + 8 * c;
     const bool col_in = col < D;
     const u32x4 zero4 = {0u, 0u, 0u, 0u};
 
@@ -270,20 +275,20 @@ __global__ __launch_bounds__(256) void grad_mfma_kernel(PlanDev pd, const uint16
     }
 }
 
-hipError_t grad_mfma(const PlanDev& pd, const void* P_blk, const void* Z, float* part, int32_t D,
-                     hipStream_t st)
+hipError_t grad_mfma(const PlanDev& pd, const GradJob& ja, const GradJob& jb, hipStream_t st)
 {
     if (pd.nchunks == 0) return hipSuccess;
     const int nrb = pd.r_pad / 16;
     const int NRB = nrb <= 1 ? 1 : (nrb <= 2 ? 2 : 4);
-    const dim3 grid(pd.nchunks, (D + 127) / 128, (nrb + NRB - 1) / NRB);
+    const int32_t tiles_a = (ja.D + 127) / 128, tiles_b = jb.P ? (jb.D + 127) / 128 : 0;
+    const dim3 grid(pd.nchunks, tiles_a + tiles_b, (nrb + NRB - 1) / NRB);
     if (grid.y > 65535u) return hipErrorInvalidValue;
     if (NRB == 1)
-        grad_mfma_kernel<1><<<grid, 256, 0, st>>>(pd, (const uint16_t*)P_blk, (const uint16_t*)Z, part, D);
+        grad_mfma_kernel<1><<<grid, 256, 0, st>>>(pd, ja, jb, tiles_a);
     else if (NRB == 2)
-        grad_mfma_kernel<2><<<grid, 256, 0, st>>>(pd, (const uint16_t*)P_blk, (const uint16_t*)Z, part, D);
+        grad_mfma_kernel<2><<<grid, 256, 0, st>>>(pd, ja, jb, tiles_a);
     else
-        grad_mfma_kernel<4><<<grid, 256, 0, st>>>(pd, (const uint16_t*)P_blk, (const uint16_t*)Z, part, D);
+        grad_mfma_kernel<4><<<grid, 256, 0, st>>>(pd, ja, jb, tiles_a);
     return hipGetLastError();
 }
 
