@@ -164,6 +164,30 @@ lobra_status lobra_mlora_bwd(const lobra_mlora_plan *plan, const void *x, const 
 lobra_status lobra_token_task_map(const lobra_mlora_plan *plan, int32_t *out_task,
                                   int64_t *out_count, void *hip_stream);
 
+/* Fused multi-adapter Adam step: the update that follows the backward pass, for the adapters of
+ * all tasks in one launch (the paper trains every task with Adam and cites its decoupled
+ * weight-decay form next to it: section 5.1).  Per element of task t, in fp32:
+ *     g = grad_scale[t] * grad;  m = beta1 m + (1-beta1) g;  v = beta2 v + (1-beta2) g^2
+ *     theta -= lr[t] * ( (m / (1-beta1^k)) / (sqrt(v / (1-beta2^k)) + eps) + weight_decay * theta )
+ * with k = step[t], the 1-based count of the step being taken by task t (tasks join a running
+ * batch at different times, so every task carries its own count, rate and gradient scale).
+ *   plan                 : any plan of this task set (supplies dtype, ranks, d_in, d_out)
+ *   lr, grad_scale       : device fp32 [n_tasks]; grad_scale may be NULL (= 1)
+ *   step                 : device int32 [n_tasks], every entry >= 1
+ *   dA, dB               : device fp32 gradients [R_tot, d_in] / [R_tot, d_out] (read only)
+ *   master_A, m_A, v_A   : device fp32 [R_tot, d_in], updated in place; likewise *_B with d_out
+ *   A, B                 : device, element type of the plan, or NULL: receive the updated parameters
+ *                          rounded once (to nearest even) for the next forward pass
+ * Rows of a task whose step entry is <= 0 are left untouched. */
+typedef struct {
+    float beta1, beta2, eps, weight_decay;
+} lobra_adam_config;
+lobra_status lobra_mlora_adam_step(const lobra_mlora_plan *plan, const lobra_adam_config *cfg,
+                                   const float *lr, const int32_t *step, const float *grad_scale,
+                                   const float *dA, const float *dB, float *master_A,
+                                   float *master_B, float *m_A, float *v_A, float *m_B, float *v_B,
+                                   void *A, void *B, void *hip_stream);
+
 /* Profiling aid (bench, tests).  While a trace is attached, every kernel that fwd / bwd /
  * token_task_map launch through this plan is bracketed by hipEventRecord on the call's stream:
  * the i-th launch since the trace was attached records events[2i] before and events[2i+1]
@@ -173,7 +197,7 @@ lobra_status lobra_token_task_map(const lobra_mlora_plan *plan, int32_t *out_tas
  * (host, may be NULL) counts the launches seen.  n_pairs = 0 or events = NULL detaches.
  * A plan with a trace attached must not be used from two threads at once. */
 enum { LOBRA_K_SHRINK = 1, LOBRA_K_GEMM = 2, LOBRA_K_GRAD_STAGE1 = 3, LOBRA_K_GRAD_STAGE2 = 4,
-       LOBRA_K_TOKEN_TASK = 5 };
+       LOBRA_K_TOKEN_TASK = 5, LOBRA_K_ADAM = 6 };
 lobra_status lobra_mlora_plan_set_trace(lobra_mlora_plan *plan, void *const *events,
                                         int32_t n_pairs, int32_t *kernel_ids,
                                         int32_t *n_launched);

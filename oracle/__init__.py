@@ -10,4 +10,5 @@ from .oracle import (  # noqa: F401
     forward,
     backward_dx,
     backward_grads,
+    adam_step,
 )

@@ -20,6 +20,7 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "lobra_oracle.c")
+_SRC_ADAM = os.path.join(_HERE, "lobra_adam_oracle.c")
 _LIB = os.path.join(_HERE, "liblobra_oracle.so")
 _lock = threading.Lock()
 _handle = None
@@ -29,12 +30,13 @@ F32, BF16 = 0, 1
 
 def build_oracle(force: bool = False, src: str = _SRC, out: str = _LIB) -> str:
     """Compile the C oracle with gcc (-O2 -fopenmp, no fast-math). Returns the .so path."""
+    srcs = [src, _SRC_ADAM]
     if (not force and os.path.exists(out)
-            and os.path.getmtime(out) >= os.path.getmtime(src)):
+            and os.path.getmtime(out) >= max(os.path.getmtime(f) for f in srcs)):
         return out
     tmp = out + ".tmp%d" % os.getpid()
     cmd = ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11",
-           "-Wall", "-Wextra", "-o", tmp, src]
+           "-Wall", "-Wextra", "-o", tmp] + srcs + ["-lm"]
     subprocess.run(cmd, check=True)
     os.replace(tmp, out)
     return out
@@ -67,6 +69,11 @@ def _bind(lib):
         ctypes.c_int, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32,
         ctypes.c_int32, i32p, i32p, vp, vp, vp, f32p, vp,
         ctypes.c_int64, i64p, f64p, f64p]
+    lib.lobra_oracle_adam.restype = ctypes.c_int
+    lib.lobra_oracle_adam.argtypes = [
+        ctypes.c_int32, i32p, ctypes.c_int32, f64p, i32p, f64p,
+        ctypes.c_double, ctypes.c_double, ctypes.c_double, ctypes.c_double,
+        f64p, f64p, f64p, f64p]
     lib.lobra_oracle_bwd_grads.restype = ctypes.c_int
     lib.lobra_oracle_bwd_grads.argtypes = [
         ctypes.c_int, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32,
@@ -210,6 +217,25 @@ def backward_grads(x, A, B, s, dy, rank_off, task_of):
     if rc != 0:
         raise RuntimeError("lobra_oracle_bwd_grads failed: %d" % rc)
     return dA, dB
+
+
+def adam_step(rank_off, lr, step, scale, beta1, beta2, eps, wd, grad, theta, m, v):
+    """One Adam / AdamW step on a stacked [R_tot, d] parameter; returns new (theta, m, v) in fp64."""
+    rank_off = _c(rank_off, np.int32)
+    n_tasks = int(rank_off.shape[0]) - 1
+    grad = _c(grad, np.float64)
+    theta, m, v = (np.array(a, dtype=np.float64, order="C", copy=True) for a in (theta, m, v))
+    assert grad.shape == theta.shape == m.shape == v.shape and grad.shape[0] == rank_off[-1]
+    lr, scale = _c(lr, np.float64), _c(scale, np.float64)
+    step = _c(step, np.int32)
+    rc = _lib().lobra_oracle_adam(
+        n_tasks, _p(rank_off, ctypes.c_int32), int(grad.shape[1]), _p(lr, ctypes.c_double),
+        _p(step, ctypes.c_int32), _p(scale, ctypes.c_double), float(beta1), float(beta2),
+        float(eps), float(wd), _p(grad, ctypes.c_double), _p(theta, ctypes.c_double),
+        _p(m, ctypes.c_double), _p(v, ctypes.c_double))
+    if rc != 0:
+        raise ValueError("lobra_oracle_adam failed: %d" % rc)
+    return theta, m, v
 
 
 class Oracle:

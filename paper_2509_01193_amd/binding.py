@@ -24,7 +24,7 @@ MAX_RANK = 128
 EXPORTS = [
     "lobra_mlora_validate", "lobra_mlora_plan_create", "lobra_mlora_plan_destroy",
     "lobra_mlora_plan_sizes", "lobra_mlora_plan_query", "lobra_mlora_fwd", "lobra_mlora_bwd",
-    "lobra_token_task_map", "lobra_mlora_plan_set_trace", "lobra_status_string", "lobra_version",
+    "lobra_token_task_map", "lobra_mlora_adam_step", "lobra_mlora_plan_set_trace", "lobra_status_string", "lobra_version",
 ]
 
 
@@ -36,6 +36,11 @@ class Desc(ctypes.Structure):
         ("seg_off", ctypes.POINTER(ctypes.c_int32)),
         ("seg_task", ctypes.POINTER(ctypes.c_int32)),
     ]
+
+
+class AdamConfig(ctypes.Structure):
+    _fields_ = [("beta1", ctypes.c_float), ("beta2", ctypes.c_float), ("eps", ctypes.c_float),
+                ("weight_decay", ctypes.c_float)]
 
 
 class LobraError(RuntimeError):
@@ -73,6 +78,8 @@ def lib():
         L.lobra_mlora_bwd.argtypes = [vp] * 11 + [u32, vp, sz, vp]
         L.lobra_token_task_map.restype = ctypes.c_int
         L.lobra_token_task_map.argtypes = [vp, vp, vp, vp]
+        L.lobra_mlora_adam_step.restype = ctypes.c_int
+        L.lobra_mlora_adam_step.argtypes = [vp, ctypes.POINTER(AdamConfig)] + [vp] * 13 + [vp]
         L.lobra_status_string.restype = ctypes.c_char_p
         L.lobra_status_string.argtypes = [ctypes.c_int]
         L.lobra_version.restype = ctypes.c_int
@@ -205,6 +212,17 @@ def lobra_mlora_bwd(plan: Plan, x, W, A, B, s, dy, h_saved, dx, dA, dB, flags=0,
     return st
 
 
+def lobra_mlora_adam_step(plan: Plan, cfg: AdamConfig, lr, step, grad_scale, dA, dB, master_A, master_B,
+                          m_A, v_A, m_B, v_B, A=None, B=None, stream=None, check=True):
+    """Fused Adam over all tasks' adapters (device tensors, updated in place). Returns the status."""
+    st = lib().lobra_mlora_adam_step(plan.handle, ctypes.byref(cfg), _ptr(lr), _ptr(step), _ptr(grad_scale),
+                                     _ptr(dA), _ptr(dB), _ptr(master_A), _ptr(master_B), _ptr(m_A),
+                                     _ptr(v_A), _ptr(m_B), _ptr(v_B), _ptr(A), _ptr(B), _stream(stream))
+    if check:
+        _check(st, "lobra_mlora_adam_step")
+    return st
+
+
 def lobra_token_task_map(plan: Plan, out_task, out_count, stream=None):
     _check(lib().lobra_token_task_map(plan.handle, _ptr(out_task), _ptr(out_count), _stream(stream)),
            "lobra_token_task_map")
@@ -274,7 +292,7 @@ class DeviceProblem:
 # ---------------------------------------------------------------------------------------------
 # launch trace: per-kernel durations from HIP events recorded on the stream the kernels run on
 # ---------------------------------------------------------------------------------------------
-KERNEL_NAMES = {1: "shrink", 2: "gemm", 3: "grad_stage1", 4: "grad_stage2", 5: "token_task"}
+KERNEL_NAMES = {1: "shrink", 2: "gemm", 3: "grad_stage1", 4: "grad_stage2", 5: "token_task", 6: "adam"}
 
 
 class LaunchTrace:

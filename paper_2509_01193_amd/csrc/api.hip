@@ -313,6 +313,29 @@ lobra_status lobra_token_task_map(const lobra_mlora_plan* plan, int32_t* out_tas
     return LOBRA_OK;
 }
 
+lobra_status lobra_mlora_adam_step(const lobra_mlora_plan* plan, const lobra_adam_config* cfg,
+                                   const float* lr, const int32_t* step, const float* grad_scale,
+                                   const float* dA, const float* dB, float* master_A,
+                                   float* master_B, float* m_A, float* v_A, float* m_B, float* v_B,
+                                   void* A, void* B, void* hip_stream)
+{
+    lobra_status rs = runnable(plan);
+    if (rs != LOBRA_OK) return rs;
+    const Plan& p = *plan;
+    if (p.R_tot == 0) return LOBRA_OK;
+    if (!cfg || !lr || !step || !dA || !dB || !master_A || !master_B || !m_A || !v_A || !m_B || !v_B)
+        return LOBRA_ERR_NULL;
+    if (!(cfg->beta1 >= 0.f && cfg->beta1 < 1.f && cfg->beta2 >= 0.f && cfg->beta2 < 1.f && cfg->eps >= 0.f))
+        return LOBRA_ERR_SHAPE;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const PlanDev pd = device_view(p);
+    const AdamTensor ta{dA, master_A, m_A, v_A, A, pd.d_in}, tb{dB, master_B, m_B, v_B, B, pd.d_out};
+    LOBRA_LAUNCH(p, st, LOBRA_K_ADAM,
+                 adam_step(pd, p.desc.dtype, cfg->beta1, cfg->beta2, cfg->eps, cfg->weight_decay, lr, step,
+                           grad_scale, ta, tb, st));
+    return LOBRA_OK;
+}
+
 lobra_status lobra_mlora_plan_set_trace(lobra_mlora_plan* plan, void* const* events, int32_t n_pairs,
                                         int32_t* kernel_ids, int32_t* n_launched)
 {

@@ -46,6 +46,19 @@ hipError_t shrink_mfma(const PlanDev& pd, const void* Z, const void* M, const fl
 // (P = block-transposed bf16 copy; one launch for up to two gradients, jb.P == nullptr: only ja.)
 hipError_t grad_mfma(const PlanDev& pd, const GradJob& ja, const GradJob& jb, hipStream_t st);
 
+// Fused Adam over the stacked adapters A [R_tot, d_in] and B [R_tot, d_out] (one launch).
+struct AdamTensor {
+    const float* grad;
+    float* master;
+    float* m;
+    float* v;
+    void* param;     // plan dtype, may be nullptr
+    int32_t D;
+};
+hipError_t adam_step(const PlanDev& pd, int dtype, float beta1, float beta2, float eps, float wd,
+                     const float* lr, const int32_t* step, const float* grad_scale,
+                     const AdamTensor& ta, const AdamTensor& tb, hipStream_t st);
+
 hipError_t token_task_map(const PlanDev& pd, int32_t* out_task, int64_t* out_count, hipStream_t st);
 
 }  // namespace lobra

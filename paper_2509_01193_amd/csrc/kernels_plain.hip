@@ -257,6 +257,60 @@ hipError_t plain_grad_stage1(const PlanDev& pd, int dtype, bool p_bf16, const vo
 }
 
 // -------------------------------------------------------------------------------------------
+// fused multi-adapter Adam (Kingma & Ba, Algorithm 1; decoupled decay of Loshchilov & Hutter):
+// one workgroup per (rank row, 1024 columns) of A, then of B; the row's task supplies lr, step
+// count and gradient scale; bias corrections are taken in double once per workgroup
+// -------------------------------------------------------------------------------------------
+template <typename E>
+__global__ __launch_bounds__(256) void adam_kernel(PlanDev pd, float beta1, float beta2, float eps, float wd,
+                                                   const float* __restrict__ lr,
+                                                   const int32_t* __restrict__ step,
+                                                   const float* __restrict__ grad_scale, AdamTensor ta,
+                                                   AdamTensor tb, int32_t tiles_a)
+{
+    const bool first = int32_t(blockIdx.y) < tiles_a;
+    const AdamTensor& tn = first ? ta : tb;
+    const int32_t coltile = first ? int32_t(blockIdx.y) : int32_t(blockIdx.y) - tiles_a;
+    const int32_t R = blockIdx.x;
+    int32_t t = 0;
+    while (pd.rank_off[t + 1] <= R) ++t;
+    const int32_t k = step[t];
+    if (k <= 0) return;
+    const float c1 = float(1.0 - pow(double(beta1), double(k)));
+    const float c2 = float(1.0 - pow(double(beta2), double(k)));
+    const float lrt = lr[t], sc = grad_scale ? grad_scale[t] : 1.f;
+    E* param = static_cast<E*>(tn.param);
+    for (int32_t col = coltile * 1024 + threadIdx.x; col < min(tn.D, (coltile + 1) * 1024); col += 256) {
+        const size_t i = size_t(R) * tn.D + col;
+        const float g = sc * tn.grad[i];
+        const float m = beta1 * tn.m[i] + (1.f - beta1) * g;
+        const float v = beta2 * tn.v[i] + (1.f - beta2) * g * g;
+        const float th = tn.master[i];
+        const float upd = (m / c1) / (sqrtf(v / c2) + eps) + wd * th;
+        const float nt = th - lrt * upd;
+        tn.m[i] = m;
+        tn.v[i] = v;
+        tn.master[i] = nt;
+        if (param) Elem<E>::store(param, i, nt);
+    }
+}
+
+hipError_t adam_step(const PlanDev& pd, int dtype, float beta1, float beta2, float eps, float wd,
+                     const float* lr, const int32_t* step, const float* grad_scale,
+                     const AdamTensor& ta, const AdamTensor& tb, hipStream_t st)
+{
+    if (pd.R_tot == 0) return hipSuccess;
+    const int32_t tiles_a = (ta.D + 1023) / 1024, tiles_b = (tb.D + 1023) / 1024;
+    const dim3 grid(pd.R_tot, tiles_a + tiles_b);
+    if (grid.y > 65535u) return hipErrorInvalidValue;
+    if (dtype == LOBRA_F32)
+        adam_kernel<float><<<grid, 256, 0, st>>>(pd, beta1, beta2, eps, wd, lr, step, grad_scale, ta, tb, tiles_a);
+    else
+        adam_kernel<uint16_t><<<grid, 256, 0, st>>>(pd, beta1, beta2, eps, wd, lr, step, grad_scale, ta, tb, tiles_a);
+    return hipGetLastError();
+}
+
+// -------------------------------------------------------------------------------------------
 // index probe
 // -------------------------------------------------------------------------------------------
 __global__ void zero_counts_kernel(unsigned long long* cnt, int32_t n)
