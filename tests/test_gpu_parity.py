@@ -272,3 +272,52 @@ def test_full_size_workload_sampled_rows(cfg):
     del dp
     import torch
     torch.cuda.empty_cache()
+
+
+# ---------------------------------------------------------------------------------------------
+# randomised problems: widths, ranks, tables and scales drawn from a seeded generator
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("seed", range(12))
+def test_random_problems(seed):
+    rng = np.random.default_rng(1000 + seed)
+    dtype = "bf16" if seed % 3 else "f32"
+    mult = 8 if dtype == "bf16" else 1
+    d_in = int(rng.integers(1, 80)) * mult
+    d_out = int(rng.integers(1, 80)) * mult
+    n_tasks = int(rng.integers(1, 7))
+    ranks = rng.choice([1, 2, 4, 8, 15, 16, 17, 32, 48, 64, 100, 128], n_tasks)
+    S = int(rng.integers(1, 30))
+    lens = rng.choice([0, 1, 2, 7, 16, 31, 32, 33, 63, 64, 65, 200, 256, 300, 700], S)
+    seg_task = rng.integers(-1, n_tasks, S)
+    seg_off = np.concatenate([[0], np.cumsum(lens)])
+    s = rng.uniform(-2, 2, n_tasks).astype(np.float32)
+    p = wl.make_custom("random%d" % seed, dtype, d_in, d_out, ranks, seg_off, seg_task, 500 + seed, s=s,
+                       std_x=1.0, std_w=0.05, std_a=0.05, std_b=0.05)
+    check_index_probe(p)
+    check_problem(p, label="%s %dx%d n=%d T=%d" % (dtype, d_in, d_out, n_tasks, p.T))
+
+
+def test_padded_bucket_layout_as_no_adapter_spans():
+    """The paper's default layout pads every sequence of a chunk to a bucket boundary (section 2.1).
+    Pad tokens are segments of task -1: they take the base product only and stay out of dA, dB."""
+    import torch
+    lens, tasks, bucket = [100, 250, 17, 256, 190], [0, 1, 1, 0, 2], 256
+    seg_off, seg_task = [0], []
+    for L, t in zip(lens, tasks):
+        seg_off.append(seg_off[-1] + L); seg_task.append(t)
+        if L < bucket:
+            seg_off.append(seg_off[-1] + bucket - L); seg_task.append(-1)
+    padded = wl.make_custom("padded", "bf16", 320, 192, [16, 8, 32], seg_off, seg_task, 11)
+    dp, _ = check_problem(padded, label="padded")
+    # the packed batch of the same sequences gives the same adapter gradients
+    keep = np.concatenate([np.arange(seg_off[k], seg_off[k + 1]) for k in range(len(seg_task)) if seg_task[k] >= 0])
+    packed = wl.make_custom("packed", "bf16", 320, 192, [16, 8, 32], np.concatenate([[0], np.cumsum(lens)]), tasks, 11)
+    packed.x, packed.dy = padded.x[keep], padded.dy[keep]
+    packed.W, packed.A, packed.B = padded.W, padded.A, padded.B
+    dq = bd.DeviceProblem(packed)
+    dq.step()
+    torch.cuda.synchronize()
+    idx = torch.from_numpy(keep).to(dp.dev)
+    assert torch.equal(dp.y.index_select(0, idx), dq.y) and torch.equal(dp.dx.index_select(0, idx), dq.dx)
+    for a, b in ((dp.dA, dq.dA), (dp.dB, dq.dB)):
+        assert ((a - b).abs().max() / b.abs().max()).item() < 1e-5      # same terms, other summation order
