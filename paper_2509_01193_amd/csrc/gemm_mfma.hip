@@ -29,6 +29,9 @@
 #ifndef LOBRA_GEMM_DST
 #define LOBRA_GEMM_DST 2
 #endif
+#ifndef LOBRA_GEMM_ISSUE_AT
+#define LOBRA_GEMM_ISSUE_AT 2      // K step of the tile after which the next tile's copies are issued
+#endif
 #ifndef LOBRA_GEMM_GM
 #define LOBRA_GEMM_GM 8
 #endif
@@ -194,6 +197,17 @@ void gemm_mfma_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const uint16_t
         }
         const unsigned char* zbase = reinterpret_cast<const unsigned char*>(Z + size_t(row0) * K);
         const unsigned char* wbase = reinterpret_cast<const unsigned char*>(W_KN ? W + col0 : W + size_t(col0) * ldw);
+        // copies q0 .. q1-1 of this wave for K tile kt (q < NBZ: Z blocks, then W blocks)
+        auto issue_some = [&](int32_t kt, int q0, int q1) {
+            const uint32_t st = lds0 + uint32_t(kt % DST) * DSTAGE_BYTES;
+            const unsigned char* zb = zbase + size_t(kt) * (DBK * 2);
+            const unsigned char* wb = W_KN ? wbase + size_t(kt) * DBK * ldw * 2 : wbase + size_t(kt) * (DBK * 2);
+#pragma unroll
+            for (int q = q0; q < q1; ++q) {
+                if (q < NBZ) dma16(st + (wave + NW * q) * 1024, zb, zvo[q]);
+                else dma16(st + DZT_BYTES + (wave + NW * (q - NBZ)) * 1024, wb, wvo[q - NBZ]);
+            }
+        };
         auto issue = [&](int32_t kt) {              // all of this wave's copies for K tile kt
             const uint32_t st = lds0 + uint32_t(kt % DST) * DSTAGE_BYTES;
 #if defined(LOBRA_GEMM_EXP) && LOBRA_GEMM_EXP == 6      // timing experiment: every K tile re-reads tile 0..3
@@ -208,11 +222,11 @@ void gemm_mfma_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const uint16_t
 #pragma unroll
             for (int j = 0; j < NBZ; ++j) dma16(st + DZT_BYTES + (wave + NW * j) * 1024, wb, wvo[j]);
         };
-        auto compute = [&](int stage) {
+        auto compute = [&](int stage, int ks0, int ks1) {
             const unsigned char* zs = lds + stage * DSTAGE_BYTES;
             const unsigned char* ws = zs + DZT_BYTES;
 #pragma unroll
-            for (int ks = 0; ks < DBK / 16; ++ks) {
+            for (int ks = ks0; ks < ks1; ++ks) {
                 bf16x8 zf[MB], wf[NB];
 #pragma unroll
                 for (int mb = 0; mb < MB; ++mb) {
@@ -266,10 +280,30 @@ void gemm_mfma_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const uint16_t
 #if !defined(LOBRA_GEMM_EXP) || LOBRA_GEMM_EXP != 5
             __builtin_amdgcn_s_barrier();
 #endif
+#if LOBRA_GEMM_ISSUE_AT == 0
 #if !defined(LOBRA_GEMM_EXP) || LOBRA_GEMM_EXP < 4
             if (kt + DST - 1 < KT) issue(kt + DST - 1);
 #endif
-            compute(kt % DST);
+            compute(kt % DST, 0, DBK / 16);
+#elif LOBRA_GEMM_ISSUE_AT > 0
+            compute(kt % DST, 0, LOBRA_GEMM_ISSUE_AT);
+            if (kt + DST - 1 < KT) issue(kt + DST - 1);
+            compute(kt % DST, LOBRA_GEMM_ISSUE_AT, DBK / 16);
+#else       // spread: a share of the copies after every K step but the last |LOBRA_GEMM_ISSUE_AT| - ... 
+            {
+                constexpr int NKS = DBK / 16, FIRST = -LOBRA_GEMM_ISSUE_AT - 1;   // first K step that is followed by copies
+                constexpr int SLOTS = NKS - 1 - FIRST + 1;
+                const bool more = kt + DST - 1 < KT;
+#pragma unroll
+                for (int ks = 0; ks < NKS; ++ks) {
+                    compute(kt % DST, ks, ks + 1);
+                    if (ks >= FIRST && ks - FIRST < SLOTS && more) {
+                        const int sl = ks - FIRST;
+                        issue_some(kt + DST - 1, (2 * NBZ * sl) / SLOTS, (2 * NBZ * (sl + 1)) / SLOTS);
+                    }
+                }
+            }
+#endif
         }
         wait_vmcnt<0>();
         __syncthreads();
