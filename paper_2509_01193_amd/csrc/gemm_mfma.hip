@@ -5,19 +5,30 @@
 // (paper section 2.1: X W + X (down)(up); section 1: one shared base product for the fused batch,
 // a per-task adapter product on top of it).
 //
-// Tiling: 256 x 256 x 64 per workgroup of WM x WN waves, every wave owns (256/WM) x (256/WN) as
-// blocks of v_mfma_f32_32x32x16_bf16 with fp32 accumulators in AGPRs, LDS double buffered,
-// global -> register -> LDS prefetch of the next K tile while the current one is multiplied.
-// The MFMA "A" operand is fed from W and the "B" operand from Z, so a lane ends up with four
-// consecutive output columns of one row, which packs into 8-byte LDS writes in the epilogue.
+// Tiling: 256 x 256 x 64 per workgroup of WM x WN waves (default 2 x 4 = 512 threads, two waves per
+// SIMD), every wave owns (256/WM) x (256/WN) as blocks of v_mfma_f32_32x32x16_bf16 with fp32
+// accumulators.  The MFMA "A" operand is fed from W and the "B" operand from Z, so a lane ends up
+// with four consecutive output columns of one row, which packs into 8-byte LDS writes in the epilogue.
 //
-// LDS layouts
-//   Z tile, and the W tile when K is fastest: [256 rows][64 k], 16-byte chunks XOR-swizzled
-//       with (row >> 1) & 7 so that the 16 rows of one ds_read_b128 pass hit 16 bank groups.
-//   W tile when N is fastest (forward): [64 k][256 + 32 n]; the MFMA operand (8 consecutive k
-//       of one column) is gathered with two ds_read_b64_tr_b16, the row pitch of 576 bytes puts
-//       the 4 k-rows of one pass in different bank quarters.
-//   C staging in the epilogue: per wave [rows][cols + 8] bf16.
+// Two loaders behind one kernel template:
+//   DMA  (K a multiple of 64): K tiles go global -> LDS with global_load_lds_dwordx4, no registers
+//        and no ds_write in between; two LDS stages; the copies of tile kt+1 are issued in the middle
+//        of tile kt, after the barrier that freed their stage; every row segment is one 128-byte line.
+//   register-staged (any K that is a multiple of 8): global -> VGPR -> LDS with a zero-filled K tail.
+//
+// LDS layouts (DMA path; the register-staged path pads the forward W tile instead of swizzling it)
+//   Z tile, and the W tile when K is fastest (backward): [256 rows][64 k], 16-byte chunk c of a row
+//       stored at c ^ ((row >> 1) & 7): the 16 rows of one ds_read_b128 pass hit 16 bank groups.
+//   W tile when N is fastest (forward): [64 k][256 n], chunk c of k-row k stored at c ^ ((k & 3) << 2);
+//       the MFMA operand (8 consecutive k of one column) is gathered with two ds_read_b64_tr_b16 and
+//       the 4 k-rows of one such read sit in different bank quarters.
+//   A wave-wide direct-to-LDS copy lands in lane order, so the swizzle is applied to the global
+//       address each lane fetches from.
+//   C staging in the epilogue: per wave [rows][cols + 8] bf16, written back with non-temporal stores.
+//
+// Tuning macros (defaults are what the measurements chose): LOBRA_GEMM_WM/WN wave grid, LOBRA_GEMM_DBK/
+// DST K-tile width and stage count of the DMA path, LOBRA_GEMM_ISSUE_AT, LOBRA_GEMM_GM tile-rows per
+// sweep of the XCD-aware tile order, LOBRA_GEMM_NT_STORE, LOBRA_GEMM_DMA.
 #include "kernels.h"
 
 #ifndef LOBRA_GEMM_DMA
@@ -197,26 +208,10 @@ void gemm_mfma_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const uint16_t
         }
         const unsigned char* zbase = reinterpret_cast<const unsigned char*>(Z + size_t(row0) * K);
         const unsigned char* wbase = reinterpret_cast<const unsigned char*>(W_KN ? W + col0 : W + size_t(col0) * ldw);
-        // copies q0 .. q1-1 of this wave for K tile kt (q < NBZ: Z blocks, then W blocks)
-        auto issue_some = [&](int32_t kt, int q0, int q1) {
+        auto issue = [&](int32_t kt) {              // all of this wave's copies for K tile kt
             const uint32_t st = lds0 + uint32_t(kt % DST) * DSTAGE_BYTES;
             const unsigned char* zb = zbase + size_t(kt) * (DBK * 2);
             const unsigned char* wb = W_KN ? wbase + size_t(kt) * DBK * ldw * 2 : wbase + size_t(kt) * (DBK * 2);
-#pragma unroll
-            for (int q = q0; q < q1; ++q) {
-                if (q < NBZ) dma16(st + (wave + NW * q) * 1024, zb, zvo[q]);
-                else dma16(st + DZT_BYTES + (wave + NW * (q - NBZ)) * 1024, wb, wvo[q - NBZ]);
-            }
-        };
-        auto issue = [&](int32_t kt) {              // all of this wave's copies for K tile kt
-            const uint32_t st = lds0 + uint32_t(kt % DST) * DSTAGE_BYTES;
-#if defined(LOBRA_GEMM_EXP) && LOBRA_GEMM_EXP == 6      // timing experiment: every K tile re-reads tile 0..3
-            const int32_t kq = kt & 3;
-#else
-            const int32_t kq = kt;
-#endif
-            const unsigned char* zb = zbase + size_t(kq) * (DBK * 2);
-            const unsigned char* wb = W_KN ? wbase + size_t(kq) * DBK * ldw * 2 : wbase + size_t(kq) * (DBK * 2);
 #pragma unroll
             for (int j = 0; j < NBZ; ++j) dma16(st + (wave + NW * j) * 1024, zb, zvo[j]);
 #pragma unroll
@@ -272,38 +267,15 @@ void gemm_mfma_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const uint16_t
             // this wave's copies of tile kt have landed once at most the copies of the (up to DST-2)
             // tiles issued after it are still outstanding; the barrier then covers the other waves'
             // copies and tells that everybody is done reading the stage that is refilled next
-#if !defined(LOBRA_GEMM_EXP) || LOBRA_GEMM_EXP < 3     // EXP >= 3: timing experiments only, wrong results
             if (DST >= 4 && kt + 2 < KT) wait_vmcnt<(DST >= 4 ? 2 : 0) * NPW>();
             else if (DST >= 3 && kt + 1 < KT) wait_vmcnt<(DST >= 3 ? 1 : 0) * NPW>();
             else wait_vmcnt<0>();
-#endif
-#if !defined(LOBRA_GEMM_EXP) || LOBRA_GEMM_EXP != 5
             __builtin_amdgcn_s_barrier();
-#endif
-#if LOBRA_GEMM_ISSUE_AT == 0
-#if !defined(LOBRA_GEMM_EXP) || LOBRA_GEMM_EXP < 4
-            if (kt + DST - 1 < KT) issue(kt + DST - 1);
-#endif
-            compute(kt % DST, 0, DBK / 16);
-#elif LOBRA_GEMM_ISSUE_AT > 0
+            // the copies of the tile that reuses the freed stage go out after K step ISSUE_AT of this
+            // tile: right after the barrier they would compete with the tile's first LDS reads
             compute(kt % DST, 0, LOBRA_GEMM_ISSUE_AT);
             if (kt + DST - 1 < KT) issue(kt + DST - 1);
             compute(kt % DST, LOBRA_GEMM_ISSUE_AT, DBK / 16);
-#else       // spread: a share of the copies after every K step but the last |LOBRA_GEMM_ISSUE_AT| - ... 
-            {
-                constexpr int NKS = DBK / 16, FIRST = -LOBRA_GEMM_ISSUE_AT - 1;   // first K step that is followed by copies
-                constexpr int SLOTS = NKS - 1 - FIRST + 1;
-                const bool more = kt + DST - 1 < KT;
-#pragma unroll
-                for (int ks = 0; ks < NKS; ++ks) {
-                    compute(kt % DST, ks, ks + 1);
-                    if (ks >= FIRST && ks - FIRST < SLOTS && more) {
-                        const int sl = ks - FIRST;
-                        issue_some(kt + DST - 1, (2 * NBZ * sl) / SLOTS, (2 * NBZ * (sl + 1)) / SLOTS);
-                    }
-                }
-            }
-#endif
         }
         wait_vmcnt<0>();
         __syncthreads();
@@ -409,16 +381,6 @@ void gemm_mfma_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const uint16_t
         if (KF > 0) gload(0); else gload_tail(0);
         lstore(0);
         __syncthreads();
-#if defined(LOBRA_GEMM_EXP) && LOBRA_GEMM_EXP >= 1   // timing experiments only: wrong results
-        for (int32_t kt = 0; kt < KT; ++kt) {
-            const int buf = kt & 1;
-            compute(buf);
-#if LOBRA_GEMM_EXP == 1
-            if (kt + 1 < KT) lstore(buf ^ 1);
-            __syncthreads();
-#endif
-        }
-#else
         for (int32_t kt = 0; kt < KT; ++kt) {
             const int buf = kt & 1;
             if (kt + 1 < KF) gload((kt + 1) * BK);
@@ -427,8 +389,6 @@ void gemm_mfma_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const uint16_t
             if (kt + 1 < KT) lstore(buf ^ 1);
             __syncthreads();
         }
-#endif
-
     }
 
     // ---- fused up projection: for every adapter segment that crosses this tile, ceil(r_t / 16) extra
