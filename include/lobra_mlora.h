@@ -188,6 +188,22 @@ lobra_status lobra_mlora_adam_step(const lobra_mlora_plan *plan, const lobra_ada
                                    float *master_B, float *m_A, float *v_A, float *m_B, float *v_B,
                                    void *A, void *B, void *hip_stream);
 
+/* Host-side dynamic bucketing (paper section 4.3, "Dynamic Bucketing"): the caller's step right before
+ * the layer when chunks are padded.  Given the lengths of a batch and U candidate boundaries
+ * u_1 < ... < u_U, choose at most R of them so that padding every sequence to the closest chosen
+ * boundary at or above its length costs the fewest pad tokens (the paper's dynamic programme over
+ * State_{i,j}; O(n_seq + R U^2) with prefix sums, empty intervals cost nothing).  Pure host code: all
+ * pointers are HOST pointers, no HIP call is made.
+ *   seq_len [n_seq]   : every length in [1, bounds[U-1]]
+ *   bounds  [U]       : strictly increasing, positive
+ *   out_bounds [R]    : the chosen boundaries, ascending, *out_n of them (the rest set to 0); the
+ *                       largest one is the smallest candidate that covers the longest sequence
+ *   out_padding       : total pad tokens of the batch under the chosen boundaries (may be NULL)
+ * LOBRA_ERR_SHAPE for U < 1, R < 1, a non-increasing table or a length outside the table. */
+lobra_status lobra_dynamic_buckets(const int32_t *seq_len, int64_t n_seq, const int32_t *bounds,
+                                   int32_t U, int32_t R, int32_t *out_bounds, int32_t *out_n,
+                                   int64_t *out_padding);
+
 /* Profiling aid (bench, tests).  While a trace is attached, every kernel that fwd / bwd /
  * token_task_map launch through this plan is bracketed by hipEventRecord on the call's stream:
  * the i-th launch since the trace was attached records events[2i] before and events[2i+1]

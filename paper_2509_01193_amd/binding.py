@@ -24,7 +24,7 @@ MAX_RANK = 128
 EXPORTS = [
     "lobra_mlora_validate", "lobra_mlora_plan_create", "lobra_mlora_plan_destroy",
     "lobra_mlora_plan_sizes", "lobra_mlora_plan_query", "lobra_mlora_fwd", "lobra_mlora_bwd",
-    "lobra_token_task_map", "lobra_mlora_adam_step", "lobra_mlora_plan_set_trace", "lobra_status_string", "lobra_version",
+    "lobra_token_task_map", "lobra_mlora_adam_step", "lobra_dynamic_buckets", "lobra_mlora_plan_set_trace", "lobra_status_string", "lobra_version",
 ]
 
 
@@ -221,6 +221,22 @@ def lobra_mlora_adam_step(plan: Plan, cfg: AdamConfig, lr, step, grad_scale, dA,
     if check:
         _check(st, "lobra_mlora_adam_step")
     return st
+
+
+def lobra_dynamic_buckets(seq_len, bounds, R):
+    """Host-side dynamic bucketing: returns (chosen boundaries ascending, total pad tokens)."""
+    L = lib()
+    L.lobra_dynamic_buckets.restype = ctypes.c_int
+    i32p = ctypes.POINTER(ctypes.c_int32)
+    L.lobra_dynamic_buckets.argtypes = [i32p, ctypes.c_int64, i32p, ctypes.c_int32, ctypes.c_int32, i32p, i32p,
+                                        ctypes.POINTER(ctypes.c_int64)]
+    sl, bo = _i32(seq_len), _i32(bounds)
+    out = np.zeros(max(int(R), 1), np.int32)
+    n, pad = ctypes.c_int32(), ctypes.c_int64()
+    _check(L.lobra_dynamic_buckets(sl.ctypes.data_as(i32p), int(sl.shape[0]), bo.ctypes.data_as(i32p),
+                                   int(bo.shape[0]), int(R), out.ctypes.data_as(i32p), ctypes.byref(n),
+                                   ctypes.byref(pad)), "lobra_dynamic_buckets")
+    return out[: n.value].tolist(), int(pad.value)
 
 
 def lobra_token_task_map(plan: Plan, out_task, out_count, stream=None):

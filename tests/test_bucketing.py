@@ -1,0 +1,69 @@
+"""Dynamic bucketing (paper section 4.3): oracle pins and the host implementation against the oracle. CPU only."""
+import numpy as np
+import pytest
+
+from oracle import bucketing as ob
+from paper_2509_01193_amd import binding as bd
+
+
+def batches():
+    rng = np.random.default_rng(5)
+    for trial in range(40):
+        U = int(rng.integers(1, 8))
+        u = sorted(rng.choice(np.arange(1, 40), U, replace=False).tolist())
+        n = int(rng.integers(0, 12))
+        lens = rng.integers(1, u[-1] + 1, n).tolist()
+        R = int(rng.integers(1, U + 2))
+        yield lens, u, R
+
+
+def test_oracle_dp_equals_brute_force_definition():
+    for lens, u, R in batches():
+        total, bounds = ob.dp_min_padding(lens, u, R)
+        bf = ob.brute_force(lens, u, R)
+        assert total == bf, (lens, u, R)
+        if lens:
+            assert len(bounds) <= R and ob.padding_for(lens, bounds) == total
+
+
+def test_oracle_special_cases():
+    u = [256, 512, 768, 1024]
+    lens = [100, 300, 300, 700, 1000]
+    # as many buckets as boundaries: only the padding inside each interval remains
+    assert ob.dp_min_padding(lens, u, 4)[0] == sum(b - s for s, b in zip(lens, [256, 512, 512, 768, 1024]))
+    # one bucket: everything is padded to the boundary that covers the longest sequence
+    assert ob.dp_min_padding(lens, u, 1) == (sum(1024 - s for s in lens), [1024])
+    # worked by hand: two buckets -> {512, 1024}: 412 + 212 + 212 + 324 + 24
+    assert ob.dp_min_padding(lens, u, 2) == (1184, [512, 1024])
+    with pytest.raises(ValueError):
+        ob.dp_min_padding([2000], u, 2)
+
+
+def test_host_implementation_equals_oracle():
+    for lens, u, R in batches():
+        total, _ = ob.dp_min_padding(lens, u, R)
+        bounds, pad = bd.lobra_dynamic_buckets(lens, u, R)
+        assert pad == (total if lens else 0)
+        assert len(bounds) <= R and bounds == sorted(bounds) and set(bounds) <= set(u)
+        if lens:
+            assert ob.padding_for(lens, bounds) == total
+
+
+def test_host_implementation_paper_scale_and_errors():
+    # boundaries every 256 tokens up to 16384, R = 16 (the paper's defaults), a long-tailed batch
+    rng = np.random.default_rng(0)
+    u = list(range(256, 16385, 256))
+    lens = np.clip(np.rint(rng.lognormal(6.0, 1.2, 4096)), 1, 16384).astype(int).tolist()
+    b16, p16 = bd.lobra_dynamic_buckets(lens, u, 16)
+    b8, p8 = bd.lobra_dynamic_buckets(lens, u, 8)
+    b64, p64 = bd.lobra_dynamic_buckets(lens, u, 64)
+    assert len(b16) == 16 and p64 <= p16 <= p8
+    assert p16 == ob.padding_for(lens, b16) and p8 == ob.padding_for(lens, b8)
+    assert p64 == sum(-(-s // 256) * 256 - s for s in lens)          # every occupied interval its own bucket
+    assert b16[-1] == -(-max(lens) // 256) * 256
+    assert bd.lib().lobra_dynamic_buckets(None, 0, None, 1, 1, None, None, None) == -1
+    with pytest.raises(bd.LobraError):
+        bd.lobra_dynamic_buckets([5], [4, 4], 1)
+    with pytest.raises(bd.LobraError):
+        bd.lobra_dynamic_buckets([9], [4, 8], 1)
+    assert bd.lobra_dynamic_buckets([], [4, 8], 2) == ([], 0)
