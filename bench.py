@@ -128,6 +128,23 @@ def main():
     tr.close()
     kern = {k: {"launches_per_step": len(v) // a.steps, "avg_ms": float(np.mean(v))} for k, v in per.items()}
 
+    # outside the step: the optimiser update that follows it, and the cost of building a batch plan
+    extras = {}
+    if p.R_tot:
+        cfg = bd.AdamConfig(0.9, 0.999, 1e-8, 0.0)
+        f = lambda shape: torch.zeros(shape, dtype=torch.float32, device=dp.dev)
+        lr = torch.full((p.n_tasks,), 1e-4, dtype=torch.float32, device=dp.dev)
+        stp = torch.ones((p.n_tasks,), dtype=torch.int32, device=dp.dev)
+        mA, vA, mB, vB = f(dp.dA.shape), f(dp.dA.shape), f(dp.dB.shape), f(dp.dB.shape)
+        wA, wB = dp.A.float(), dp.B.float()
+        a2, b2 = dp.A.clone(), dp.B.clone()
+        adam = lambda: bd.lobra_mlora_adam_step(dp.plan, cfg, lr, stp, None, dp.dA, dp.dB, wA, wB, mA, vA, mB, vB, a2, b2)
+        extras["adam_step_ms"] = timed(adam, 20, 3)[1]
+    t1 = time.perf_counter()
+    for _ in range(5):
+        bd.Plan.for_problem(p).close()
+    extras["plan_create_ms"] = (time.perf_counter() - t1) * 1e3 / 5
+
     cnt = p.task_tokens()
     tok_rank = float((cnt * p.ranks).sum())
     flops = p.useful_flops()
@@ -160,7 +177,7 @@ def main():
         "pct_of_peak": 100.0 * flops / (ms_wall * 1e-3) / 1e12 / peak,
         "ms_per_step_events": ms_ev, "ms_base_only": ms_base,
         "lora_overhead_pct": 100.0 * (ms_ev - ms_base) / ms_base,
-        "kernels": kern, "skinny_hbm": skinny, "roofline": roofline,
+        "kernels": kern, "skinny_hbm": skinny, "extras": extras, "roofline": roofline,
         "setup_s": time.perf_counter() - t0,
     }
     if not a.no_cpu_baseline:
