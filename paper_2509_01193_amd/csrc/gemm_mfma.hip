@@ -112,7 +112,7 @@ __device__ __forceinline__ void dma16(uint32_t lds_addr, const unsigned char* gb
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                  :
                  : "s"(la), "v"(voff), "s"(gu)
-                 : "memory");
+                 : "memory");     // m0 is a reserved register: the compiler re-loads it before each of its own uses
 }
 
 template <int N> __device__ __forceinline__ void wait_vmcnt()

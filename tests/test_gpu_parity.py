@@ -353,3 +353,44 @@ def test_fwd_bwd_under_hip_graph_capture():
         torch.cuda.synchronize()
         for a, b, name in zip(got, (dp.y, dp.dx, dp.dA, dp.dB), ("y", "dx", "dA", "dB")):
             assert torch.equal(a, b), (rep, name)
+
+
+def test_shared_input_projection_fusion_through_the_same_entry_point():
+    """q/k/v (or gate/up) LoRA-linears read the same x: one call with W concatenated along d_out, A_t
+    stacked along the rank and B_t block-diagonal computes all three layers at once."""
+    import torch
+    d_in, d = 320, 128
+    base = wl.make_config(2, "shuffled", d_in=d_in, d_out=d)
+    parts = []
+    for j in range(3):                                   # three layers on the same x and segment table
+        q = wl.make_custom("proj%d" % j, "bf16", d_in, d, base.ranks, base.seg_off, base.seg_task, 40 + j, s=base.s)
+        q.x = base.x
+        parts.append(q)
+    n, r = base.n_tasks, int(base.ranks[0])
+    fused = wl.make_custom("fused", "bf16", d_in, 3 * d, base.ranks * 3, base.seg_off, base.seg_task, 50, s=base.s)
+    fused.x = base.x
+    fused.W = np.concatenate([q.W for q in parts], axis=1)
+    fused.dy = np.concatenate([q.dy for q in parts], axis=1)
+    fused.A = np.concatenate([np.concatenate([q.A[t * r:(t + 1) * r] for q in parts]) for t in range(n)])
+    fused.B = np.zeros((3 * r * n, 3 * d), np.uint16)
+    for t in range(n):
+        for j, q in enumerate(parts):
+            fused.B[(3 * t + j) * r:(3 * t + j + 1) * r, j * d:(j + 1) * d] = q.B[t * r:(t + 1) * r]
+    df = bd.DeviceProblem(fused)
+    df.step()
+    dps = [bd.DeviceProblem(q) for q in parts]
+    for dq in dps:
+        dq.step()
+    torch.cuda.synchronize()
+    y = torch.cat([dq.y for dq in dps], dim=1).float()
+    assert ((df.y.float() - y).abs().max() / y.abs().max()).item() < 1e-2     # bf16 outputs, other summation order
+    dx = sum(dq.dx.float() for dq in dps)
+    assert ((df.dx.float() - dx).abs().max() / dx.abs().max()).item() < 2e-2
+    for t in range(n):
+        for j, dq in enumerate(dps):
+            rows = slice((3 * t + j) * r, (3 * t + j + 1) * r)
+            a, b = df.dA[rows], dq.dA[t * r:(t + 1) * r]
+            assert ((a - b).abs().max() / b.abs().max()).item() < 1e-2
+            a, b = df.dB[rows, j * d:(j + 1) * d], dq.dB[t * r:(t + 1) * r]
+            assert ((a - b).abs().max() / b.abs().max()).item() < 1e-2
+    check_problem(fused, label="fused qkv")            # and the fused call itself against the oracle
