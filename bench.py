@@ -67,6 +67,8 @@ def main():
     ap.add_argument("--order", default="shuffled", choices=["shuffled", "sorted"])
     ap.add_argument("--oracle-rows", type=int, default=8192)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-graph", action="store_true",
+                    help="time eager launches instead of replays of a HIP graph of one step")
     ap.add_argument("--pmc-probe", action="store_true",
                     help="for rocprofv3 --pmc runs: 2 steps and one plain device copy of x (a kernel of "
                          "known traffic that calibrates FETCH_SIZE / WRITE_SIZE), then exit")
@@ -110,11 +112,32 @@ def main():
         wall = (time.perf_counter() - w0) * 1e3 / steps
         return wall, e0.elapsed_time(e1) / steps
 
-    ms_wall, ms_ev = timed(dp.step, a.steps, a.warmup)
+    ms_wall_eager, ms_ev_eager = timed(dp.step, a.steps, a.warmup)
+    if a.no_graph:
+        ms_wall, ms_ev = ms_wall_eager, ms_ev_eager
+    else:
+        # one step (fwd + bwd, all kernels) captured once and replayed: the launch path of a training
+        # loop that does not want to pay host launch latency between dependent kernels
+        graph, side = torch.cuda.CUDAGraph(), torch.cuda.Stream()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                dp.step()
+        torch.cuda.synchronize()
+        ms_wall, ms_ev = timed(graph.replay, a.steps, a.warmup)
 
     # the same library with no adapters: base GEMM time, for the LoRA overhead figure
     base = dp.base_only()
-    ms_base_wall, ms_base = timed(base.step, max(a.steps // 2, 1), min(a.warmup, 3))
+    if a.no_graph:
+        ms_base_wall, ms_base = timed(base.step, max(a.steps // 2, 1), min(a.warmup, 3))
+    else:
+        base.step()
+        torch.cuda.synchronize()
+        bgraph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(bgraph, stream=side):
+                base.step()
+        torch.cuda.synchronize()
+        ms_base_wall, ms_base = timed(bgraph.replay, max(a.steps // 2, 1), min(a.warmup, 3))
 
     # per-kernel durations from HIP events on the launch stream, over `steps` more passes
     tr = bd.LaunchTrace(dp.plan, 32)
@@ -170,6 +193,7 @@ def main():
         "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms_wall,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": p.dtype, "data": "synthetic",
+        "launch": "eager" if a.no_graph else "hip_graph_replay", "ms_per_step_eager": ms_wall_eager,
         "config": {"workload": p.name, "T": p.T, "d_in": p.d_in, "d_out": p.d_out,
                    "n_tasks": p.n_tasks, "ranks": sorted(set(int(r) for r in p.ranks)),
                    "segments": p.S, "order": a.order},

@@ -407,6 +407,23 @@ void gemm_mfma_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const uint16_t
             const int32_t lo = max(pd.cseg_off[sg], row0), hi = min(pd.cseg_off[sg + 1], row_end);
             const int32_t r0 = pd.rank_off[t], r = pd.rank_off[t + 1] - r0;
             const int32_t rp = (r + 15) & ~15;
+            const bool mine = hi > wrow0 && lo < wrow0 + TM;   // wave-uniform: the segment crosses this wave's rows
+            // P fragments of up to four rank steps are fetched before the adapter slice is staged, so
+            // that their latency overlaps the staging and its barriers
+            constexpr int KG = 4;
+            u32x4 pv[KG][MB];
+            auto load_p = [&](int32_t kk0) {
+#pragma unroll
+                for (int q = 0; q < KG; ++q)
+#pragma unroll
+                    for (int mb = 0; mb < MB; ++mb) {
+                        const int32_t row = wrow0 + mb * 32 + l32;
+                        const int32_t kk = kk0 + 16 * q;
+                        pv[q][mb] = (mine && kk < rp && row >= lo && row < hi)
+                            ? *reinterpret_cast<const u32x4*>(P + size_t(row) * pd.r_pad + kk + 8 * lh) : zero4;
+                    }
+            };
+            load_p(0);
             __syncthreads();                        // everybody is done with what the LDS held before
             for (int32_t ch = tid; ch < rp * 32; ch += NT2) {
                 const int32_t kr = ch >> 5, c = ch & 31;
@@ -415,40 +432,39 @@ void gemm_mfma_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const uint16_t
                 *reinterpret_cast<u32x4*>(lds + kr * 512 + ((c ^ ((kr & 3) << 2)) << 4)) = v;
             }
             __syncthreads();
-            if (hi <= wrow0 || lo >= wrow0 + TM) continue;     // wave-uniform; the barriers are above
+            if (!mine) continue;                    // wave-uniform; the barriers are above
             const int s16 = lane & 15, g16 = lane >> 4;
-            for (int32_t kk = 0; kk < rp; kk += 16) {
-                u32x4 pv[MB];
+            for (int32_t kk0 = 0; kk0 < rp; kk0 += 16 * KG) {
+                if (kk0 > 0) load_p(kk0);
 #pragma unroll
-                for (int mb = 0; mb < MB; ++mb) {
-                    const int32_t row = wrow0 + mb * 32 + l32;
-                    pv[mb] = (row >= lo && row < hi)
-                        ? *reinterpret_cast<const u32x4*>(P + size_t(row) * pd.r_pad + kk + 8 * lh) : zero4;
-                }
-                bf16x8 wf[NB];
-                const int krow = kk + 8 * (g16 >> 1) + (s16 >> 2);
+                for (int q = 0; q < KG; ++q) {
+                    const int32_t kk = kk0 + 16 * q;
+                    if (kk >= rp) break;            // wave-uniform
+                    bf16x8 wf[NB];
+                    const int krow = kk + 8 * (g16 >> 1) + (s16 >> 2);
 #pragma unroll
-                for (int nb = 0; nb < NB; ++nb) {
-                    const int n = wn * TN + nb * 32 + 16 * (g16 & 1) + 4 * (s16 & 3);
-                    const int c = (n >> 3) ^ ((krow & 3) << 2);
-                    const unsigned char* p0 = lds + krow * 512 + c * 16 + (n & 7) * 2;
-                    const s16x4 vlo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                        (s16x4 __attribute__((address_space(3)))*)(p0));
-                    const s16x4 vhi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                        (s16x4 __attribute__((address_space(3)))*)(p0 + 4 * 512));
-                    union { s16x4 h[2]; bf16x8 b; } cv;
-                    cv.h[0] = vlo;
-                    cv.h[1] = vhi;
-                    wf[nb] = cv.b;
-                }
+                    for (int nb = 0; nb < NB; ++nb) {
+                        const int n = wn * TN + nb * 32 + 16 * (g16 & 1) + 4 * (s16 & 3);
+                        const int c = (n >> 3) ^ ((krow & 3) << 2);
+                        const unsigned char* p0 = lds + krow * 512 + c * 16 + (n & 7) * 2;
+                        const s16x4 vlo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                            (s16x4 __attribute__((address_space(3)))*)(p0));
+                        const s16x4 vhi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                            (s16x4 __attribute__((address_space(3)))*)(p0 + 4 * 512));
+                        union { s16x4 h[2]; bf16x8 b; } cv;
+                        cv.h[0] = vlo;
+                        cv.h[1] = vhi;
+                        wf[nb] = cv.b;
+                    }
 #pragma unroll
-                for (int mb = 0; mb < MB; ++mb) {
-                    const int32_t rb = wrow0 + mb * 32;
-                    if (hi <= rb || lo >= rb + 32) continue;        // wave-uniform
-                    const bf16x8 pf = as_bf16x8(pv[mb]);
+                    for (int mb = 0; mb < MB; ++mb) {
+                        const int32_t rb = wrow0 + mb * 32;
+                        if (hi <= rb || lo >= rb + 32) continue;        // wave-uniform
+                        const bf16x8 pf = as_bf16x8(pv[q][mb]);
 #pragma unroll
-                    for (int nb = 0; nb < NB; ++nb)
-                        acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[nb], pf, acc[mb][nb], 0, 0, 0);
+                        for (int nb = 0; nb < NB; ++nb)
+                            acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[nb], pf, acc[mb][nb], 0, 0, 0);
+                    }
                 }
             }
         }
