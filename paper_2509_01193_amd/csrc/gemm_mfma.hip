@@ -163,6 +163,15 @@ void gemm_mfma_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const uint16_t
     }
     const int32_t row0 = tile_m * BM, col0 = tile_n * BN;
 
+    // The table entries of the first segment that crosses this tile are read now: after the main loop
+    // (whose copies are opaque to the compiler) the chain of dependent loads would sit in front of the
+    // epilogue.  Most tiles lie inside one segment.
+    const int32_t sg_first = pd.rowblk_seg[row0 / kRowBlock];
+    const int32_t sf_lo = pd.cseg_off[sg_first], sf_hi = pd.cseg_off[sg_first + 1];
+    const int32_t sf_task = pd.cseg_task[sg_first];
+    const int32_t sf_r0 = sf_task >= 0 ? pd.rank_off[sf_task] : 0;
+    const int32_t sf_r1 = sf_task >= 0 ? pd.rank_off[sf_task + 1] : 0;
+
     auto zs = [&](int buf) { return lds + buf * ZT_BYTES; };
     auto ws = [&](int buf) { return lds + 2 * ZT_BYTES + buf * WT_BYTES; };
 
@@ -400,17 +409,21 @@ void gemm_mfma_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const uint16_t
         constexpr int NT2 = 64 * WM * WN;
         const int32_t row_end = min(row0 + BM, T);
         const int32_t wrow0 = row0 + wm * TM;       // the wave's rows are wrow0 .. wrow0 + TM - 1
-        int32_t sg = pd.rowblk_seg[row0 / kRowBlock];
-        for (; sg < pd.nseg && pd.cseg_off[sg] < row_end; ++sg) {
-            const int32_t t = pd.cseg_task[sg];
+        for (int32_t sg = sg_first; sg < pd.nseg; ++sg) {
+            const bool cached = sg == sg_first;
+            const int32_t seg_lo = cached ? sf_lo : pd.cseg_off[sg];
+            if (seg_lo >= row_end) break;
+            const int32_t t = cached ? sf_task : pd.cseg_task[sg];
             if (t < 0) continue;
-            const int32_t lo = max(pd.cseg_off[sg], row0), hi = min(pd.cseg_off[sg + 1], row_end);
-            const int32_t r0 = pd.rank_off[t], r = pd.rank_off[t + 1] - r0;
+            const int32_t seg_hi = cached ? sf_hi : pd.cseg_off[sg + 1];
+            const int32_t lo = max(seg_lo, row0), hi = min(seg_hi, row_end);
+            const int32_t r0 = cached ? sf_r0 : pd.rank_off[t];
+            const int32_t r = (cached ? sf_r1 : pd.rank_off[t + 1]) - r0;
             const int32_t rp = (r + 15) & ~15;
             const bool mine = hi > wrow0 && lo < wrow0 + TM;   // wave-uniform: the segment crosses this wave's rows
-            // P fragments of up to four rank steps are fetched before the adapter slice is staged, so
+            // P fragments of up to two rank steps are fetched before the adapter slice is staged, so
             // that their latency overlaps the staging and its barriers
-            constexpr int KG = 4;
+            constexpr int KG = 2;
             u32x4 pv[KG][MB];
             auto load_p = [&](int32_t kk0) {
 #pragma unroll
@@ -424,12 +437,31 @@ void gemm_mfma_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const uint16_t
                     }
             };
             load_p(0);
+            // the adapter slice is rp * 32 chunks of 16 bytes; the first MCH * NT2 of them (ranks up to
+            // 64 with 512 threads) are fetched before the barrier that frees the LDS and written after it
+            constexpr int MCH = 4;
+            u32x4 mreg[MCH];
+            auto fetch_m = [&](int32_t base) {
+#pragma unroll
+                for (int q = 0; q < MCH; ++q) {
+                    const int32_t ch = base + tid + q * NT2, kr = ch >> 5, n = col0 + 8 * (ch & 31);
+                    mreg[q] = (ch < rp * 32 && kr < r && n < N)
+                                  ? *reinterpret_cast<const u32x4*>(M + size_t(r0 + kr) * N + n) : zero4;
+                }
+            };
+            auto store_m = [&](int32_t base) {
+#pragma unroll
+                for (int q = 0; q < MCH; ++q) {
+                    const int32_t ch = base + tid + q * NT2, kr = ch >> 5, c = ch & 31;
+                    if (ch < rp * 32) *reinterpret_cast<u32x4*>(lds + kr * 512 + ((c ^ ((kr & 3) << 2)) << 4)) = mreg[q];
+                }
+            };
+            fetch_m(0);
             __syncthreads();                        // everybody is done with what the LDS held before
-            for (int32_t ch = tid; ch < rp * 32; ch += NT2) {
-                const int32_t kr = ch >> 5, c = ch & 31;
-                const int32_t n = col0 + 8 * c;
-                const u32x4 v = (kr < r && n < N) ? *reinterpret_cast<const u32x4*>(M + size_t(r0 + kr) * N + n) : zero4;
-                *reinterpret_cast<u32x4*>(lds + kr * 512 + ((c ^ ((kr & 3) << 2)) << 4)) = v;
+            store_m(0);
+            for (int32_t base = MCH * NT2; base < rp * 32; base += MCH * NT2) {
+                fetch_m(base);
+                store_m(base);
             }
             __syncthreads();
             if (!mine) continue;                    // wave-uniform; the barriers are above
