@@ -29,6 +29,8 @@
 // Tuning macros (defaults are what the measurements chose): LOBRA_GEMM_WM/WN wave grid, LOBRA_GEMM_DBK/
 // DST K-tile width and stage count of the DMA path, LOBRA_GEMM_ISSUE_AT, LOBRA_GEMM_GM tile-rows per
 // sweep of the XCD-aware tile order, LOBRA_GEMM_NT_STORE, LOBRA_GEMM_DMA.
+#include <atomic>
+
 #include "kernels.h"
 
 #ifndef LOBRA_GEMM_DMA
@@ -542,12 +544,17 @@ static hipError_t launch_gemm(const PlanDev& pd, const void* Z, const void* W, c
                               int32_t tiles_m, int32_t tiles_n, hipStream_t st)
 {
     constexpr int bytes = lds_bytes<W_KN, WN, DMA>();
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mfma_kernel<W_KN, WM, WN, DMA>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    // the kernel needs more dynamic LDS than the default limit: raise it once per device
+    static std::atomic<uint64_t> raised{0};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const uint64_t bit = uint64_t(1) << (dev & 63);
+    if (!(raised.load(std::memory_order_acquire) & bit)) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mfma_kernel<W_KN, WM, WN, DMA>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
         if (e != hipSuccess) return e;
-        attr_set = true;
+        raised.fetch_or(bit, std::memory_order_release);
     }
     gemm_mfma_kernel<W_KN, WM, WN, DMA><<<dim3(uint32_t(tiles_m) * uint32_t(tiles_n)), 64 * WM * WN, bytes, st>>>(
         pd, (const uint16_t*)Z, (const uint16_t*)W, (const uint16_t*)P, (const uint16_t*)M, (uint16_t*)C,

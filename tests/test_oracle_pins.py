@@ -320,7 +320,8 @@ def test_planted_mistake_is_caught(name, old, new, monkeypatch):
     with tempfile.TemporaryDirectory() as d:
         c, so = os.path.join(d, "m.c"), os.path.join(d, "m.so")
         open(c, "w").write(src.replace(old, new, 1))
-        subprocess.run(["gcc", "-O1", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-o", so, c], check=True)
+        subprocess.run(["gcc", "-O1", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-o", so, c,
+                        orc_mod._SRC_ADAM, "-lm"], check=True)
         monkeypatch.setattr(orc_mod, "_handle", orc_mod._bind(ctypes.CDLL(so)))
         caught = []
         for pin in PINS:
