@@ -228,46 +228,54 @@ void gemm_mfma_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const uint16_t
 #pragma unroll
             for (int j = 0; j < NBZ; ++j) dma16(st + DZT_BYTES + (wave + NW * j) * 1024, wb, wvo[j]);
         };
-        auto compute = [&](int stage, int ks0, int ks1) {
+        // operand fragments of K step ks of a stage
+        auto load_frags = [&](int stage, int ks, bf16x8 (&zf)[MB], bf16x8 (&wf)[NB]) {
             const unsigned char* zs = lds + stage * DSTAGE_BYTES;
             const unsigned char* ws = zs + DZT_BYTES;
 #pragma unroll
+            for (int mb = 0; mb < MB; ++mb) {
+                const int row = wm * TM + mb * 32 + l32;
+                zf[mb] = *reinterpret_cast<const bf16x8*>(zs + row * (DBK * 2) + ((2 * ks + lh) ^ fz(row)) * 16);
+            }
+            if (W_KN) {
+                const int s = lane & 15, g = lane >> 4;
+                const int krow = 16 * ks + 8 * (g >> 1) + (s >> 2);
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) {
+                    const int n = wn * TN + nb * 32 + 16 * (g & 1) + 4 * (s & 3);
+                    const int c = (n >> 3) ^ ((krow & 3) << 2);
+                    const unsigned char* p0 = ws + krow * 512 + c * 16 + (n & 7) * 2;
+                    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                        (s16x4 __attribute__((address_space(3)))*)(p0));
+                    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                        (s16x4 __attribute__((address_space(3)))*)(p0 + 4 * 512));
+                    union { s16x4 h[2]; bf16x8 b; } cv;
+                    cv.h[0] = lo;
+                    cv.h[1] = hi;
+                    wf[nb] = cv.b;
+                }
+            } else {
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) {
+                    const int row = wn * TN + nb * 32 + l32;
+                    wf[nb] = *reinterpret_cast<const bf16x8*>(ws + row * (DBK * 2) + ((2 * ks + lh) ^ fz(row)) * 16);
+                }
+            }
+        };
+        auto mma = [&](const bf16x8 (&zf)[MB], const bf16x8 (&wf)[NB]) {
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb)
+                    acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[nb], zf[mb], acc[mb][nb], 0, 0, 0);
+        };
+        // K steps ks0 .. ks1-1 of a stage (the compiler interleaves the LDS reads of a step with the MFMAs of the one before)
+        auto compute = [&](int stage, int ks0, int ks1) {
+#pragma unroll
             for (int ks = ks0; ks < ks1; ++ks) {
                 bf16x8 zf[MB], wf[NB];
-#pragma unroll
-                for (int mb = 0; mb < MB; ++mb) {
-                    const int row = wm * TM + mb * 32 + l32;
-                    zf[mb] = *reinterpret_cast<const bf16x8*>(zs + row * (DBK * 2) + ((2 * ks + lh) ^ fz(row)) * 16);
-                }
-                if (W_KN) {
-                    const int s = lane & 15, g = lane >> 4;
-                    const int krow = 16 * ks + 8 * (g >> 1) + (s >> 2);
-#pragma unroll
-                    for (int nb = 0; nb < NB; ++nb) {
-                        const int n = wn * TN + nb * 32 + 16 * (g & 1) + 4 * (s & 3);
-                        const int c = (n >> 3) ^ ((krow & 3) << 2);
-                        const unsigned char* p0 = ws + krow * 512 + c * 16 + (n & 7) * 2;
-                        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                            (s16x4 __attribute__((address_space(3)))*)(p0));
-                        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                            (s16x4 __attribute__((address_space(3)))*)(p0 + 4 * 512));
-                        union { s16x4 h[2]; bf16x8 b; } cv;
-                        cv.h[0] = lo;
-                        cv.h[1] = hi;
-                        wf[nb] = cv.b;
-                    }
-                } else {
-#pragma unroll
-                    for (int nb = 0; nb < NB; ++nb) {
-                        const int row = wn * TN + nb * 32 + l32;
-                        wf[nb] = *reinterpret_cast<const bf16x8*>(ws + row * (DBK * 2) + ((2 * ks + lh) ^ fz(row)) * 16);
-                    }
-                }
-#pragma unroll
-                for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-                    for (int nb = 0; nb < NB; ++nb)
-                        acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[nb], zf[mb], acc[mb][nb], 0, 0, 0);
+                load_frags(stage, ks, zf, wf);
+                mma(zf, wf);
             }
         };
         constexpr int NPW = 2 * NBZ;                // copies per wave and K tile
