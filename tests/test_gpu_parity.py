@@ -263,6 +263,12 @@ def test_mfma_kernels_against_plain_kernels_every_element_full_size():
 FULL_ROWS = {2: 1024, 3: 768, 4: 96, 5: 256}
 
 
+def test_full_size_workload2_with_unit_variance_activations():
+    """Sensitivity row: x ~ N(0, 1) instead of N(0, 0.02) (the workload text fixes x only for workload 1)."""
+    p = wl.make_config(2, "sorted", std_x=1.0)
+    check_problem(p, rows=sample_rows(p, 512, seed=3), label="x~N(0,1)")
+
+
 @pytest.mark.parametrize("cfg", [2, 3, 5, 4])
 def test_full_size_workload_sampled_rows(cfg):
     p = wl.make_config(cfg, "shuffled")
