@@ -41,6 +41,9 @@
 #include <stddef.h>
 #include <stdint.h>
 
+/* The library is built with hidden visibility; only the entry points below are exported. */
+#define LOBRA_API __attribute__((visibility("default")))
+
 #ifdef __cplusplus
 extern "C" {
 #endif
@@ -99,21 +102,21 @@ typedef struct {
 typedef struct lobra_mlora_plan lobra_mlora_plan;
 
 /* Host-only argument check of a descriptor (the checks plan_create performs). */
-lobra_status lobra_mlora_validate(const lobra_mlora_desc *desc);
+LOBRA_API lobra_status lobra_mlora_validate(const lobra_mlora_desc *desc);
 
 /* Build a plan on the current HIP device.  Allocates one small device buffer
  * (a few bytes per 32 tokens) with hipMalloc and fills it with a blocking copy.
  * *out is set only on success. */
-lobra_status lobra_mlora_plan_create(const lobra_mlora_desc *desc, uint32_t plan_flags,
+LOBRA_API lobra_status lobra_mlora_plan_create(const lobra_mlora_desc *desc, uint32_t plan_flags,
                                      lobra_mlora_plan **out);
 
 /* Frees the plan and its device buffer.  The caller makes sure no launched work still uses it.
  * NULL is accepted. */
-lobra_status lobra_mlora_plan_destroy(lobra_mlora_plan *plan);
+LOBRA_API lobra_status lobra_mlora_plan_destroy(lobra_mlora_plan *plan);
 
 /* Buffer sizes in bytes (each may be 0): h_save = the saved down-projected activations that
  * fwd can hand to bwd; fwd_ws / bwd_ws = scratch for one call.  Any out pointer may be NULL. */
-lobra_status lobra_mlora_plan_sizes(const lobra_mlora_plan *plan, size_t *h_save_bytes,
+LOBRA_API lobra_status lobra_mlora_plan_sizes(const lobra_mlora_plan *plan, size_t *h_save_bytes,
                                     size_t *fwd_ws_bytes, size_t *bwd_ws_bytes);
 
 /* Introspection of the host side of a plan (tests, debugging).  Copies up to `capacity`
@@ -125,10 +128,12 @@ lobra_status lobra_mlora_plan_sizes(const lobra_mlora_plan *plan, size_t *h_save
  *   LOBRA_Q_TOKEN_BLOCKS n x {row0, nrows, task, rank_row0}: runs of <= 32 tokens of one adapter
  *                        segment, grouped by task; rank_row0 = rank_off[task]
  *   LOBRA_Q_GRAD_CHUNKS  n x {block_begin, block_end, task, partial_row0}: reduction work items
- *   LOBRA_Q_TASK_CHUNKS  [n_tasks+1]: prefix of chunks per task */
+ *   LOBRA_Q_TASK_CHUNKS  [n_tasks+1]: prefix of chunks per task
+ *   LOBRA_Q_BLOCK_RUNS   [n_runs+1]: token blocks run[k] .. run[k+1]-1 (all of one task) are
+ *                        projected by one workgroup */
 enum { LOBRA_Q_SEGMENTS = 0, LOBRA_Q_ROWBLOCK_SEG = 1, LOBRA_Q_TOKEN_BLOCKS = 2,
-       LOBRA_Q_GRAD_CHUNKS = 3, LOBRA_Q_TASK_CHUNKS = 4 };
-lobra_status lobra_mlora_plan_query(const lobra_mlora_plan *plan, int32_t what, int32_t *out,
+       LOBRA_Q_GRAD_CHUNKS = 3, LOBRA_Q_TASK_CHUNKS = 4, LOBRA_Q_BLOCK_RUNS = 5 };
+LOBRA_API lobra_status lobra_mlora_plan_query(const lobra_mlora_plan *plan, int32_t what, int32_t *out,
                                     size_t capacity, size_t *count);
 
 /* Forward: y = x W + s_t (A_t x) B_t for every token (section 2.1; fused batch, section 1).
@@ -140,7 +145,7 @@ lobra_status lobra_mlora_plan_query(const lobra_mlora_plan *plan, int32_t what, 
  *   ws, ws_bytes  : device scratch of at least fwd_ws_bytes (NULL allowed when that is 0)
  *   hip_stream    : hipStream_t (NULL = default stream); work is enqueued, not awaited
  * x, W, A, B, s are read only; y and h_save are overwritten. */
-lobra_status lobra_mlora_fwd(const lobra_mlora_plan *plan, const void *x, const void *W,
+LOBRA_API lobra_status lobra_mlora_fwd(const lobra_mlora_plan *plan, const void *x, const void *W,
                              const void *A, const void *B, const float *s, void *y,
                              void *h_save, void *ws, size_t ws_bytes, void *hip_stream);
 
@@ -153,7 +158,7 @@ lobra_status lobra_mlora_fwd(const lobra_mlora_plan *plan, const void *x, const 
  *             tokens become 0), or added to with LOBRA_FLAG_ACCUMULATE_GRADS
  *   ws      : device scratch of at least bwd_ws_bytes
  * The reductions run in a fixed order: results are bit-identical from run to run. */
-lobra_status lobra_mlora_bwd(const lobra_mlora_plan *plan, const void *x, const void *W,
+LOBRA_API lobra_status lobra_mlora_bwd(const lobra_mlora_plan *plan, const void *x, const void *W,
                              const void *A, const void *B, const float *s, const void *dy,
                              const void *h_saved, void *dx, float *dA, float *dB,
                              uint32_t flags, void *ws, size_t ws_bytes, void *hip_stream);
@@ -161,7 +166,7 @@ lobra_status lobra_mlora_bwd(const lobra_mlora_plan *plan, const void *x, const 
 /* Index probe: writes the task of every token (device int32 [T], -1 = none) and the number
  * of tokens per task (device int64 [n_tasks]) with the same device-side table walk the
  * kernels use.  Either output may be NULL. */
-lobra_status lobra_token_task_map(const lobra_mlora_plan *plan, int32_t *out_task,
+LOBRA_API lobra_status lobra_token_task_map(const lobra_mlora_plan *plan, int32_t *out_task,
                                   int64_t *out_count, void *hip_stream);
 
 /* Fused multi-adapter Adam step: the update that follows the backward pass, for the adapters of
@@ -182,7 +187,7 @@ lobra_status lobra_token_task_map(const lobra_mlora_plan *plan, int32_t *out_tas
 typedef struct {
     float beta1, beta2, eps, weight_decay;
 } lobra_adam_config;
-lobra_status lobra_mlora_adam_step(const lobra_mlora_plan *plan, const lobra_adam_config *cfg,
+LOBRA_API lobra_status lobra_mlora_adam_step(const lobra_mlora_plan *plan, const lobra_adam_config *cfg,
                                    const float *lr, const int32_t *step, const float *grad_scale,
                                    const float *dA, const float *dB, float *master_A,
                                    float *master_B, float *m_A, float *v_A, float *m_B, float *v_B,
@@ -200,7 +205,7 @@ lobra_status lobra_mlora_adam_step(const lobra_mlora_plan *plan, const lobra_ada
  *                       largest one is the smallest candidate that covers the longest sequence
  *   out_padding       : total pad tokens of the batch under the chosen boundaries (may be NULL)
  * LOBRA_ERR_SHAPE for U < 1, R < 1, a non-increasing table or a length outside the table. */
-lobra_status lobra_dynamic_buckets(const int32_t *seq_len, int64_t n_seq, const int32_t *bounds,
+LOBRA_API lobra_status lobra_dynamic_buckets(const int32_t *seq_len, int64_t n_seq, const int32_t *bounds,
                                    int32_t U, int32_t R, int32_t *out_bounds, int32_t *out_n,
                                    int64_t *out_padding);
 
@@ -214,15 +219,15 @@ lobra_status lobra_dynamic_buckets(const int32_t *seq_len, int64_t n_seq, const 
  * A plan with a trace attached must not be used from two threads at once. */
 enum { LOBRA_K_SHRINK = 1, LOBRA_K_GEMM = 2, LOBRA_K_GRAD_STAGE1 = 3, LOBRA_K_GRAD_STAGE2 = 4,
        LOBRA_K_TOKEN_TASK = 5, LOBRA_K_ADAM = 6 };
-lobra_status lobra_mlora_plan_set_trace(lobra_mlora_plan *plan, void *const *events,
+LOBRA_API lobra_status lobra_mlora_plan_set_trace(lobra_mlora_plan *plan, void *const *events,
                                         int32_t n_pairs, int32_t *kernel_ids,
                                         int32_t *n_launched);
 
 /* Static, never NULL. */
-const char *lobra_status_string(lobra_status st);
+LOBRA_API const char *lobra_status_string(lobra_status st);
 
 /* major * 10000 + minor * 100 + patch */
-int lobra_version(void);
+LOBRA_API int lobra_version(void);
 
 #ifdef __cplusplus
 }

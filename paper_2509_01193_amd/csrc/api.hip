@@ -28,6 +28,7 @@ PlanDev device_view(const Plan& p)
     d.task_chunk_off = b + p.o_task_chunk;
     d.rank_off = b + p.o_rank_off;
     d.task_tb_off = b + p.o_task_tb;
+    d.sb_off = b + p.o_sb;
     d.T = int32_t(p.desc.T);
     d.d_in = p.desc.d_in;
     d.d_out = p.desc.d_out;
@@ -38,6 +39,8 @@ PlanDev device_view(const Plan& p)
     d.r_max = p.r_max;
     d.r_pad = p.r_pad;
     d.R_tot = p.R_tot;
+    d.nsb = int32_t(p.sb_off.size()) - 1;
+    d.shrink_group = p.shrink_group;
     return d;
 }
 
@@ -171,6 +174,10 @@ lobra_status lobra_mlora_plan_query(const lobra_mlora_plan* plan, int32_t what, 
     case LOBRA_Q_TASK_CHUNKS:
         src = plan->task_chunk_off.data();
         n = plan->task_chunk_off.size();
+        break;
+    case LOBRA_Q_BLOCK_RUNS:
+        src = plan->sb_off.data();
+        n = plan->sb_off.size();
         break;
     default:
         return LOBRA_ERR_SHAPE;

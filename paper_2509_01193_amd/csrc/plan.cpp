@@ -107,6 +107,24 @@ lobra_status build_host_plan(const lobra_mlora_desc* d, uint32_t flags, Plan* p)
             }
         }
 
+        // 3b. runs of token blocks that one workgroup of the rank-r projection handles.  A run
+        //     shares the adapter rows it loads, so longer runs cut the adapter traffic (r_t rows
+        //     per 32 token rows); they are used when the ranks are large and the batch still
+        //     yields a few workgroups per compute unit.
+        {
+            // token-weighted mean rank: runs of two pay off when most of the work is at rank >= 48
+            int64_t wsum = 0;
+            const int64_t ntb_all = p->task_tb_off[n];
+            for (int32_t t = 0; t < n; ++t)
+                wsum += int64_t(p->task_tb_off[t + 1] - p->task_tb_off[t]) * (p->rank_off[t + 1] - p->rank_off[t]);
+            const int32_t g = (ntb_all >= 2 * 512 && wsum >= 48 * ntb_all) ? 2 : 1;
+            p->shrink_group = g;
+            p->sb_off.assign(1, 0);
+            for (int32_t t = 0; t < n; ++t)
+                for (int32_t b = p->task_tb_off[t]; b < p->task_tb_off[t + 1]; b += g)
+                    p->sb_off.push_back(std::min(b + g, p->task_tb_off[t + 1]));
+        }
+
         // 4. reduction chunks: runs of token blocks of one task.  The chunk length is chosen so
         //    that (chunks x 128-column tiles) gives roughly a thousand workgroups, within
         //    [4, 64] token blocks; fewer, longer chunks mean less partial-sum traffic.
@@ -172,6 +190,7 @@ std::vector<int32_t> pack_blob(Plan* p)
     p->o_task_chunk = put(p->task_chunk_off.data(), p->task_chunk_off.size());
     p->o_rank_off = put(p->rank_off.data(), p->rank_off.size());
     p->o_task_tb = put(p->task_tb_off.data(), p->task_tb_off.size());
+    p->o_sb = put(p->sb_off.data(), p->sb_off.size());
     while (blob.size() % 4) blob.push_back(0);
     return blob;
 }

@@ -34,6 +34,8 @@ struct Plan {
     std::vector<int32_t> rowblk_seg;    // [ceil(T/32)]
     std::vector<TokenBlock> tb;         // grouped by task, token order inside a task
     std::vector<int32_t> task_tb_off;   // [n_tasks+1]
+    std::vector<int32_t> sb_off;        // [nsb+1] runs of <= shrink_group token blocks of one task
+    int32_t shrink_group = 1;           // token blocks that one shrink workgroup handles
     std::vector<GradChunk> chunks;      // grouped by task
     std::vector<int32_t> task_chunk_off;// [n_tasks+1]
     int32_t part_rows = 0;              // rows of the partial-sum buffer = sum over chunks of r_t
@@ -56,7 +58,7 @@ struct Plan {
     size_t blob_bytes = 0;
     // offsets (in int32 units) of the lists inside the blob
     size_t o_cseg_off = 0, o_cseg_task = 0, o_rowblk = 0, o_tb = 0, o_chunks = 0,
-           o_task_chunk = 0, o_rank_off = 0, o_task_tb = 0;
+           o_task_chunk = 0, o_rank_off = 0, o_task_tb = 0, o_sb = 0;
 };
 
 lobra_status validate(const lobra_mlora_desc* d);

@@ -25,124 +25,150 @@ __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v)
 }  // namespace
 
 // -------------------------------------------------------------------------------------------------
-// shrink: one workgroup per token block (<= 32 tokens of one task), 4 waves split K.
-// v_mfma_f32_16x16x32_bf16 with the MFMA "A" operand = 16 rank rows of M_t and the "B" operand =
-// 16 token rows of Z, so a lane ends up with 4 consecutive ranks of one token.  K is walked in
-// slabs of 128 = 4 MFMA steps of 32: in step q lane (row, kg) loads the 8 elements
+// shrink: one workgroup per run of NTB token blocks (<= 32 tokens each, all of one task), 4 waves
+// split K.  v_mfma_f32_16x16x32_bf16 with the MFMA "A" operand = 16 rank rows of M_t and the "B"
+// operand = 16 token rows of Z, so a lane ends up with 4 consecutive ranks of one token.  K is
+// walked in slabs of 128 = 4 MFMA steps of 32: in step q lane (row, kg) loads the 8 elements
 // slab + 32 q + 8 kg .. + 7 of its row, so the four lanes of a row read one 64-byte sector per
-// load instruction and a whole 256-byte run per slab.
+// load instruction and a whole 256-byte run per slab.  The rank rows of a slab are loaded once
+// for all token blocks of the run (this matters when r_t is large: r_t adapter rows per 32 token
+// rows); rank blocks beyond the task's rank are skipped.
 // -------------------------------------------------------------------------------------------------
-#ifndef LOBRA_SHRINK_WAVES
-#define LOBRA_SHRINK_WAVES 4
-#endif
-template <int NRB, int NWV>   // rank blocks of 16 handled (r_t <= 16 NRB); waves that split K
+// NRB: rank blocks of 16 (r_t <= 16 NRB); NWV: waves; NTB: token blocks per run; DEPTH: slabs in
+// flight per wave
+template <int NRB, int NWV, int NTB, int DEPTH>
 __global__ __launch_bounds__(64 * NWV) void shrink_mfma_kernel(PlanDev pd, const uint16_t* __restrict__ Z,
                                                           const uint16_t* __restrict__ M,
                                                           const float* __restrict__ s,
                                                           uint16_t* __restrict__ P_tok,
-                                                          uint16_t* __restrict__ P_blk, int32_t D,
-                                                          int32_t tb_begin)
+                                                          uint16_t* __restrict__ P_blk, int32_t D)
 {
     __shared__ float red[NWV][2][NRB][64][4];   // [wave][token half][rank block][lane][4]
-    const int32_t bi = tb_begin + blockIdx.x;
-    const TokenBlock b = pd.tb[bi];
-    const int32_t r = pd.rank_off[b.task + 1] - b.rank_row0;
+    const int32_t tb0 = NTB == 1 ? int32_t(blockIdx.x) : pd.sb_off[blockIdx.x];
+    const int32_t cnt = NTB == 1 ? 1 : pd.sb_off[blockIdx.x + 1] - tb0;
+    TokenBlock b[NTB];
+#pragma unroll
+    for (int t = 0; t < NTB; ++t) b[t] = pd.tb[tb0 + min(t, cnt - 1)];
+    const int32_t rank_row0 = b[0].rank_row0;
+    const int32_t r = pd.rank_off[b[0].task + 1] - rank_row0;
+    const int32_t nrb_t = (r + 15) >> 4;        // rank blocks this task needs (uniform)
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int j = lane & 15, kg = lane >> 4;
     const u32x4 zero4 = {0u, 0u, 0u, 0u};
 
-    f32x4 acc[2][NRB];
+    f32x4 acc[NTB][2][NRB];
 #pragma unroll
-    for (int h = 0; h < 2; ++h)
+    for (int t = 0; t < NTB; ++t)
 #pragma unroll
-        for (int rb = 0; rb < NRB; ++rb) acc[h][rb] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int rb = 0; rb < NRB; ++rb) acc[t][h][rb] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    // rows beyond the block repeat its last row (their results are never stored)
-    const uint16_t* zrow[2];
+    // rows beyond a block repeat its last row (their results are never stored)
+    const uint16_t* zrow[NTB][2];
+    bool two_halves[NTB];
 #pragma unroll
-    for (int h = 0; h < 2; ++h)
-        zrow[h] = Z + size_t(b.row0 + min(16 * h + j, b.nrows - 1)) * D;
-    const bool two_halves = b.nrows > 16;
+    for (int t = 0; t < NTB; ++t) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+            zrow[t][h] = Z + size_t(b[t].row0 + min(16 * h + j, b[t].nrows - 1)) * D;
+        two_halves[t] = b[t].nrows > 16;
+    }
+    const uint16_t* mrow[NRB];
+#pragma unroll
+    for (int rb = 0; rb < NRB; ++rb) mrow[rb] = M + size_t(rank_row0 + min(16 * rb + j, r - 1)) * D;
 
-    // operands of one slab: 4 steps x (2 token halves of Z, NRB rank blocks of M)
-    struct Slab { u32x4 zv[2][4], mv[NRB][4]; };
+    // operands of one slab: 4 steps x (2 token halves of Z per block, NRB rank blocks of M)
+    struct Slab { u32x4 zv[NTB][2][4], mv[NRB][4]; };
     auto load = [&](Slab& sl, int32_t slab) {
         const int32_t k = slab + 8 * kg;
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             const bool kin = k + 32 * q < D;
 #pragma unroll
-            for (int h = 0; h < 2; ++h)
-                sl.zv[h][q] = (kin && (h == 0 || two_halves))
-                                  ? *reinterpret_cast<const u32x4*>(zrow[h] + k + 32 * q) : zero4;
-#pragma unroll
             for (int rb = 0; rb < NRB; ++rb)
-                sl.mv[rb][q] = (kin && 16 * rb + j < r)
-                                   ? *reinterpret_cast<const u32x4*>(M + size_t(b.rank_row0 + 16 * rb + j) * D + k + 32 * q)
-                                   : zero4;
+                if (rb < nrb_t)
+                    sl.mv[rb][q] = (kin && 16 * rb + j < r)
+                                       ? *reinterpret_cast<const u32x4*>(mrow[rb] + k + 32 * q) : zero4;
+#pragma unroll
+            for (int t = 0; t < NTB; ++t)
+                if (t < cnt)
+#pragma unroll
+                    for (int h = 0; h < 2; ++h)
+                        sl.zv[t][h][q] = (kin && (h == 0 || two_halves[t]))
+                                             ? *reinterpret_cast<const u32x4*>(zrow[t][h] + k + 32 * q) : zero4;
         }
     };
     auto mac = [&](const Slab& sl) {
 #pragma unroll
-        for (int q = 0; q < 4; ++q)
+        for (int t = 0; t < NTB; ++t)
+            if (t < cnt)
 #pragma unroll
-            for (int h = 0; h < 2; ++h)
+                for (int q = 0; q < 4; ++q)
 #pragma unroll
-                for (int rb = 0; rb < NRB; ++rb)
-                    acc[h][rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(sl.mv[rb][q]), as_bf16x8(sl.zv[h][q]),
-                                                                         acc[h][rb], 0, 0, 0);
+                    for (int h = 0; h < 2; ++h)
+#pragma unroll
+                        for (int rb = 0; rb < NRB; ++rb)
+                            if (rb < nrb_t)
+                                acc[t][h][rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                                    as_bf16x8(sl.mv[rb][q]), as_bf16x8(sl.zv[t][h][q]), acc[t][h][rb], 0, 0, 0);
     };
-    if constexpr (NRB <= 2) {
-        // two slabs in flight per wave: the loads of the next slab are issued before the MFMAs of this one
-        Slab cur, nxt;
-        int32_t slab = wave * 128;
-        if (slab < D) load(cur, slab);
-        for (; slab < D; slab += 128 * NWV) {
-            const bool more = slab + 128 * NWV < D;
-            if (more) load(nxt, slab + 128 * NWV);
-            mac(cur);
-            if (more) cur = nxt;
-        }
-    } else {
-        for (int32_t slab = wave * 128; slab < D; slab += 128 * NWV) {
-            Slab cur;
-            load(cur, slab);
-            mac(cur);
+    // DEPTH slabs in flight per wave: the loads of slab i + DEPTH - 1 are issued before the MFMAs
+    // of slab i (DEPTH = 1: load, then multiply).
+    const int32_t nsl = (D + 127) >> 7;
+    Slab buf[DEPTH];
+#pragma unroll
+    for (int d = 0; d < DEPTH - 1; ++d)
+        if (wave + NWV * d < nsl) load(buf[d], (wave + NWV * d) << 7);
+    for (int32_t i = wave; i < nsl; i += NWV * DEPTH) {
+#pragma unroll
+        for (int d = 0; d < DEPTH; ++d) {
+            const int32_t nx = i + NWV * (d + DEPTH - 1);
+            if (nx < nsl) load(buf[(d + DEPTH - 1) % DEPTH], nx << 7);
+            if (i + NWV * d < nsl) mac(buf[d]);
         }
     }
-    // cross-wave sum through LDS, then lane (token j, rank group kg) of wave 0/1 stores half h
+    // per token block: cross-wave sum through LDS, then lane (token j, rank group kg) of wave 0/1
+    // stores half h
+    const float st = s[b[0].task];
 #pragma unroll
-    for (int h = 0; h < 2; ++h)
+    for (int t = 0; t < NTB; ++t) {
+        if (t >= cnt) break;
+        if (t > 0) __syncthreads();
 #pragma unroll
-        for (int rb = 0; rb < NRB; ++rb)
+        for (int h = 0; h < 2; ++h)
 #pragma unroll
-            for (int v = 0; v < 4; ++v) red[wave][h][rb][lane][v] = acc[h][rb][v];
-    __syncthreads();
-    if (wave < 2) {
-        const int h = wave;
-        const int32_t tok = 16 * h + j;
-        const float st = s[b.task];
+            for (int rb = 0; rb < NRB; ++rb)
+                if (rb < nrb_t)
 #pragma unroll
-        for (int rb = 0; rb < NRB; ++rb) {
-            bf16x4 o;
+                    for (int v = 0; v < 4; ++v) red[wave][h][rb][lane][v] = acc[t][h][rb][v];
+        __syncthreads();
+        if (wave < 2) {
+            const int h = wave;
+            const int32_t tok = 16 * h + j;
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                float sum = 0.f;
-#pragma unroll
-                for (int w = 0; w < NWV; ++w) sum += red[w][h][rb][lane][v];   // fixed order
-                const int32_t p = 16 * rb + 4 * kg + v;
-                o[v] = (__bf16)((p < r && tok < b.nrows) ? st * sum : 0.f);
-            }
-            const int32_t p0 = 16 * rb + 4 * kg;
-            if (p0 < pd.r_pad) {
-                if (tok < b.nrows)
-                    *reinterpret_cast<bf16x4*>(P_tok + size_t(b.row0 + tok) * pd.r_pad + p0) = o;
-                // block-transposed copy [block][rank][32 tokens]; tokens beyond the block hold 0
+            for (int rb = 0; rb < NRB; ++rb) {
+                bf16x4 o;
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
-                    union { __bf16 b; uint16_t u; } c;
-                    c.b = o[v];
-                    P_blk[(size_t(bi) * pd.r_pad + p0 + v) * kTokenBlock + tok] = c.u;
+                    float sum = 0.f;
+                    if (rb < nrb_t)
+#pragma unroll
+                        for (int w = 0; w < NWV; ++w) sum += red[w][h][rb][lane][v];   // fixed order
+                    const int32_t p = 16 * rb + 4 * kg + v;
+                    o[v] = (__bf16)((p < r && tok < b[t].nrows) ? st * sum : 0.f);
+                }
+                const int32_t p0 = 16 * rb + 4 * kg;
+                if (p0 < pd.r_pad) {
+                    if (tok < b[t].nrows)
+                        *reinterpret_cast<bf16x4*>(P_tok + size_t(b[t].row0 + tok) * pd.r_pad + p0) = o;
+                    // block-transposed copy [block][rank][32 tokens]; tokens beyond the block hold 0
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        union { __bf16 b; uint16_t u; } c;
+                        c.b = o[v];
+                        P_blk[(size_t(tb0 + t) * pd.r_pad + p0 + v) * kTokenBlock + tok] = c.u;
+                    }
                 }
             }
         }
@@ -154,29 +180,41 @@ hipError_t shrink_mfma(const PlanDev& pd, const void* Z, const void* M, const fl
 {
     if (pd.ntb == 0) return hipSuccess;
     const int nrb = pd.r_pad / 16;
-#define LOBRA_SHRINK(NRB, NWV)                                                                         \
-    shrink_mfma_kernel<NRB, NWV><<<pd.ntb, 64 * NWV, 0, st>>>(pd, (const uint16_t*)Z, (const uint16_t*)M, \
-                                                              s, (uint16_t*)P_tok, (uint16_t*)P_blk, D, 0)
-    if (nrb <= 1) LOBRA_SHRINK(1, LOBRA_SHRINK_WAVES);
-    else if (nrb <= 2) LOBRA_SHRINK(2, LOBRA_SHRINK_WAVES);
-    else if (nrb <= 4) LOBRA_SHRINK(4, 4);
-    else LOBRA_SHRINK(8, 4);
+#define LOBRA_SHRINK(NRB, NTB, DEPTH)                                                                  \
+    shrink_mfma_kernel<NRB, 4, NTB, DEPTH><<<(NTB == 1 ? pd.ntb : pd.nsb), 256, 0, st>>>(                \
+        pd, (const uint16_t*)Z, (const uint16_t*)M, s, (uint16_t*)P_tok, (uint16_t*)P_blk, D)
+    if (pd.shrink_group == 1) {
+        if (nrb <= 1) LOBRA_SHRINK(1, 1, 3);
+        else if (nrb <= 2) LOBRA_SHRINK(2, 1, 2);
+        else if (nrb <= 4) LOBRA_SHRINK(4, 1, 2);
+        else LOBRA_SHRINK(8, 1, 1);
+    } else if (pd.shrink_group == 2) {
+        if (nrb <= 4) LOBRA_SHRINK(4, 2, 1);
+        else LOBRA_SHRINK(8, 2, 1);
+    } else {
+        return hipErrorInvalidValue;
+    }
 #undef LOBRA_SHRINK
     return hipGetLastError();
 }
 
 // -------------------------------------------------------------------------------------------------
-// grad stage 1: partial dM over one reduction chunk and 128 columns per workgroup of 4 waves.
+// grad stage 1: partial dM over one reduction chunk and 16 CW columns per workgroup of 4 waves
+// (CW = 8: 128 columns; CW = 4: 64 columns, for large ranks, where the accumulators of a
+// 128-column tile would leave room for one wave per SIMD only).
 // Wave w takes the chunk's token blocks w, w+4, ...  For one block, lane (c, g) loads the 8 token
-// rows 8g .. 8g+7 at the 8 columns 8c .. 8c+7 (16 bytes per row, so a row is read in 256-byte runs),
-// transposes the 8 x 8 patch in registers (v_perm_b32) into 8 MFMA "B" operands - operand jj holds
-// 8 tokens of column 8c + jj - and multiplies each with the "A" operand P_blk[rank][32 tokens].
-// MFMA jj therefore produces the columns {8c + jj}, and a lane ends up with 8 consecutive columns.
+// rows 8g .. 8g+7 at the CW columns CW c .. CW c + CW-1 (so 16 lanes read 256 or 128 contiguous
+// bytes of a row), transposes the 8 x CW patch in registers (v_perm_b32) into CW MFMA "B"
+// operands - operand jj holds 8 tokens of column CW c + jj - and multiplies each with the "A"
+// operand P_blk[rank][32 tokens].  MFMA jj therefore produces the columns {CW c + jj}, and a lane
+// ends up with CW consecutive columns.  Rank blocks beyond the task's rank are skipped.
 // The four waves' sums are combined through LDS in two rounds (fixed order: ((w0+w2)+(w1+w3))).
 // -------------------------------------------------------------------------------------------------
-template <int NRB>
+template <int NRB, int CW>
 __global__ __launch_bounds__(256) void grad_mfma_kernel(PlanDev pd, GradJob ja, GradJob jb, int32_t tiles_a)
 {
+    typedef uint32_t zvec __attribute__((ext_vector_type(CW / 2)));
+    typedef float ovec __attribute__((ext_vector_type(4)));
     // one launch serves both gradients: column tiles [0, tiles_a) belong to job a, the rest to job b
     const bool first = int32_t(blockIdx.y) < tiles_a;
     const uint16_t* __restrict__ P_blk = static_cast<const uint16_t*>(first ? ja.P : jb.P);
@@ -184,41 +222,40 @@ __global__ __launch_bounds__(256) void grad_mfma_kernel(PlanDev pd, GradJob ja, 
     float* __restrict__ part = first ? ja.part : jb.part;
     const int32_t D = first ? ja.D : jb.D;
     const int32_t coltile = first ? int32_t(blockIdx.y) : int32_t(blockIdx.y) - tiles_a;
-    __shared__ float red[2][NRB][8][64][4];
+    __shared__ float red[2][NRB][CW][64][4];
     const GradChunk ch = pd.chunks[blockIdx.x];
     const int32_t r = pd.rank_off[ch.task + 1] - pd.rank_off[ch.task];
     const int32_t rb0 = blockIdx.z * NRB;                 // first rank block of this pass
     if (16 * rb0 >= r) return;                            // uniform: nothing to do for this task
+    const int32_t nrb_t = min(NRB, (r - 16 * rb0 + 15) >> 4);   // rank blocks needed (uniform)
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int c = lane & 15, g = lane >> 4;
-    const int32_t col = coltile * 128 + 8 * c;
+    const int32_t col = coltile * (16 * CW) + CW * c;
     const bool col_in = col < D;
-    const u32x4 zero4 = {0u, 0u, 0u, 0u};
 
-    f32x4 acc[NRB][8];
+    f32x4 acc[NRB][CW];
 #pragma unroll
     for (int rb = 0; rb < NRB; ++rb)
 #pragma unroll
-        for (int jj = 0; jj < 8; ++jj) acc[rb][jj] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int jj = 0; jj < CW; ++jj) acc[rb][jj] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     for (int32_t bi = ch.tb_begin + wave; bi < ch.tb_end; bi += 4) {
         const TokenBlock b = pd.tb[bi];
-        u32x4 zin[8];
+        zvec zin[8];
 #pragma unroll
         for (int q = 0; q < 8; ++q) {
             // rows beyond the block repeat its last row; their P entries are zero
             const int32_t row = b.row0 + min(8 * g + q, b.nrows - 1);
-            zin[q] = col_in ? *reinterpret_cast<const u32x4*>(Z + size_t(row) * D + col) : zero4;
+            zin[q] = col_in ? *reinterpret_cast<const zvec*>(Z + size_t(row) * D + col) : zvec(0u);
         }
         u32x4 pf[NRB];
 #pragma unroll
         for (int rb = 0; rb < NRB; ++rb)
-            pf[rb] = (16 * (rb0 + rb) < pd.r_pad)
-                         ? *reinterpret_cast<const u32x4*>(
-                               P_blk + (size_t(bi) * pd.r_pad + 16 * (rb0 + rb) + c) * kTokenBlock + 8 * g)
-                         : zero4;
+            if (rb < nrb_t)
+                pf[rb] = *reinterpret_cast<const u32x4*>(
+                    P_blk + (size_t(bi) * pd.r_pad + 16 * (rb0 + rb) + c) * kTokenBlock + 8 * g);
 #pragma unroll
-        for (int jj = 0; jj < 8; ++jj) {
+        for (int jj = 0; jj < CW; ++jj) {
             u32x4 f;
 #pragma unroll
             for (int e = 0; e < 4; ++e)
@@ -226,34 +263,38 @@ __global__ __launch_bounds__(256) void grad_mfma_kernel(PlanDev pd, GradJob ja, 
                                              (jj & 1) ? 0x07060302u : 0x05040100u);
 #pragma unroll
             for (int rb = 0; rb < NRB; ++rb)
-                acc[rb][jj] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(pf[rb]), as_bf16x8(f),
-                                                                      acc[rb][jj], 0, 0, 0);
+                if (rb < nrb_t)
+                    acc[rb][jj] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(pf[rb]), as_bf16x8(f),
+                                                                          acc[rb][jj], 0, 0, 0);
         }
     }
     // round 1: waves 2, 3 hand their sums to waves 0, 1; round 2: wave 1 hands its sum to wave 0
     if (wave >= 2)
 #pragma unroll
         for (int rb = 0; rb < NRB; ++rb)
+            if (rb < nrb_t)
 #pragma unroll
-            for (int jj = 0; jj < 8; ++jj)
+                for (int jj = 0; jj < CW; ++jj)
 #pragma unroll
-                for (int v = 0; v < 4; ++v) red[wave - 2][rb][jj][lane][v] = acc[rb][jj][v];
+                    for (int v = 0; v < 4; ++v) red[wave - 2][rb][jj][lane][v] = acc[rb][jj][v];
     __syncthreads();
     if (wave < 2)
 #pragma unroll
         for (int rb = 0; rb < NRB; ++rb)
+            if (rb < nrb_t)
 #pragma unroll
-            for (int jj = 0; jj < 8; ++jj)
+                for (int jj = 0; jj < CW; ++jj)
 #pragma unroll
-                for (int v = 0; v < 4; ++v) acc[rb][jj][v] += red[wave][rb][jj][lane][v];
+                    for (int v = 0; v < 4; ++v) acc[rb][jj][v] += red[wave][rb][jj][lane][v];
     __syncthreads();
     if (wave == 1)
 #pragma unroll
         for (int rb = 0; rb < NRB; ++rb)
+            if (rb < nrb_t)
 #pragma unroll
-            for (int jj = 0; jj < 8; ++jj)
+                for (int jj = 0; jj < CW; ++jj)
 #pragma unroll
-                for (int v = 0; v < 4; ++v) red[0][rb][jj][lane][v] = acc[rb][jj][v];
+                    for (int v = 0; v < 4; ++v) red[0][rb][jj][lane][v] = acc[rb][jj][v];
     __syncthreads();
     if (wave == 0 && col_in) {
 #pragma unroll
@@ -262,15 +303,14 @@ __global__ __launch_bounds__(256) void grad_mfma_kernel(PlanDev pd, GradJob ja, 
             for (int v = 0; v < 4; ++v) {
                 const int32_t p = 16 * (rb0 + rb) + 4 * g + v;
                 if (p >= r) continue;
-                f32x4 lo, hi;
-#pragma unroll
-                for (int jj = 0; jj < 4; ++jj) {
-                    lo[jj] = acc[rb][jj][v] + red[0][rb][jj][lane][v];
-                    hi[jj] = acc[rb][jj + 4][v] + red[0][rb][jj + 4][lane][v];
-                }
                 float* dst = part + size_t(ch.part_row0 + p) * D + col;
-                *reinterpret_cast<f32x4*>(dst) = lo;
-                *reinterpret_cast<f32x4*>(dst + 4) = hi;
+#pragma unroll
+                for (int j4 = 0; j4 < CW; j4 += 4) {
+                    ovec o;
+#pragma unroll
+                    for (int jj = 0; jj < 4; ++jj) o[jj] = acc[rb][j4 + jj][v] + red[0][rb][j4 + jj][lane][v];
+                    *reinterpret_cast<ovec*>(dst + j4) = o;
+                }
             }
     }
 }
@@ -280,15 +320,17 @@ hipError_t grad_mfma(const PlanDev& pd, const GradJob& ja, const GradJob& jb, hi
     if (pd.nchunks == 0) return hipSuccess;
     const int nrb = pd.r_pad / 16;
     const int NRB = nrb <= 1 ? 1 : (nrb <= 2 ? 2 : 4);
-    const int32_t tiles_a = (ja.D + 127) / 128, tiles_b = jb.P ? (jb.D + 127) / 128 : 0;
+    const int cw = NRB == 4 ? 4 : 8;
+    const int32_t tw = 16 * cw;
+    const int32_t tiles_a = (ja.D + tw - 1) / tw, tiles_b = jb.P ? (jb.D + tw - 1) / tw : 0;
     const dim3 grid(pd.nchunks, tiles_a + tiles_b, (nrb + NRB - 1) / NRB);
     if (grid.y > 65535u) return hipErrorInvalidValue;
     if (NRB == 1)
-        grad_mfma_kernel<1><<<grid, 256, 0, st>>>(pd, ja, jb, tiles_a);
+        grad_mfma_kernel<1, 8><<<grid, 256, 0, st>>>(pd, ja, jb, tiles_a);
     else if (NRB == 2)
-        grad_mfma_kernel<2><<<grid, 256, 0, st>>>(pd, ja, jb, tiles_a);
+        grad_mfma_kernel<2, 8><<<grid, 256, 0, st>>>(pd, ja, jb, tiles_a);
     else
-        grad_mfma_kernel<4><<<grid, 256, 0, st>>>(pd, ja, jb, tiles_a);
+        grad_mfma_kernel<4, 4><<<grid, 256, 0, st>>>(pd, ja, jb, tiles_a);
     return hipGetLastError();
 }
 
