@@ -41,11 +41,32 @@ def cpu_baseline(p, budget_rows):
     t_grads = time.perf_counter() - t0
     per_token = t_rows / len(rows) + t_grads / p.T
     cores = int(os.environ.get("OMP_NUM_THREADS", 0)) or len(os.sched_getaffinity(0))
-    return {
+    out = {
         "value": 1.0 / per_token, "unit": "tokens/s", "cores": cores, "kind": "oracle",
         "sample": "y and dx of %d evenly spaced rows (%.2f s) + dA, dB over all %d tokens (%.2f s); "
                   "per-token cost = rows_time/rows + grads_time/T" % (len(rows), t_rows, p.T, t_grads),
     }
+    # the same code on one thread (the OpenMP runtime's own switch; the oracle is not touched)
+    try:
+        import ctypes
+        gomp = ctypes.CDLL("libgomp.so.1")
+        gomp.omp_set_num_threads(1)
+        try:
+            rows1 = rows[:: max(1, cores)]
+            t0 = time.perf_counter()
+            o.y(rows1)
+            o.dx(rows1)
+            t_rows1 = time.perf_counter() - t0
+            t0 = time.perf_counter()
+            o.grads()
+            t_grads1 = time.perf_counter() - t0
+        finally:
+            gomp.omp_set_num_threads(cores)
+        out["value_1core"] = 1.0 / (t_rows1 / len(rows1) + t_grads1 / p.T)
+        out["sample_1core"] = "%d rows (%.2f s) + dA, dB (%.2f s)" % (len(rows1), t_rows1, t_grads1)
+    except OSError:
+        pass
+    return out
 
 
 def read_traffic(workload):
@@ -61,8 +82,8 @@ def read_traffic(workload):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--order", default="shuffled", choices=["shuffled", "sorted"])
     ap.add_argument("--oracle-rows", type=int, default=8192)

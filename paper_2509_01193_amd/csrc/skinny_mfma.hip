@@ -66,50 +66,63 @@ __global__ __launch_bounds__(64 * NWV) void shrink_mfma_kernel(PlanDev pd, const
 
     // rows beyond a block repeat its last row (their results are never stored)
     const uint16_t* zrow[NTB][2];
-    bool two_halves[NTB];
 #pragma unroll
-    for (int t = 0; t < NTB; ++t) {
+    for (int t = 0; t < NTB; ++t)
 #pragma unroll
         for (int h = 0; h < 2; ++h)
             zrow[t][h] = Z + size_t(b[t].row0 + min(16 * h + j, b[t].nrows - 1)) * D;
-        two_halves[t] = b[t].nrows > 16;
-    }
     const uint16_t* mrow[NRB];
 #pragma unroll
     for (int rb = 0; rb < NRB; ++rb) mrow[rb] = M + size_t(rank_row0 + min(16 * rb + j, r - 1)) * D;
 
-    // operands of one slab: 4 steps x (2 token halves of Z per block, NRB rank blocks of M)
+    // operands of one slab: 4 steps x (2 token halves of Z per block, NRB rank blocks of M).
+    // Rank rows beyond r_t and token rows beyond the block repeat a valid row: what they produce
+    // is dropped at the store, so the loads of a whole slab need no per-lane condition.
     struct Slab { u32x4 zv[NTB][2][4], mv[NRB][4]; };
     auto load = [&](Slab& sl, int32_t slab) {
         const int32_t k = slab + 8 * kg;
+        if (slab + 128 <= D) {
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const bool kin = k + 32 * q < D;
+            for (int q = 0; q < 4; ++q) {
 #pragma unroll
-            for (int rb = 0; rb < NRB; ++rb)
-                if (rb < nrb_t)
-                    sl.mv[rb][q] = (kin && 16 * rb + j < r)
-                                       ? *reinterpret_cast<const u32x4*>(mrow[rb] + k + 32 * q) : zero4;
+                for (int rb = 0; rb < NRB; ++rb)
+                    if (NRB == 1 || rb < nrb_t)
+                        sl.mv[rb][q] = *reinterpret_cast<const u32x4*>(mrow[rb] + k + 32 * q);
 #pragma unroll
-            for (int t = 0; t < NTB; ++t)
-                if (t < cnt)
+                for (int t = 0; t < NTB; ++t)
+                    if (NTB == 1 || t < cnt)
 #pragma unroll
-                    for (int h = 0; h < 2; ++h)
-                        sl.zv[t][h][q] = (kin && (h == 0 || two_halves[t]))
-                                             ? *reinterpret_cast<const u32x4*>(zrow[t][h] + k + 32 * q) : zero4;
+                        for (int h = 0; h < 2; ++h)
+                            sl.zv[t][h][q] = *reinterpret_cast<const u32x4*>(zrow[t][h] + k + 32 * q);
+            }
+        } else {   // the last slab of a width that is not a multiple of 128: columns beyond D read as 0
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const bool kin = k + 32 * q < D;
+#pragma unroll
+                for (int rb = 0; rb < NRB; ++rb)
+                    if (NRB == 1 || rb < nrb_t)
+                        sl.mv[rb][q] = kin ? *reinterpret_cast<const u32x4*>(mrow[rb] + k + 32 * q) : zero4;
+#pragma unroll
+                for (int t = 0; t < NTB; ++t)
+                    if (NTB == 1 || t < cnt)
+#pragma unroll
+                        for (int h = 0; h < 2; ++h)
+                            sl.zv[t][h][q] = kin ? *reinterpret_cast<const u32x4*>(zrow[t][h] + k + 32 * q) : zero4;
+            }
         }
     };
     auto mac = [&](const Slab& sl) {
 #pragma unroll
         for (int t = 0; t < NTB; ++t)
-            if (t < cnt)
+            if (NTB == 1 || t < cnt)
 #pragma unroll
                 for (int q = 0; q < 4; ++q)
 #pragma unroll
                     for (int h = 0; h < 2; ++h)
 #pragma unroll
                         for (int rb = 0; rb < NRB; ++rb)
-                            if (rb < nrb_t)
+                            if (NRB == 1 || rb < nrb_t)
                                 acc[t][h][rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
                                     as_bf16x8(sl.mv[rb][q]), as_bf16x8(sl.zv[t][h][q]), acc[t][h][rb], 0, 0, 0);
     };
@@ -232,6 +245,7 @@ __global__ __launch_bounds__(256) void grad_mfma_kernel(PlanDev pd, GradJob ja, 
     const int c = lane & 15, g = lane >> 4;
     const int32_t col = coltile * (16 * CW) + CW * c;
     const bool col_in = col < D;
+    const bool tile_full = (coltile + 1) * (16 * CW) <= D;   // uniform: no lane of this tile is beyond D
 
     f32x4 acc[NRB][CW];
 #pragma unroll
@@ -242,11 +256,17 @@ __global__ __launch_bounds__(256) void grad_mfma_kernel(PlanDev pd, GradJob ja, 
     for (int32_t bi = ch.tb_begin + wave; bi < ch.tb_end; bi += 4) {
         const TokenBlock b = pd.tb[bi];
         zvec zin[8];
+        // rows beyond the block repeat its last row; their P entries are zero
+        if (tile_full) {
 #pragma unroll
-        for (int q = 0; q < 8; ++q) {
-            // rows beyond the block repeat its last row; their P entries are zero
-            const int32_t row = b.row0 + min(8 * g + q, b.nrows - 1);
-            zin[q] = col_in ? *reinterpret_cast<const zvec*>(Z + size_t(row) * D + col) : zvec(0u);
+            for (int q = 0; q < 8; ++q)
+                zin[q] = *reinterpret_cast<const zvec*>(Z + size_t(b.row0 + min(8 * g + q, b.nrows - 1)) * D + col);
+        } else {
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                const int32_t row = b.row0 + min(8 * g + q, b.nrows - 1);
+                zin[q] = col_in ? *reinterpret_cast<const zvec*>(Z + size_t(row) * D + col) : zvec(0u);
+            }
         }
         u32x4 pf[NRB];
 #pragma unroll
