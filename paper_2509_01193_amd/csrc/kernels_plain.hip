@@ -11,9 +11,34 @@
 namespace lobra {
 
 // -------------------------------------------------------------------------------------------
-// shrink: one workgroup per token block, one wave per row, lanes strided over D
+// shrink: one workgroup per token block; wave w takes the rows 8w .. 8w+7 and, eight ranks at a
+// time, keeps an 8 x 8 block of sums in registers while its lanes stride over D four elements at
+// a time (so a rank row fetched from the cache serves eight token rows); the 64 lanes' partial
+// sums are combined with shuffles at the end.  Widths that are not a multiple of 4 take the
+// same loop one element at a time.
 // -------------------------------------------------------------------------------------------
-template <typename E>
+namespace {
+template <typename E> struct Vec4;
+template <> struct Vec4<float> {
+    static __device__ __forceinline__ void load(const float* p, size_t i, float (&v)[4])
+    {
+        typedef float f4 __attribute__((ext_vector_type(4)));
+        const f4 t = *reinterpret_cast<const f4*>(p + i);
+        v[0] = t[0], v[1] = t[1], v[2] = t[2], v[3] = t[3];
+    }
+};
+template <> struct Vec4<uint16_t> {
+    static __device__ __forceinline__ void load(const uint16_t* p, size_t i, float (&v)[4])
+    {
+        typedef uint32_t u2 __attribute__((ext_vector_type(2)));
+        const u2 t = *reinterpret_cast<const u2*>(p + i);
+        v[0] = __uint_as_float(t[0] << 16), v[1] = __uint_as_float(t[0] & 0xffff0000u);
+        v[2] = __uint_as_float(t[1] << 16), v[3] = __uint_as_float(t[1] & 0xffff0000u);
+    }
+};
+}  // namespace
+
+template <typename E, int VW>   // VW: elements per lane and step (4, or 1 for odd widths)
 __global__ __launch_bounds__(256) void plain_shrink_kernel(PlanDev pd, const E* __restrict__ Z,
                                                            const E* __restrict__ M,
                                                            const float* __restrict__ s,
@@ -23,30 +48,56 @@ __global__ __launch_bounds__(256) void plain_shrink_kernel(PlanDev pd, const E* 
     const int32_t r = pd.rank_off[b.task + 1] - pd.rank_off[b.task];
     const float st = s[b.task];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    for (int32_t rr = wave; rr < b.nrows; rr += 4) {
-        const size_t row = size_t(b.row0 + rr);
-        for (int32_t p0 = 0; p0 < pd.r_max; p0 += 8) {
-            float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-            if (p0 < r) {
-                for (int32_t k = lane; k < D; k += 64) {
-                    const float z = Elem<E>::load(Z, row * D + k);
+    const int32_t rr0 = 8 * wave;
+    if (rr0 >= b.nrows) return;
+    size_t zoff[8];          // rows beyond the block repeat its last row; their sums are not stored
 #pragma unroll
-                    for (int q = 0; q < 8; ++q)
-                        if (p0 + q < r)
-                            acc[q] = fmaf(z, Elem<E>::load(M, size_t(b.rank_row0 + p0 + q) * D + k), acc[q]);
+    for (int i = 0; i < 8; ++i) zoff[i] = size_t(b.row0 + min(rr0 + i, b.nrows - 1)) * D;
+    for (int32_t p0 = 0; p0 < pd.r_max; p0 += 8) {
+        float acc[8][8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+#pragma unroll
+            for (int q = 0; q < 8; ++q) acc[i][q] = 0.f;
+        if (p0 < r) {
+            size_t moff[8];  // ranks beyond r_t repeat the last rank row; their sums are not stored
+#pragma unroll
+            for (int q = 0; q < 8; ++q) moff[q] = size_t(b.rank_row0 + min(p0 + q, r - 1)) * D;
+            for (int32_t k = VW * lane; k < D; k += VW * 64) {
+                float z[8][VW], m[8][VW];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    if constexpr (VW == 4) Vec4<E>::load(Z, zoff[i] + k, z[i]);
+                    else z[i][0] = Elem<E>::load(Z, zoff[i] + k);
                 }
 #pragma unroll
-                for (int q = 0; q < 8; ++q)
-                    for (int off = 32; off > 0; off >>= 1) acc[q] += __shfl_xor(acc[q], off, 64);
+                for (int q = 0; q < 8; ++q) {
+                    if constexpr (VW == 4) Vec4<E>::load(M, moff[q] + k, m[q]);
+                    else m[q][0] = Elem<E>::load(M, moff[q] + k);
+                }
+#pragma unroll
+                for (int e = 0; e < VW; ++e)
+#pragma unroll
+                    for (int i = 0; i < 8; ++i)
+#pragma unroll
+                        for (int q = 0; q < 8; ++q) acc[i][q] = fmaf(z[i][e], m[q][e], acc[i][q]);
             }
-            if (lane < 8 && p0 + lane < pd.r_max) {
-                float v = 0.f;
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
 #pragma unroll
                 for (int q = 0; q < 8; ++q)
-                    if (q == lane) v = acc[q];
-                P[row * pd.r_max + p0 + lane] = (p0 + lane < r) ? st * v : 0.f;
-            }
+                    for (int off = 32; off > 0; off >>= 1) acc[i][q] += __shfl_xor(acc[i][q], off, 64);
         }
+        // lane 8 i + q stores the sum of row i and rank p0 + q
+        float v = 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+#pragma unroll
+            for (int q = 0; q < 8; ++q)
+                if (lane == 8 * i + q) v = acc[i][q];
+        const int i = lane >> 3, q = lane & 7;
+        if (rr0 + i < b.nrows && p0 + q < pd.r_max)
+            P[size_t(b.row0 + rr0 + i) * pd.r_max + p0 + q] = (p0 + q < r) ? st * v : 0.f;
     }
 }
 
@@ -54,10 +105,15 @@ hipError_t plain_shrink(const PlanDev& pd, int dtype, const void* Z, const void*
                         float* P, int32_t D, hipStream_t st)
 {
     if (pd.ntb == 0) return hipSuccess;
-    if (dtype == LOBRA_F32)
-        plain_shrink_kernel<float><<<pd.ntb, 256, 0, st>>>(pd, (const float*)Z, (const float*)M, s, P, D);
-    else
-        plain_shrink_kernel<uint16_t><<<pd.ntb, 256, 0, st>>>(pd, (const uint16_t*)Z, (const uint16_t*)M, s, P, D);
+    const bool vec = (D & 3) == 0;   // rows then start on 16-byte (fp32) or 8-byte (bf16) boundaries
+#define LOBRA_PLAIN_SHRINK(E, VW) \
+    plain_shrink_kernel<E, VW><<<pd.ntb, 256, 0, st>>>(pd, (const E*)Z, (const E*)M, s, P, D)
+    if (dtype == LOBRA_F32) {
+        if (vec) LOBRA_PLAIN_SHRINK(float, 4); else LOBRA_PLAIN_SHRINK(float, 1);
+    } else {
+        if (vec) LOBRA_PLAIN_SHRINK(uint16_t, 4); else LOBRA_PLAIN_SHRINK(uint16_t, 1);
+    }
+#undef LOBRA_PLAIN_SHRINK
     return hipGetLastError();
 }
 
@@ -166,12 +222,21 @@ __global__ __launch_bounds__(256) void plain_gradreduce_kernel(PlanDev pd, const
         float acc[16] = {};
         for (int32_t bi = c.tb_begin; bi < c.tb_end; ++bi) {
             const TokenBlock b = pd.tb[bi];
-            for (int32_t rr = 0; rr < b.nrows; ++rr) {
-                const size_t row = size_t(b.row0 + rr);
-                const float z = live ? Elem<E>::load(Z, row * D + col) : 0.f;
+            // four rows at a time, so that their loads are in flight together (rows in order:
+            // the sum does not depend on the grouping)
+            for (int32_t rr = 0; rr < b.nrows; rr += 4) {
+                float z[4];
 #pragma unroll
-                for (int q = 0; q < 16; ++q)
-                    if (p0 + q < r) acc[q] = fmaf(Elem<PE>::load(P, row * pstride + p0 + q), z, acc[q]);
+                for (int u = 0; u < 4; ++u)
+                    z[u] = (live && rr + u < b.nrows) ? Elem<E>::load(Z, size_t(b.row0 + rr + u) * D + col) : 0.f;
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    if (rr + u >= b.nrows) break;
+                    const size_t row = size_t(b.row0 + rr + u);
+#pragma unroll
+                    for (int q = 0; q < 16; ++q)
+                        if (p0 + q < r) acc[q] = fmaf(Elem<PE>::load(P, row * pstride + p0 + q), z[u], acc[q]);
+                }
             }
         }
         if (live)

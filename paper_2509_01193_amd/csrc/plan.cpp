@@ -127,10 +127,12 @@ lobra_status build_host_plan(const lobra_mlora_desc* d, uint32_t flags, Plan* p)
 
         // 4. reduction chunks: runs of token blocks of one task.  The chunk length is chosen so
         //    that (chunks x 128-column tiles) gives roughly a thousand workgroups, within
-        //    [4, 64] token blocks; fewer, longer chunks mean less partial-sum traffic.
+        //    [4, 64] token blocks ([1, 64] on the plain path); fewer, longer chunks mean less partial-sum traffic.
         const int64_t coltiles = (std::min(d->d_in, d->d_out) + 127) / 128;
         int64_t cb = (int64_t(T) * coltiles / 1024 + kTokenBlock - 1) / kTokenBlock;
-        cb = std::max<int64_t>(4, std::min<int64_t>(64, cb));
+        // (the MFMA kernel gives each of its four waves a token block of the chunk at a time; the plain
+        //  kernel walks a chunk's tokens one after the other, so small batches want short chunks there)
+        cb = std::max<int64_t>(p->mfma ? 4 : 1, std::min<int64_t>(64, cb));
         p->chunk_blocks = int32_t(cb);
         p->chunks.clear();
         p->task_chunk_off.assign(size_t(n) + 1, 0);

@@ -152,7 +152,10 @@ def test_work_lists_adversarial_tables():
         p = wl.make_custom("adv", "bf16", 64, 128, [8, 16, 3, 64, 128], seg_off, seg_task, trial, fill=False)
         check_plan(p)
     # one-token segments alternating between tasks, and an all-empty table
-    p = wl.make_custom("alt", "f32", 8, 8, [2, 2], np.arange(0, 101), np.arange(100) % 2, 1, fill=False)
+    # (chunks of at least four token blocks for the MFMA kernels, single blocks allowed on the fp32 path)
+    p = wl.make_custom("alt", "bf16", 8, 8, [2, 2], np.arange(0, 101), np.arange(100) % 2, 1, fill=False)
     assert check_plan(p) == (100, 2 * -(-50 // 4))
+    p = wl.make_custom("alt", "f32", 8, 8, [2, 2], np.arange(0, 101), np.arange(100) % 2, 1, fill=False)
+    assert check_plan(p) == (100, 100)
     p = wl.make_custom("none", "f32", 8, 8, [2, 2], [0, 0, 0], [0, 1], 1, fill=False)
     assert check_plan(p) == (0, 0)
