@@ -133,24 +133,43 @@ __global__ __launch_bounds__(256) void plain_gemm_kernel(PlanDev pd, const E* __
     const int32_t row0 = blockIdx.y * 64, col0 = blockIdx.x * 64;
     const int32_t T = pd.T;
     float acc[4][4] = {};
-    for (int32_t k0 = 0; k0 < K; k0 += 16) {
-        for (int e = tid; e < 64 * 16; e += 256) {
+    // each thread moves 4 elements of the Z tile and 4 of the W tile per K step; the elements of
+    // step k0 + 16 are fetched into registers before the products of step k0 are formed
+    float zr[4], wr[4];
+    auto fetch = [&](int32_t k0) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int e = tid + 256 * u;
             {   // Z tile: 64 rows x 16 k, k fastest in memory
                 const int kk = e & 15, m = e >> 4;
                 const int32_t row = row0 + m, k = k0 + kk;
-                Zs[kk][m] = (row < T && k < K) ? Elem<E>::load(Z, size_t(row) * K + k) : 0.f;
+                zr[u] = (row < T && k < K) ? Elem<E>::load(Z, size_t(row) * K + k) : 0.f;
             }
             if (TRANSW) {   // op(W)[k][n] = W[n*ldw + k]: k fastest
                 const int kk = e & 15, nn = e >> 4;
                 const int32_t n = col0 + nn, k = k0 + kk;
-                Ws[kk][nn] = (n < N && k < K) ? Elem<E>::load(W, size_t(n) * ldw + k) : 0.f;
+                wr[u] = (n < N && k < K) ? Elem<E>::load(W, size_t(n) * ldw + k) : 0.f;
             } else {        // op(W)[k][n] = W[k*ldw + n]: n fastest
                 const int nn = e & 63, kk = e >> 6;
                 const int32_t n = col0 + nn, k = k0 + kk;
-                Ws[kk][nn] = (n < N && k < K) ? Elem<E>::load(W, size_t(k) * ldw + n) : 0.f;
+                wr[u] = (n < N && k < K) ? Elem<E>::load(W, size_t(k) * ldw + n) : 0.f;
             }
         }
+    };
+    auto stash = [&]() {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int e = tid + 256 * u;
+            Zs[e & 15][e >> 4] = zr[u];
+            if (TRANSW) Ws[e & 15][e >> 4] = wr[u];
+            else Ws[e >> 6][e & 63] = wr[u];
+        }
+    };
+    fetch(0);
+    for (int32_t k0 = 0; k0 < K; k0 += 16) {
+        stash();
         __syncthreads();
+        if (k0 + 16 < K) fetch(k0 + 16);
 #pragma unroll
         for (int kk = 0; kk < 16; ++kk) {
             float a[4], b[4];
