@@ -209,13 +209,16 @@ def main():
                 "mfma_only_sustained_tflops": MFMA_ONLY_SUSTAINED_TFLOPS if p.dtype == "bf16" else None}
     esz = 2 if p.dtype == "bf16" else 4
     skinny = {}
-    # each of the two rank-r stages reads x once and dy once per step
+    # each of the two rank-r stages reads x once and dy once per step (algorithmic bytes); `traffic` is
+    # the same launch by the HBM-side counters of the committed rocprofv3 --pmc summary
     for name in ("shrink", "grad_stage1"):
         if name in kern and kern[name]["launches_per_step"] > 0:
             per_launch = float(esz) * p.T * (p.d_in + p.d_out) / kern[name]["launches_per_step"]
-            skinny[name + "_GBs"] = per_launch / (kern[name]["avg_ms"] * 1e-3) / 1e9
-            # the same launch by the HBM-side counters (committed rocprofv3 --pmc summary)
-            skinny[name + "_traffic"] = read_traffic("cfg%d" % a.config, "TRAFFIC_%s_BYTES_PER_LAUNCH" % name.upper())
+            gbs = per_launch / (kern[name]["avg_ms"] * 1e-3) / 1e9
+            skinny[name] = {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                            "frac": gbs / PEAK_HBM_GBS, "avg_launch_ms": kern[name]["avg_ms"],
+                            "bytes_per_launch": per_launch,
+                            "traffic": read_traffic("cfg%d" % a.config, "TRAFFIC_%s_BYTES_PER_LAUNCH" % name.upper())}
     out = {
         "metric": "multi-LoRA linear fwd+bwd tokens/s", "value": p.T / (ms_wall * 1e-3), "unit": "tokens/s",
         "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms_wall,
