@@ -91,6 +91,11 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--order", default="shuffled", choices=["shuffled", "sorted"])
+    ap.add_argument("--layout", default="packed", choices=["packed", "padded"],
+                    help="padded: every sequence padded to one of --buckets boundaries chosen by "
+                         "lobra_dynamic_buckets among multiples of 256 (pad tokens take the base product only); "
+                         "`value` then counts the real tokens")
+    ap.add_argument("--buckets", type=int, default=8)
     ap.add_argument("--oracle-rows", type=int, default=8192)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true",
@@ -110,7 +115,15 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py needs a GPU")
     torch.cuda.set_device(0)
-    p = wl.make_config(a.config, a.order)
+    p = wl.make_config(a.config, a.order, fill=(a.layout == "packed"))
+    real_tokens, useful, layout_info = p.T, p.useful_flops(), {"layout": "packed"}   # pad tokens are not useful work
+    if a.layout == "padded":
+        lens = [L for L, _ in p.seqs if L > 0]
+        cand = list(range(256, (max(lens) + 255) // 256 * 256 + 1, 256))
+        bounds, pad = bd.lobra_dynamic_buckets(lens, cand, a.buckets)
+        p = wl.pad_to_buckets(p, bounds)
+        assert p.T == real_tokens + pad
+        layout_info = {"layout": "padded", "bucket_bounds": bounds, "pad_tokens": pad, "real_tokens": real_tokens}
     t0 = time.perf_counter()
     dp = bd.DeviceProblem(p)
     torch.cuda.synchronize()
@@ -196,7 +209,7 @@ def main():
 
     cnt = p.task_tokens()
     tok_rank = float((cnt * p.ranks).sum())
-    flops = p.useful_flops()
+    flops = useful
     # dominant kernel: the fused GEMM (two launches per step: y and dx)
     gemm_flops = 0.5 * (4.0 * p.T * p.d_in * p.d_out + 2.0 * tok_rank * (p.d_in + p.d_out))
     gemm_ms = kern.get("gemm", {}).get("avg_ms", float("nan"))
@@ -220,14 +233,14 @@ def main():
                             "bytes_per_launch": per_launch,
                             "traffic": read_traffic("cfg%d" % a.config, "TRAFFIC_%s_BYTES_PER_LAUNCH" % name.upper())}
     out = {
-        "metric": "multi-LoRA linear fwd+bwd tokens/s", "value": p.T / (ms_wall * 1e-3), "unit": "tokens/s",
+        "metric": "multi-LoRA linear fwd+bwd tokens/s", "value": real_tokens / (ms_wall * 1e-3), "unit": "tokens/s",
         "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms_wall,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": p.dtype, "data": "synthetic",
         "launch": "eager" if a.no_graph else "hip_graph_replay", "ms_per_step_eager": ms_wall_eager,
         "config": {"workload": p.name, "T": p.T, "d_in": p.d_in, "d_out": p.d_out,
                    "n_tasks": p.n_tasks, "ranks": sorted(set(int(r) for r in p.ranks)),
-                   "segments": p.S, "order": a.order},
+                   "segments": p.S, "order": a.order, **layout_info},
         "useful_tflops": flops / (ms_wall * 1e-3) / 1e12,
         "pct_of_peak": 100.0 * flops / (ms_wall * 1e-3) / 1e12 / peak,
         "ms_per_step_events": ms_ev, "ms_base_only": ms_base,

@@ -276,6 +276,30 @@ def make_config(cfg: int, order: str = "shuffled", d_in: int = None, d_out: int 
     return p.fill(**fill_kw) if fill else p
 
 
+def pad_to_buckets(p: Problem, bounds, fill: bool = True, **fill_kw) -> Problem:
+    """The padded layout of the same sequences (paper section 2.1, "Processing Variable-length
+    Data"): every sequence is followed by pad tokens up to the smallest boundary in `bounds` that
+    holds it.  Pad tokens are segments of task -1 (base product only).  `bounds` comes from the
+    caller (e.g. the dynamic bucketing entry point); this function only lays tokens out."""
+    bounds = sorted(int(b) for b in bounds)
+    seg_off, seg_task = [0], []
+    for length, t in p.seqs:
+        if length <= 0:
+            continue
+        b = next((u for u in bounds if u >= length), None)
+        if b is None:
+            raise ValueError("sequence of %d tokens exceeds the largest boundary" % length)
+        seg_off.append(seg_off[-1] + length)
+        seg_task.append(t)
+        if b > length:
+            seg_off.append(seg_off[-1] + b - length)
+            seg_task.append(-1)
+    q = Problem(name=p.name + "-padded", dtype=p.dtype, T=int(seg_off[-1]), d_in=p.d_in, d_out=p.d_out,
+                ranks=p.ranks.copy(), s=p.s.copy(), seg_off=np.asarray(seg_off, np.int32),
+                seg_task=np.asarray(seg_task, np.int32), seqs=list(p.seqs), seed=p.seed)
+    return q.fill(**fill_kw) if fill else q
+
+
 def make_custom(name, dtype, d_in, d_out, ranks, seg_off, seg_task, seed, s=None,
                 fill=True, **fill_kw) -> Problem:
     """A problem from an explicit segment table (edge-case and adversarial tables)."""

@@ -80,6 +80,19 @@ def test_bench_prints_one_json_line_with_the_contract_keys():
 
 
 @pytest.mark.gpu
+def test_bench_padded_layout_counts_real_tokens_only():
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--steps", "2", "--warmup", "1",
+                        "--layout", "padded", "--buckets", "8", "--no-cpu-baseline"],
+                       capture_output=True, text=True, timeout=600)
+    assert r.returncode == 0, r.stdout[-2000:] + r.stderr[-2000:]
+    d = json.loads([l for l in r.stdout.splitlines() if l.startswith("{")][0])
+    c = d["config"]
+    assert c["layout"] == "padded" and len(c["bucket_bounds"]) <= 8
+    assert c["T"] == c["real_tokens"] + c["pad_tokens"] and c["real_tokens"] == 16384 and c["pad_tokens"] > 0
+    assert abs(d["value"] - c["real_tokens"] / (d["ms_per_step"] * 1e-3)) < 1e-6 * d["value"]
+
+
+@pytest.mark.gpu
 def test_smoke_entry_point():
     sys.path.insert(0, ROOT)
     import __graft_entry__ as ge
