@@ -67,3 +67,28 @@ def test_host_implementation_paper_scale_and_errors():
     with pytest.raises(bd.LobraError):
         bd.lobra_dynamic_buckets([9], [4, 8], 1)
     assert bd.lobra_dynamic_buckets([], [4, 8], 2) == ([], 0)
+
+
+def test_padded_layout_of_a_workload_follows_the_chosen_boundaries():
+    """Bucket boundaries -> padded batch: every sequence keeps its tokens and task and is followed
+    by exactly the pad span (task -1) that brings it to its boundary; the pad total is the programme's."""
+    from paper_2509_01193_amd import workloads as wl
+    for cfg in (2, 3, 5):
+        p = wl.make_config(cfg, "shuffled", fill=False)
+        lens = [L for L, _ in p.seqs]
+        cand = list(range(256, -(-max(lens) // 256) * 256 + 1, 256))
+        bounds, pad = bd.lobra_dynamic_buckets(lens, cand, 8)
+        q = wl.pad_to_buckets(p, bounds, fill=False)
+        assert q.T == p.T + pad == p.T + ob.padding_for(lens, bounds)
+        k = 0
+        for L, t in p.seqs:
+            assert q.seg_task[k] == t and q.seg_off[k + 1] - q.seg_off[k] == L
+            k += 1
+            b = min(u for u in bounds if u >= L)
+            if b > L:
+                assert q.seg_task[k] == -1 and q.seg_off[k + 1] - q.seg_off[k] == b - L
+                k += 1
+        assert k == q.S
+        assert (q.task_tokens() == p.task_tokens()).all()
+    with pytest.raises(ValueError):
+        wl.pad_to_buckets(p, [16])
