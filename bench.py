@@ -96,6 +96,11 @@ def main():
                          "lobra_dynamic_buckets among multiples of 256 (pad tokens take the base product only); "
                          "`value` then counts the real tokens")
     ap.add_argument("--buckets", type=int, default=8)
+    ap.add_argument("--projections", type=int, default=1,
+                    help="P > 1: P LoRA linears that read the same x (q/k/v, gate/up) as ONE call - W "
+                         "concatenated along d_out, A_t stacked along the rank, B_t compact (desc.n_proj = P) - "
+                         "timed against P separate calls and against one call on block-diagonal up factors; "
+                         "prints its own JSON line and exits")
     ap.add_argument("--oracle-rows", type=int, default=8192)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true",
@@ -127,6 +132,53 @@ def main():
     t0 = time.perf_counter()
     dp = bd.DeviceProblem(p)
     torch.cuda.synchronize()
+
+    if a.projections > 1:
+        P = a.projections
+        # (a) the fused call: stacked down factors, compact up factors, desc.n_proj = P
+        df = bd.DeviceProblem(wl.fuse_projections(p, P))
+        # (b) the same layers as ONE ordinary call on concatenated weights: up factors block-diagonal
+        dense = wl.make_custom(p.name + "-dense-x%d" % P, p.dtype, p.d_in, P * p.d_out, P * p.ranks, p.seg_off,
+                               p.seg_task, p.seed, s=p.s)
+        fro = dense.rank_off
+        for t in range(p.n_tasks):
+            r = int(p.ranks[t])
+            for j in range(P):
+                rows = slice(int(fro[t]) + j * r, int(fro[t]) + (j + 1) * r)
+                dense.B[rows, : j * p.d_out] = 0
+                dense.B[rows, (j + 1) * p.d_out:] = 0
+        dd = bd.DeviceProblem(dense)
+        # (c) P separate calls
+        parts = [dp] + [bd.DeviceProblem(p) for _ in range(P - 1)]
+
+        def t_of(fn):
+            for _ in range(a.warmup):
+                fn()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(a.steps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / a.steps
+
+        def separate():
+            for q in parts:
+                q.step()
+        acc = torch.empty_like(dp.dx)
+
+        def dx_sum():                       # what the caller of separate calls still owes: dx = sum of P partial dx
+            torch.add(parts[0].dx, parts[1].dx, out=acc)
+            for q in parts[2:]:
+                acc.add_(q.dx)
+        ms_sep, ms_sum, ms_dense, ms_fused = t_of(separate), t_of(dx_sum), t_of(dd.step), t_of(df.step)
+        print(json.dumps({"projection_fusion": True, "projections": P, "workload": p.name,
+                          "ms_per_step_fused_call": ms_fused, "ms_per_step_dense_concatenated_call": ms_dense,
+                          "ms_per_step_separate_calls": ms_sep, "ms_dx_sum_after_separate_calls": ms_sum,
+                          "tokens_per_s_fused": p.T / (ms_fused * 1e-3),
+                          "speedup_vs_separate_plus_sum": (ms_sep + ms_sum) / ms_fused}))
+        return
 
     if a.pmc_probe:
         dp.step()

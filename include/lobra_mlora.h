@@ -93,7 +93,23 @@ typedef struct {
     const int32_t *rank_off; /* [n_tasks+1], rank_off[0] = 0, r_t = rank_off[t+1]-rank_off[t] */
     const int32_t *seg_off;  /* [S+1], seg_off[0] = 0, non-decreasing, seg_off[S] = T */
     const int32_t *seg_task; /* [S], each in [-1, n_tasks) */
+    int32_t n_proj;          /* 0 or 1: one layer.  P > 1: P layers that read the same x, fused
+                                into one call (see "Shared-input projections" below) */
 } lobra_mlora_desc;
+
+/* Shared-input projections (n_proj = P > 1).  The q/k/v projections of an attention block, or the
+ * gate/up projections of an MLP, are P LoRA linears that read the same x.  Fused into one call they
+ * share the pass over x (down projections), the pass over x of the dA reduction, and the sum of
+ * their P contributions to dx (one product over the concatenated dy).  Layouts, with
+ * dg = d_out / P and r_t = (rank_off[t+1] - rank_off[t]) / P the rank of task t in every projection:
+ *     W  [d_in, d_out]   projection j in columns j dg .. (j+1) dg - 1;  y, dy [T, d_out] likewise
+ *     A  [R_tot, d_in]   task t owns rows rank_off[t] ..; of those, rows j r_t .. (j+1) r_t - 1
+ *                        are the down projection of task t in projection j;  dA alike
+ *     B  [R_tot, dg]     row (t, j, rho) is row rho of the up projection of task t in projection j
+ *                        (it only ever meets columns of projection j);  dB alike
+ * so that  y[:, j] = x W[:, j] + s_t (A_t^j x) B_t^j  and  dx = sum_j dy[:, j] W[:, j]^T + s_t (B_t^j dy[:, j]) A_t^j.
+ * Requires LOBRA_BF16 without LOBRA_PLAN_PLAIN_KERNELS (else LOBRA_ERR_DTYPE), d_out a multiple of
+ * 8 P, and every stacked rank a multiple of 8 P (else LOBRA_ERR_RANK / LOBRA_ERR_ALIGN). */
 
 /* Opaque per-batch plan: the validated table plus the device-resident work lists (token
  * blocks, per-tile segment ranges, reduction chunks).  One packed batch passes through every

@@ -5,6 +5,7 @@ Only ``tests/``, ``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of
 """
 from .oracle import (  # noqa: F401
     Oracle,
+    FusedProjections,
     build_oracle,
     token_task,
     forward,

@@ -259,3 +259,57 @@ class Oracle:
     def grads(self):
         return backward_grads(self.x, self.A, self.B, self.s, self.dy,
                               self.rank_off, self.task_of)
+
+
+class FusedProjections:
+    """Several layers that read the same x (the q/k/v projections of an attention block, gate/up of
+    an MLP; paper section 3.3 names the LoRA linears of one layer), each computed by the oracle above
+    on its own slice - nothing is fused here, the definition is "P separate layers":
+
+        y[:, j]  = layer_j(x)                 dx = sum_j dx_j
+        dA rows (t, j, :) = dA_t of layer j   dB rows (t, j, :) = dB_t of layer j
+
+    Layouts as the library takes them: W [d_in, P dg], y/dy [T, P dg], every task's rank rows stacked
+    P times in A [R_tot, d_in] (rows j r_t .. (j+1) r_t - 1 of task t belong to layer j), B [R_tot, dg].
+    """
+
+    def __init__(self, n_proj, x, W, A, B, s, dy, rank_off, seg_off, seg_task):
+        P = int(n_proj)
+        rank_off = np.asarray(rank_off, np.int64)
+        ranks = np.diff(rank_off)
+        if (ranks % P).any() or W.shape[1] % P or dy.shape[1] != W.shape[1]:
+            raise ValueError("ranks and d_out must be multiples of the number of projections")
+        self.P, self.dg = P, W.shape[1] // P
+        self.sub_ranks = ranks // P
+        sub_off = np.concatenate([[0], np.cumsum(self.sub_ranks)]).astype(np.int32)
+        # rows of the stacked factors that belong to layer j, in task order
+        self.rows = []
+        for j in range(P):
+            idx = [np.arange(rank_off[t] + j * r, rank_off[t] + (j + 1) * r) for t, r in enumerate(self.sub_ranks)]
+            self.rows.append(np.concatenate(idx).astype(np.int64) if idx else np.zeros(0, np.int64))
+        self.R_tot = int(rank_off[-1])
+        self.layers = []
+        for j in range(P):
+            cols = slice(j * self.dg, (j + 1) * self.dg)
+            self.layers.append(Oracle(x, np.ascontiguousarray(W[:, cols]), np.ascontiguousarray(A[self.rows[j]]),
+                                      np.ascontiguousarray(B[self.rows[j]]), s, np.ascontiguousarray(dy[:, cols]),
+                                      sub_off, seg_off, seg_task))
+
+    def y(self, rows=None):
+        return np.concatenate([L.y(rows) for L in self.layers], axis=1)
+
+    def dx(self, rows=None):
+        out = self.layers[0].dx(rows)
+        for L in self.layers[1:]:
+            out = out + L.dx(rows)
+        return out
+
+    def grads(self):
+        d_in = self.layers[0].x.shape[1]
+        dA = np.zeros((self.R_tot, d_in), np.float64)
+        dB = np.zeros((self.R_tot, self.dg), np.float64)
+        for j, L in enumerate(self.layers):
+            a, b = L.grads()
+            dA[self.rows[j]] = a
+            dB[self.rows[j]] = b
+        return dA, dB

@@ -35,6 +35,7 @@ class Desc(ctypes.Structure):
         ("rank_off", ctypes.POINTER(ctypes.c_int32)),
         ("seg_off", ctypes.POINTER(ctypes.c_int32)),
         ("seg_task", ctypes.POINTER(ctypes.c_int32)),
+        ("n_proj", ctypes.c_int32),
     ]
 
 
@@ -105,7 +106,7 @@ def _i32(a):
     return np.ascontiguousarray(np.asarray(a, dtype=np.int32))
 
 
-def make_desc(dtype, T, d_in, d_out, rank_off, seg_off, seg_task):
+def make_desc(dtype, T, d_in, d_out, rank_off, seg_off, seg_task, n_proj=1):
     """Returns (Desc, keepalive).  `dtype` is "f32"/"bf16" or the enum value."""
     code = {"f32": F32, "bf16": BF16}.get(dtype, dtype)
     keep = []
@@ -126,6 +127,7 @@ def make_desc(dtype, T, d_in, d_out, rank_off, seg_off, seg_task):
         d.seg_off = so.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
         d.seg_task = stk.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
     d.S = S
+    d.n_proj = int(n_proj)
     return d, keep
 
 
@@ -152,8 +154,8 @@ def _stream(stream):
 class Plan:
     """Owns a ``lobra_mlora_plan``.  One plan per packed batch, shared by every layer's calls."""
 
-    def __init__(self, dtype, T, d_in, d_out, rank_off, seg_off, seg_task, flags=0):
-        self.desc, self._keep = make_desc(dtype, T, d_in, d_out, rank_off, seg_off, seg_task)
+    def __init__(self, dtype, T, d_in, d_out, rank_off, seg_off, seg_task, flags=0, n_proj=1):
+        self.desc, self._keep = make_desc(dtype, T, d_in, d_out, rank_off, seg_off, seg_task, n_proj)
         self.handle = ctypes.c_void_p()
         _check(lib().lobra_mlora_plan_create(ctypes.byref(self.desc), int(flags),
                                              ctypes.byref(self.handle)), "lobra_mlora_plan_create")
@@ -167,7 +169,8 @@ class Plan:
 
     @classmethod
     def for_problem(cls, p, flags=0):
-        return cls(p.dtype, p.T, p.d_in, p.d_out, p.rank_off, p.seg_off, p.seg_task, flags)
+        return cls(p.dtype, p.T, p.d_in, p.d_out, p.rank_off, p.seg_off, p.seg_task, flags,
+                   getattr(p, "n_proj", 1))
 
     def query(self, what) -> np.ndarray:
         n = ctypes.c_size_t()
@@ -269,7 +272,7 @@ class DeviceProblem:
         self.y = torch.empty((p.T, p.d_out), dtype=self.edt, device=self.dev)
         self.dx = torch.empty((p.T, p.d_in), dtype=self.edt, device=self.dev)
         self.dA = torch.zeros((p.R_tot, p.d_in), dtype=torch.float32, device=self.dev)
-        self.dB = torch.zeros((p.R_tot, p.d_out), dtype=torch.float32, device=self.dev)
+        self.dB = torch.zeros((p.R_tot, p.d_out // getattr(p, "n_proj", 1)), dtype=torch.float32, device=self.dev)
         nb = lambda n: torch.empty(max(n, 16), dtype=torch.uint8, device=self.dev)
         self.h_save = nb(self.plan.h_save_bytes)
         self.ws = nb(max(self.plan.fwd_ws_bytes, self.plan.bwd_ws_bytes))

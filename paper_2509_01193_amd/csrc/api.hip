@@ -41,6 +41,8 @@ PlanDev device_view(const Plan& p)
     d.R_tot = p.R_tot;
     d.nsb = int32_t(p.sb_off.size()) - 1;
     d.shrink_group = p.shrink_group;
+    d.n_proj = p.n_proj;
+    d.dg = p.dg;
     return d;
 }
 
@@ -220,12 +222,31 @@ lobra_status lobra_mlora_fwd(const lobra_mlora_plan* plan, const void* x, const 
     }
     // bf16 MFMA path
     char* hb = static_cast<char*>(hbuf);
-    if (adapters)
+    if (adapters)   // all projections' down factors are stacked in A: one pass over x
         LOBRA_LAUNCH(p, st, LOBRA_K_SHRINK,
-                     shrink_mfma(pd, x, A, s, hb + p.p_layout.p_tok, hb + p.p_layout.p_blk, pd.d_in, st));
-    LOBRA_LAUNCH(p, st, LOBRA_K_GEMM,
-                 gemm_mfma(pd, false, x, W, adapters ? hb + p.p_layout.p_tok : nullptr, B, y, pd.d_in,
-                           pd.d_out, pd.d_out, st));
+                     shrink_mfma(pd, x, A, s, hb + p.p_layout.p_tok, hb + p.p_layout.p_blk, pd.d_in, pd.d_in, 1, 0, st));
+    if (p.n_proj == 1) {
+        LOBRA_LAUNCH(p, st, LOBRA_K_GEMM,
+                     gemm_mfma(pd, false, x, W, adapters ? hb + p.p_layout.p_tok : nullptr, B, y, pd.d_in,
+                               pd.d_out, pd.d_out, st));
+        return LOBRA_OK;
+    }
+    // fused shared-input projections: every column tile of y takes the rank window of H and the rows of
+    // the compact B that belong to its projection - in one launch when no tile straddles two projections,
+    // else in one launch per projection (its column block of W and y)
+    if (pd.dg % 256 == 0) {
+        LOBRA_LAUNCH(p, st, LOBRA_K_GEMM,
+                     gemm_mfma(pd, false, x, W, adapters ? hb + p.p_layout.p_tok : nullptr, B, y, pd.d_in,
+                               pd.d_out, pd.d_out, st, pd.d_out, p.n_proj, -1));
+        return LOBRA_OK;
+    }
+    for (int32_t j = 0; j < p.n_proj; ++j) {
+        const size_t col = size_t(j) * pd.dg * 2;                   // bytes into a row of W / y
+        LOBRA_LAUNCH(p, st, LOBRA_K_GEMM,
+                     gemm_mfma(pd, false, x, static_cast<const char*>(W) + col,
+                               adapters ? hb + p.p_layout.p_tok : nullptr, B, static_cast<char*>(y) + col, pd.d_in,
+                               pd.dg, pd.d_out, st, pd.d_out, p.n_proj, j));
+    }
     return LOBRA_OK;
 }
 
@@ -289,11 +310,15 @@ lobra_status lobra_mlora_bwd(const lobra_mlora_plan* plan, const void* x, const 
         if (!H) {
             char* Hr = wsb + p.bwd_off_h;
             LOBRA_LAUNCH(p, st, LOBRA_K_SHRINK,
-                         shrink_mfma(pd, x, A, s, Hr + p.p_layout.p_tok, Hr + p.p_layout.p_blk, pd.d_in, st));
+                         shrink_mfma(pd, x, A, s, Hr + p.p_layout.p_tok, Hr + p.p_layout.p_blk, pd.d_in, pd.d_in, 1, 0, st));
             H = Hr;
         }
-        LOBRA_LAUNCH(p, st, LOBRA_K_SHRINK,
-                     shrink_mfma(pd, dy, B, s, G + p.p_layout.p_tok, G + p.p_layout.p_blk, pd.d_out, st));
+        // G = s dy B^T; with fused projections one launch per projection: its column block of dy
+        // against its rows of the compact B, written into its rank window of G
+        for (int32_t j = 0; j < p.n_proj; ++j)
+            LOBRA_LAUNCH(p, st, LOBRA_K_SHRINK,
+                         shrink_mfma(pd, static_cast<const char*>(dy) + size_t(j) * pd.dg * 2, B, s,
+                                     G + p.p_layout.p_tok, G + p.p_layout.p_blk, pd.dg, pd.d_out, p.n_proj, j, st));
     }
     if (want_dx && p.desc.T > 0)
         LOBRA_LAUNCH(p, st, LOBRA_K_GEMM,
@@ -301,9 +326,32 @@ lobra_status lobra_mlora_bwd(const lobra_mlora_plan* plan, const void* x, const 
                                pd.d_in, pd.d_out, st));
     if (p.R_tot > 0) {
         // dB (from s h and dy) and dA (from s g and x) share one launch per stage
-        const GradJob jb{adapters ? H + p.p_layout.p_blk : nullptr, dy, part_b, dB, pd.d_out};
+        GradJob jb{adapters ? H + p.p_layout.p_blk : nullptr, dy, part_b, dB, pd.dg};
         const GradJob ja{adapters ? G + p.p_layout.p_blk : nullptr, x, part_a, dA, pd.d_in};
-        if (adapters) LOBRA_LAUNCH(p, st, LOBRA_K_GRAD_STAGE1, grad_mfma(pd, jb, ja, st));
+        if (p.n_proj == 1) {
+            if (adapters) LOBRA_LAUNCH(p, st, LOBRA_K_GRAD_STAGE1, grad_mfma(pd, jb, ja, st));
+        } else if (adapters) {
+            // dA over all stacked ranks in one pass over x; dB per projection (its column block of dy,
+            // its rank window of H, its rows of the compact dB)
+            const GradJob none{nullptr, nullptr, nullptr, nullptr, 0};
+            LOBRA_LAUNCH(p, st, LOBRA_K_GRAD_STAGE1, grad_mfma(pd, ja, none, st));
+            if (pd.dg % 128 == 0) {     // no column tile straddles two projections: one pass over all of dy
+                GradJob jall = jb;
+                jall.D = pd.d_out;
+                jall.ldp = pd.dg;
+                jall.nproj = p.n_proj;
+                jall.proj = -1;
+                LOBRA_LAUNCH(p, st, LOBRA_K_GRAD_STAGE1, grad_mfma(pd, jall, none, st));
+            } else
+            for (int32_t j = 0; j < p.n_proj; ++j) {
+                GradJob jj = jb;
+                jj.Z = static_cast<const char*>(dy) + size_t(j) * pd.dg * 2;
+                jj.ldz = pd.d_out;
+                jj.nproj = p.n_proj;
+                jj.proj = j;
+                LOBRA_LAUNCH(p, st, LOBRA_K_GRAD_STAGE1, grad_mfma(pd, jj, none, st));
+            }
+        }
         LOBRA_LAUNCH(p, st, LOBRA_K_GRAD_STAGE2, reduce_partials(pd, jb, ja, accumulate, st));
     }
     return LOBRA_OK;
@@ -336,7 +384,7 @@ lobra_status lobra_mlora_adam_step(const lobra_mlora_plan* plan, const lobra_ada
         return LOBRA_ERR_SHAPE;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const PlanDev pd = device_view(p);
-    const AdamTensor ta{dA, master_A, m_A, v_A, A, pd.d_in}, tb{dB, master_B, m_B, v_B, B, pd.d_out};
+    const AdamTensor ta{dA, master_A, m_A, v_A, A, pd.d_in}, tb{dB, master_B, m_B, v_B, B, pd.dg};
     LOBRA_LAUNCH(p, st, LOBRA_K_ADAM,
                  adam_step(pd, p.desc.dtype, cfg->beta1, cfg->beta2, cfg->eps, cfg->weight_decay, lr, step,
                            grad_scale, ta, tb, st));

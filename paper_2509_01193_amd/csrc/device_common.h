@@ -18,7 +18,7 @@ struct PlanDev {
     const int32_t* rank_off;       // [n_tasks+1]
     const int32_t* task_tb_off;    // [n_tasks+1]
     const int32_t* sb_off;         // [nsb+1]
-    int32_t T, d_in, d_out, n_tasks, nseg, ntb, nchunks, r_max, r_pad, R_tot, nsb, shrink_group;
+    int32_t T, d_in, d_out, n_tasks, nseg, ntb, nchunks, r_max, r_pad, R_tot, nsb, shrink_group, n_proj, dg;
 };
 
 // Index of the compacted segment that holds `row` (0 <= row < T): start from the table entry

@@ -128,9 +128,14 @@ template <bool W_KN, int WM, int WN, bool DMA>
 __global__ __launch_bounds__(64 * WM * WN)
 void gemm_mfma_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const uint16_t* __restrict__ W,
                       const uint16_t* __restrict__ P, const uint16_t* __restrict__ M,
-                      uint16_t* __restrict__ C, int32_t K, int32_t N, int32_t ldw,
-                      int32_t tiles_m, int32_t tiles_n)
+                      uint16_t* __restrict__ C, int32_t K, int32_t N, int32_t ldw, int32_t ldc,
+                      int32_t nproj, int32_t proj, int32_t tiles_m, int32_t tiles_n)
 {
+    // ldc: row pitch of C.  nproj > 1: this launch is projection `proj` of a fused shared-input
+    // call: of every task's rank rows (in M) and rank columns (in P) only the window
+    // [proj r, (proj + 1) r) takes part, r = the task's stacked rank / nproj.  proj < 0: the launch
+    // covers all projections (N = nproj * pd.dg, pd.dg a multiple of the tile width) and a tile takes
+    // the projection its columns lie in; M is then the compact [R_tot][pd.dg] array.
     constexpr int NT = 64 * WM * WN;                // threads
     constexpr int TM = BM / WM, TN = BN / WN;       // wave tile
     constexpr int MB = TM / 32, NB = TN / 32;       // 32 x 32 blocks per wave
@@ -171,8 +176,12 @@ void gemm_mfma_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const uint16_t
     const int32_t sg_first = pd.rowblk_seg[row0 / kRowBlock];
     const int32_t sf_lo = pd.cseg_off[sg_first], sf_hi = pd.cseg_off[sg_first + 1];
     const int32_t sf_task = pd.cseg_task[sg_first];
-    const int32_t sf_r0 = sf_task >= 0 ? pd.rank_off[sf_task] : 0;
-    const int32_t sf_r1 = sf_task >= 0 ? pd.rank_off[sf_task + 1] : 0;
+    const int32_t pj = proj >= 0 ? proj : col0 / pd.dg;          // this tile's projection
+    const int32_t mcol0 = proj >= 0 ? 0 : pj * pd.dg;            // first column of that projection
+    const int32_t mpitch = proj >= 0 ? N : pd.dg;                // row pitch of M
+    const int32_t sf_rw = sf_task >= 0 ? (pd.rank_off[sf_task + 1] - pd.rank_off[sf_task]) / nproj : 0;
+    const int32_t sf_r0 = sf_task >= 0 ? pd.rank_off[sf_task] + pj * sf_rw : 0;
+    const int32_t sf_r1 = sf_r0 + sf_rw;
 
     auto zs = [&](int buf) { return lds + buf * ZT_BYTES; };
     auto ws = [&](int buf) { return lds + 2 * ZT_BYTES + buf * WT_BYTES; };
@@ -427,8 +436,8 @@ void gemm_mfma_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const uint16_t
             if (t < 0) continue;
             const int32_t seg_hi = cached ? sf_hi : pd.cseg_off[sg + 1];
             const int32_t lo = max(seg_lo, row0), hi = min(seg_hi, row_end);
-            const int32_t r0 = cached ? sf_r0 : pd.rank_off[t];
-            const int32_t r = (cached ? sf_r1 : pd.rank_off[t + 1]) - r0;
+            const int32_t r = cached ? sf_r1 - sf_r0 : (pd.rank_off[t + 1] - pd.rank_off[t]) / nproj;
+            const int32_t r0 = cached ? sf_r0 : pd.rank_off[t] + pj * r;
             const int32_t rp = (r + 15) & ~15;
             const bool mine = hi > wrow0 && lo < wrow0 + TM;   // wave-uniform: the segment crosses this wave's rows
             // P fragments of up to two rank steps are fetched before the adapter slice is staged, so
@@ -442,8 +451,10 @@ void gemm_mfma_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const uint16_t
                     for (int mb = 0; mb < MB; ++mb) {
                         const int32_t row = wrow0 + mb * 32 + l32;
                         const int32_t kk = kk0 + 16 * q;
-                        pv[q][mb] = (mine && kk < rp && row >= lo && row < hi)
-                            ? *reinterpret_cast<const u32x4*>(P + size_t(row) * pd.r_pad + kk + 8 * lh) : zero4;
+                        // (a lane's 8 ranks start at kk + 8 lh: groups that start beyond r_t hold padding,
+                        //  or another projection's ranks, and are not read)
+                        pv[q][mb] = (mine && kk + 8 * lh < r && row >= lo && row < hi)
+                            ? *reinterpret_cast<const u32x4*>(P + size_t(row) * pd.r_pad + pj * r + kk + 8 * lh) : zero4;
                     }
             };
             load_p(0);
@@ -456,7 +467,7 @@ void gemm_mfma_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const uint16_t
                 for (int q = 0; q < MCH; ++q) {
                     const int32_t ch = base + tid + q * NT2, kr = ch >> 5, n = col0 + 8 * (ch & 31);
                     mreg[q] = (ch < rp * 32 && kr < r && n < N)
-                                  ? *reinterpret_cast<const u32x4*>(M + size_t(r0 + kr) * N + n) : zero4;
+                                  ? *reinterpret_cast<const u32x4*>(M + size_t(r0 + kr) * mpitch + (n - mcol0)) : zero4;
                 }
             };
             auto store_m = [&](int32_t base) {
@@ -539,8 +550,8 @@ void gemm_mfma_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const uint16_t
             const int32_t row = row0 + wm * TM + m;
             const u32x4 v = *reinterpret_cast<const u32x4*>(cs + (m * CS_PITCH + cchunk * 8) * 2);
             if (row < T && col < N) {
-                if (LOBRA_GEMM_NT_STORE) __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(C + size_t(row) * N + col));
-                else *reinterpret_cast<u32x4*>(C + size_t(row) * N + col) = v;
+                if (LOBRA_GEMM_NT_STORE) __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(C + size_t(row) * ldc + col));
+                else *reinterpret_cast<u32x4*>(C + size_t(row) * ldc + col) = v;
             }
         }
     }
@@ -548,8 +559,8 @@ void gemm_mfma_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const uint16_t
 
 template <bool W_KN, int WM, int WN, bool DMA>
 static hipError_t launch_gemm(const PlanDev& pd, const void* Z, const void* W, const void* P,
-                              const void* M, void* C, int32_t K, int32_t N, int32_t ldw,
-                              int32_t tiles_m, int32_t tiles_n, hipStream_t st)
+                              const void* M, void* C, int32_t K, int32_t N, int32_t ldw, int32_t ldc,
+                              int32_t nproj, int32_t proj, int32_t tiles_m, int32_t tiles_n, hipStream_t st)
 {
     constexpr int bytes = lds_bytes<W_KN, WN, DMA>();
     // the kernel needs more dynamic LDS than the default limit: raise it once per device
@@ -566,14 +577,16 @@ static hipError_t launch_gemm(const PlanDev& pd, const void* Z, const void* W, c
     }
     gemm_mfma_kernel<W_KN, WM, WN, DMA><<<dim3(uint32_t(tiles_m) * uint32_t(tiles_n)), 64 * WM * WN, bytes, st>>>(
         pd, (const uint16_t*)Z, (const uint16_t*)W, (const uint16_t*)P, (const uint16_t*)M, (uint16_t*)C,
-        K, N, ldw, tiles_m, tiles_n);
+        K, N, ldw, ldc, nproj, proj, tiles_m, tiles_n);
     return hipGetLastError();
 }
 
 hipError_t gemm_mfma(const PlanDev& pd, bool transW, const void* Z, const void* W, const void* P,
-                     const void* M, void* C, int32_t K, int32_t N, int32_t ldw, hipStream_t st)
+                     const void* M, void* C, int32_t K, int32_t N, int32_t ldw, hipStream_t st,
+                     int32_t ldc, int32_t nproj, int32_t proj)
 {
     if (pd.T == 0) return hipSuccess;
+    if (ldc == 0) ldc = N;
     const int32_t tiles_m = (pd.T + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
     if (int64_t(tiles_m) * tiles_n > 0x7fffffff) return hipErrorInvalidValue;
     // 32-bit byte offsets inside a tile: 256 rows of K (or ldw) elements, 64 rows of ldw elements
@@ -583,11 +596,11 @@ hipError_t gemm_mfma(const PlanDev& pd, bool transW, const void* Z, const void* 
     // the direct-to-LDS pipeline needs whole K tiles of 32; other K take the register-staged kernel
     const bool dma = LOBRA_GEMM_DMA && K % DBK == 0;
     if (!transW) {
-        if (dma) return launch_gemm<true, LOBRA_GEMM_WM, LOBRA_GEMM_WN, true>(pd, Z, W, P, M, C, K, N, ldw, tiles_m, tiles_n, st);
-        return launch_gemm<true, LOBRA_GEMM_WM, LOBRA_GEMM_WN, false>(pd, Z, W, P, M, C, K, N, ldw, tiles_m, tiles_n, st);
+        if (dma) return launch_gemm<true, LOBRA_GEMM_WM, LOBRA_GEMM_WN, true>(pd, Z, W, P, M, C, K, N, ldw, ldc, nproj, proj, tiles_m, tiles_n, st);
+        return launch_gemm<true, LOBRA_GEMM_WM, LOBRA_GEMM_WN, false>(pd, Z, W, P, M, C, K, N, ldw, ldc, nproj, proj, tiles_m, tiles_n, st);
     }
-    if (dma) return launch_gemm<false, LOBRA_GEMM_WM, LOBRA_GEMM_WN, true>(pd, Z, W, P, M, C, K, N, ldw, tiles_m, tiles_n, st);
-    return launch_gemm<false, LOBRA_GEMM_WM, LOBRA_GEMM_WN, false>(pd, Z, W, P, M, C, K, N, ldw, tiles_m, tiles_n, st);
+    if (dma) return launch_gemm<false, LOBRA_GEMM_WM, LOBRA_GEMM_WN, true>(pd, Z, W, P, M, C, K, N, ldw, ldc, nproj, proj, tiles_m, tiles_n, st);
+    return launch_gemm<false, LOBRA_GEMM_WM, LOBRA_GEMM_WN, false>(pd, Z, W, P, M, C, K, N, ldw, ldc, nproj, proj, tiles_m, tiles_n, st);
 }
 
 }  // namespace lobra

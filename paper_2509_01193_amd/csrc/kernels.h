@@ -13,6 +13,11 @@ struct GradJob {
     float* part;     // [sum over chunks of r_t, D]
     float* out;      // [R_tot, D]
     int32_t D;
+    int32_t ldz = 0;    // row pitch of Z in elements (0: D)
+    int32_t nproj = 1;  // > 1 (fused projections): only the rank window `proj` of every task;
+    int32_t proj = 0;   //   proj < 0: D spans all projections (nproj * dg columns, dg a multiple of 128)
+                        //   and a column tile takes the projection its columns lie in
+    int32_t ldp = 0;    // row pitch of part (0: D); dg when proj < 0
 };
 
 // ---- plain fp32-FMA kernels (fp32 path; bf16 storage as a cross-check) ---------------------
@@ -36,11 +41,17 @@ hipError_t reduce_partials(const PlanDev& pd, const GradJob& ja, const GradJob& 
                            hipStream_t st);
 // ---- bf16 MFMA kernels ------------------------------------------------------------------------
 // C[T, N] = Z[T, K] * op(W) + P * M_t with P bf16 [T][r_pad] (already scaled by s_t, zero beyond r_t).
+// ldc: row pitch of C (0: N).  nproj > 1: projection `proj` of a fused shared-input call - of every
+// task's ranks only the window [proj r, (proj+1) r) takes part (rows of M, columns of P); proj < 0: one
+// launch over all projections (N = nproj * pd.dg, pd.dg a multiple of 256), M compact [R_tot][pd.dg].
 hipError_t gemm_mfma(const PlanDev& pd, bool transW, const void* Z, const void* W, const void* P,
-                     const void* M, void* C, int32_t K, int32_t N, int32_t ldw, hipStream_t st);
+                     const void* M, void* C, int32_t K, int32_t N, int32_t ldw, hipStream_t st,
+                     int32_t ldc = 0, int32_t nproj = 1, int32_t proj = 0);
 // P = s_t Z M_t^T in bf16, written token-major [T][r_pad] and block-transposed [ntb][r_pad][32].
+// (ldz: row pitch of Z; nproj > 1: projection `proj` of a fused call - rank window, see the kernel)
 hipError_t shrink_mfma(const PlanDev& pd, const void* Z, const void* M, const float* s,
-                       void* P_tok, void* P_blk, int32_t D, hipStream_t st);
+                       void* P_tok, void* P_blk, int32_t D, int32_t ldz, int32_t nproj, int32_t proj,
+                       hipStream_t st);
 
 // Stage 1 of dM_t = sum_i P_i^T Z_i from the block-transposed P; partial sums per reduction chunk.
 // (P = block-transposed bf16 copy; one launch for up to two gradients, jb.P == nullptr: only ja.)

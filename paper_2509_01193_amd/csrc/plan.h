@@ -28,6 +28,8 @@ struct Plan {
     uint32_t flags = 0;
     bool mfma = false;                  // bf16 storage and MFMA kernels
     int32_t r_max = 0, r_pad = 0, R_tot = 0;
+    int32_t n_proj = 1;                 // shared-input projections fused into the call
+    int32_t dg = 0;                     // d_out / n_proj: width of B and dB
     std::vector<int32_t> rank_off;      // [n_tasks+1]
     std::vector<int32_t> seg_off_in, seg_task_in;   // the caller's table, as given
     std::vector<int32_t> cseg_off, cseg_task;       // compacted table

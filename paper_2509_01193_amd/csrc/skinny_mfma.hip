@@ -41,16 +41,22 @@ __global__ __launch_bounds__(64 * NWV) void shrink_mfma_kernel(PlanDev pd, const
                                                           const uint16_t* __restrict__ M,
                                                           const float* __restrict__ s,
                                                           uint16_t* __restrict__ P_tok,
-                                                          uint16_t* __restrict__ P_blk, int32_t D)
+                                                          uint16_t* __restrict__ P_blk, int32_t D,
+                                                          int32_t ldz, int32_t nproj, int32_t proj)
 {
+    // nproj > 1 (fused shared-input projections): this launch handles projection `proj` only - Z is
+    // that projection's column block of dy (row pitch ldz), M its rows of the compact up factors,
+    // and the task's rank rows it reads and writes are the window [proj r, (proj + 1) r).
     __shared__ float red[NWV][2][NRB][64][4];   // [wave][token half][rank block][lane][4]
     const int32_t tb0 = NTB == 1 ? int32_t(blockIdx.x) : pd.sb_off[blockIdx.x];
     const int32_t cnt = NTB == 1 ? 1 : pd.sb_off[blockIdx.x + 1] - tb0;
     TokenBlock b[NTB];
 #pragma unroll
     for (int t = 0; t < NTB; ++t) b[t] = pd.tb[tb0 + min(t, cnt - 1)];
-    const int32_t rank_row0 = b[0].rank_row0;
-    const int32_t r = pd.rank_off[b[0].task + 1] - rank_row0;
+    const int32_t r = (pd.rank_off[b[0].task + 1] - b[0].rank_row0) / nproj;
+    const int32_t pofs = proj * r;               // first rank of the window inside the task's rows
+    const int32_t rank_row0 = b[0].rank_row0 + pofs;
+    const int32_t plim = proj == nproj - 1 ? pd.r_pad - pofs : r;   // ranks (and zero padding) stored by this launch
     const int32_t nrb_t = (r + 15) >> 4;        // rank blocks this task needs (uniform)
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int j = lane & 15, kg = lane >> 4;
@@ -70,7 +76,7 @@ __global__ __launch_bounds__(64 * NWV) void shrink_mfma_kernel(PlanDev pd, const
     for (int t = 0; t < NTB; ++t)
 #pragma unroll
         for (int h = 0; h < 2; ++h)
-            zrow[t][h] = Z + size_t(b[t].row0 + min(16 * h + j, b[t].nrows - 1)) * D;
+            zrow[t][h] = Z + size_t(b[t].row0 + min(16 * h + j, b[t].nrows - 1)) * ldz;
     const uint16_t* mrow[NRB];
 #pragma unroll
     for (int rb = 0; rb < NRB; ++rb) mrow[rb] = M + size_t(rank_row0 + min(16 * rb + j, r - 1)) * D;
@@ -172,15 +178,15 @@ __global__ __launch_bounds__(64 * NWV) void shrink_mfma_kernel(PlanDev pd, const
                     o[v] = (__bf16)((p < r && tok < b[t].nrows) ? st * sum : 0.f);
                 }
                 const int32_t p0 = 16 * rb + 4 * kg;
-                if (p0 < pd.r_pad) {
+                if (p0 < plim) {
                     if (tok < b[t].nrows)
-                        *reinterpret_cast<bf16x4*>(P_tok + size_t(b[t].row0 + tok) * pd.r_pad + p0) = o;
+                        *reinterpret_cast<bf16x4*>(P_tok + size_t(b[t].row0 + tok) * pd.r_pad + pofs + p0) = o;
                     // block-transposed copy [block][rank][32 tokens]; tokens beyond the block hold 0
 #pragma unroll
                     for (int v = 0; v < 4; ++v) {
                         union { __bf16 b; uint16_t u; } c;
                         c.b = o[v];
-                        P_blk[(size_t(tb0 + t) * pd.r_pad + p0 + v) * kTokenBlock + tok] = c.u;
+                        P_blk[(size_t(tb0 + t) * pd.r_pad + pofs + p0 + v) * kTokenBlock + tok] = c.u;
                     }
                 }
             }
@@ -189,14 +195,16 @@ __global__ __launch_bounds__(64 * NWV) void shrink_mfma_kernel(PlanDev pd, const
 }
 
 hipError_t shrink_mfma(const PlanDev& pd, const void* Z, const void* M, const float* s,
-                       void* P_tok, void* P_blk, int32_t D, hipStream_t st)
+                       void* P_tok, void* P_blk, int32_t D, int32_t ldz, int32_t nproj, int32_t proj,
+                       hipStream_t st)
 {
     if (pd.ntb == 0) return hipSuccess;
-    const int nrb = pd.r_pad / 16;
+    // rank blocks of the widest window (nproj = 1: of the widest task)
+    const int nrb = (pd.r_max / nproj + 15) / 16;
 #define LOBRA_SHRINK(NRB, NTB, DEPTH)                                                                  \
     shrink_mfma_kernel<NRB, 4, NTB, DEPTH><<<(NTB == 1 ? pd.ntb : pd.nsb), 256, 0, st>>>(                \
-        pd, (const uint16_t*)Z, (const uint16_t*)M, s, (uint16_t*)P_tok, (uint16_t*)P_blk, D)
-    if (pd.shrink_group == 1) {
+        pd, (const uint16_t*)Z, (const uint16_t*)M, s, (uint16_t*)P_tok, (uint16_t*)P_blk, D, ldz, nproj, proj)
+    if (pd.shrink_group == 1 || nproj > 1) {
         if (nrb <= 1) LOBRA_SHRINK(1, 1, 3);
         else if (nrb <= 2) LOBRA_SHRINK(2, 1, 2);
         else if (nrb <= 4) LOBRA_SHRINK(4, 1, 2);
@@ -234,10 +242,17 @@ __global__ __launch_bounds__(256) void grad_mfma_kernel(PlanDev pd, GradJob ja, 
     const uint16_t* __restrict__ Z = static_cast<const uint16_t*>(first ? ja.Z : jb.Z);
     float* __restrict__ part = first ? ja.part : jb.part;
     const int32_t D = first ? ja.D : jb.D;
+    const int32_t ldz = (first ? ja.ldz : jb.ldz) ? (first ? ja.ldz : jb.ldz) : D;   // row pitch of Z (elements)
+    const int32_t nproj = first ? ja.nproj : jb.nproj;    // > 1: only the rank window of one projection
     const int32_t coltile = first ? int32_t(blockIdx.y) : int32_t(blockIdx.y) - tiles_a;
+    const int32_t proj_in = first ? ja.proj : jb.proj;
+    const int32_t proj = proj_in >= 0 ? proj_in : coltile * (16 * CW) / pd.dg;   // projection of this column tile
+    const int32_t pcol0 = proj_in >= 0 ? 0 : proj * pd.dg;                      // its first column
+    const int32_t ldp = (first ? ja.ldp : jb.ldp) ? (first ? ja.ldp : jb.ldp) : D;   // row pitch of part
     __shared__ float red[2][NRB][CW][64][4];
     const GradChunk ch = pd.chunks[blockIdx.x];
-    const int32_t r = pd.rank_off[ch.task + 1] - pd.rank_off[ch.task];
+    const int32_t r = (pd.rank_off[ch.task + 1] - pd.rank_off[ch.task]) / nproj;
+    const int32_t pofs = proj * r;                        // first rank of the window inside the task's rows
     const int32_t rb0 = blockIdx.z * NRB;                 // first rank block of this pass
     if (16 * rb0 >= r) return;                            // uniform: nothing to do for this task
     const int32_t nrb_t = min(NRB, (r - 16 * rb0 + 15) >> 4);   // rank blocks needed (uniform)
@@ -260,12 +275,12 @@ __global__ __launch_bounds__(256) void grad_mfma_kernel(PlanDev pd, GradJob ja, 
         if (tile_full) {
 #pragma unroll
             for (int q = 0; q < 8; ++q)
-                zin[q] = *reinterpret_cast<const zvec*>(Z + size_t(b.row0 + min(8 * g + q, b.nrows - 1)) * D + col);
+                zin[q] = *reinterpret_cast<const zvec*>(Z + size_t(b.row0 + min(8 * g + q, b.nrows - 1)) * ldz + col);
         } else {
 #pragma unroll
             for (int q = 0; q < 8; ++q) {
                 const int32_t row = b.row0 + min(8 * g + q, b.nrows - 1);
-                zin[q] = col_in ? *reinterpret_cast<const zvec*>(Z + size_t(row) * D + col) : zvec(0u);
+                zin[q] = col_in ? *reinterpret_cast<const zvec*>(Z + size_t(row) * ldz + col) : zvec(0u);
             }
         }
         u32x4 pf[NRB];
@@ -273,7 +288,7 @@ __global__ __launch_bounds__(256) void grad_mfma_kernel(PlanDev pd, GradJob ja, 
         for (int rb = 0; rb < NRB; ++rb)
             if (rb < nrb_t)
                 pf[rb] = *reinterpret_cast<const u32x4*>(
-                    P_blk + (size_t(bi) * pd.r_pad + 16 * (rb0 + rb) + c) * kTokenBlock + 8 * g);
+                    P_blk + (size_t(bi) * pd.r_pad + min(pofs + 16 * (rb0 + rb) + c, pd.r_pad - 1)) * kTokenBlock + 8 * g);
 #pragma unroll
         for (int jj = 0; jj < CW; ++jj) {
             u32x4 f;
@@ -323,7 +338,7 @@ __global__ __launch_bounds__(256) void grad_mfma_kernel(PlanDev pd, GradJob ja, 
             for (int v = 0; v < 4; ++v) {
                 const int32_t p = 16 * (rb0 + rb) + 4 * g + v;
                 if (p >= r) continue;
-                float* dst = part + size_t(ch.part_row0 + p) * D + col;
+                float* dst = part + size_t(ch.part_row0 + pofs + p) * ldp + (col - pcol0);
 #pragma unroll
                 for (int j4 = 0; j4 < CW; j4 += 4) {
                     ovec o;
@@ -338,7 +353,8 @@ __global__ __launch_bounds__(256) void grad_mfma_kernel(PlanDev pd, GradJob ja, 
 hipError_t grad_mfma(const PlanDev& pd, const GradJob& ja, const GradJob& jb, hipStream_t st)
 {
     if (pd.nchunks == 0) return hipSuccess;
-    const int nrb = pd.r_pad / 16;
+    // rank blocks of the widest window (both jobs of a launch have the same nproj)
+    const int nrb = ja.nproj > 1 ? (pd.r_max / ja.nproj + 15) / 16 : pd.r_pad / 16;
     const int NRB = nrb <= 1 ? 1 : (nrb <= 2 ? 2 : 4);
     const int cw = NRB == 4 ? 4 : 8;
     const int32_t tw = 16 * cw;

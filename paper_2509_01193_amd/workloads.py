@@ -77,6 +77,7 @@ class Problem:
     seg_task: np.ndarray       # [S] int32, -1 = no adapter
     seqs: list                 # [(length, task)] in packed order, before merging
     seed: int
+    n_proj: int = 1            # > 1: that many layers reading the same x, fused (ranks stacked, B compact)
     x: np.ndarray = None       # [T, d_in]      float32, or uint16 bf16 bits
     W: np.ndarray = None       # [d_in, d_out]
     A: np.ndarray = None       # [R_tot, d_in]  (down projections, stacked by task)
@@ -110,7 +111,7 @@ class Problem:
         """fwd+bwd flops the method itself needs: base product twice plus six rank-r products."""
         cnt = self.task_tokens()
         base = 4.0 * self.T * self.d_in * self.d_out
-        lora = 6.0 * float((cnt * self.ranks).sum()) * (self.d_in + self.d_out)
+        lora = 6.0 * float((cnt * self.ranks).sum()) * (self.d_in + self.d_out // self.n_proj)
         return base + lora
 
     def fill(self, std_x=0.02, std_w=0.02, std_a=0.02, std_b=0.02, std_dy=1.0):
@@ -118,7 +119,7 @@ class Problem:
         self.x = _normal(sd, 1, (self.T, self.d_in), std_x, dt)
         self.W = _normal(sd, 2, (self.d_in, self.d_out), std_w, dt)
         self.A = _normal(sd, 3, (self.R_tot, self.d_in), std_a, dt)
-        self.B = _normal(sd, 4, (self.R_tot, self.d_out), std_b, dt)
+        self.B = _normal(sd, 4, (self.R_tot, self.d_out // self.n_proj), std_b, dt)
         self.dy = _normal(sd, 5, (self.T, self.d_out), std_dy, dt)
         return self
 
@@ -274,6 +275,16 @@ def make_config(cfg: int, order: str = "shuffled", d_in: int = None, d_out: int 
                 ranks=ranks, s=np.full(len(ranks), scale, np.float32),
                 seg_off=seg_off, seg_task=seg_task, seqs=seqs, seed=seed)
     return p.fill(**fill_kw) if fill else p
+
+
+def fuse_projections(p: Problem, n_proj: int, fill: bool = True, **fill_kw) -> Problem:
+    """`n_proj` layers of p's shape that read the same x (q/k/v, gate/up), as one fused problem:
+    W [d_in, n_proj d_out], every task's ranks stacked n_proj times (rows j r_t .. of a task belong
+    to projection j), B compact [R_tot, d_out], y/dy [T, n_proj d_out].  Token structure as in p."""
+    q = Problem(name=p.name + "-x%d" % n_proj, dtype=p.dtype, T=p.T, d_in=p.d_in, d_out=n_proj * p.d_out,
+                ranks=(n_proj * p.ranks).astype(np.int32), s=p.s.copy(), seg_off=p.seg_off.copy(),
+                seg_task=p.seg_task.copy(), seqs=list(p.seqs), seed=p.seed + 7919 * n_proj, n_proj=n_proj)
+    return q.fill(**fill_kw) if fill else q
 
 
 def pad_to_buckets(p: Problem, bounds, fill: bool = True, **fill_kw) -> Problem:

@@ -22,6 +22,8 @@ def relerr(got, ref):
 
 
 def make_oracle(p):
+    if p.n_proj > 1:
+        return oracle.FusedProjections(p.n_proj, p.x, p.W, p.A, p.B, p.s, p.dy, p.rank_off, p.seg_off, p.seg_task)
     return oracle.Oracle(p.x, p.W, p.A, p.B, p.s, p.dy, p.rank_off, p.seg_off, p.seg_task)
 
 
@@ -417,3 +419,49 @@ def test_shared_input_projection_fusion_through_the_same_entry_point():
             a, b = df.dB[rows, j * d:(j + 1) * d], dq.dB[t * r:(t + 1) * r]
             assert ((a - b).abs().max() / b.abs().max()).item() < 1e-2
     check_problem(fused, label="fused qkv")            # and the fused call itself against the oracle
+
+
+# ---------------------------------------------------------------------------------------------
+# fused shared-input projections (desc.n_proj > 1): stacked down factors, compact up factors
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("n_proj,d_in,dg,ranks", [
+    (3, 320, 256, [16, 16, 16, 16]),      # q/k/v at the benchmark's rank; whole K tiles
+    (2, 264, 192, [8, 16, 32, 64]),       # gate/up, heterogeneous ranks, widths off the tile grid
+    (3, 128, 64, [8, 24, 40]),            # windows that are not multiples of 16
+    (4, 192, 128, [32]),                  # one task, stacked rank 128
+])
+def test_fused_shared_input_projections(n_proj, d_in, dg, ranks):
+    import torch
+    base = wl.make_config(2, "shuffled", d_in=d_in, d_out=dg, fill=False)
+    base.ranks = np.asarray(ranks, np.int32)
+    base.s = np.linspace(0.5, 2.0, len(ranks)).astype(np.float32)
+    base.seg_task = (base.seg_task % len(ranks)).astype(np.int32)
+    base.seg_off, base.seg_task = wl.segments_from_sequences(
+        [(int(base.seg_off[k + 1] - base.seg_off[k]), int(base.seg_task[k])) for k in range(base.S)])
+    f = wl.fuse_projections(base, n_proj)
+    dp, _ = check_problem(f, label="fused x%d" % n_proj)
+    want = [t.clone() for t in (dp.y, dp.dx, dp.dA, dp.dB)]
+    # recomputed H, dx skipped, gradients accumulated: same numbers
+    dp.dA.fill_(1.0)
+    dp.dB.fill_(-2.0)
+    dp.dx.fill_(9.0)
+    dp.bwd(use_saved_h=False, flags=bd.FLAG_ACCUMULATE_GRADS | bd.FLAG_NO_DX)
+    torch.cuda.synchronize()
+    assert bool((dp.dx.float() == 9.0).all())
+    assert torch.allclose(dp.dA - 1.0, want[2], rtol=0, atol=1e-5 * float(want[2].abs().max()) + 1e-6)
+    assert torch.allclose(dp.dB + 2.0, want[3], rtol=0, atol=1e-5 * float(want[3].abs().max()) + 1e-6)
+    # against n_proj separate calls on the slices: y and the gradients are the same arithmetic
+    ro = f.rank_off
+    for j in range(n_proj):
+        rows = np.concatenate([np.arange(ro[t] + j * r, ro[t] + (j + 1) * r) for t, r in enumerate(base.ranks)])
+        q = wl.make_custom("part%d" % j, "bf16", d_in, dg, base.ranks, base.seg_off, base.seg_task, 1, s=base.s, fill=False)
+        q.x, q.W, q.dy = f.x, np.ascontiguousarray(f.W[:, j * dg:(j + 1) * dg]), np.ascontiguousarray(f.dy[:, j * dg:(j + 1) * dg])
+        q.A, q.B = np.ascontiguousarray(f.A[rows]), np.ascontiguousarray(f.B[rows])
+        dq = bd.DeviceProblem(q)
+        dq.step()
+        torch.cuda.synchronize()
+        idx = torch.from_numpy(rows).to(dp.dev)
+        assert torch.equal(want[0][:, j * dg:(j + 1) * dg], dq.y), j
+        assert torch.equal(want[3].index_select(0, idx), dq.dB), j
+        ref = dq.dA
+        assert float((want[2].index_select(0, idx) - ref).abs().max()) <= 1e-5 * float(ref.abs().max()), j

@@ -330,3 +330,35 @@ def test_planted_mistake_is_caught(name, old, new, monkeypatch):
             except (AssertionError, ValueError):
                 caught.append(pin.__name__)
         assert caught, "no pin noticed the planted mistake: " + name
+
+
+def test_fused_projections_are_the_block_diagonal_dense_layer():
+    """P layers that share x, as the oracle composes them, equal ONE layer of the pinned oracle whose up
+    factors are block-diagonal over the concatenated outputs (and P = 1 is the layer itself)."""
+    from paper_2509_01193_amd import workloads as wl
+    base = wl.make_custom("b", "bf16", 24, 16, [8, 16], [0, 5, 9, 30, 41], [0, 1, -1, 0], 5)
+    for P in (1, 2, 3):
+        f = wl.fuse_projections(base, P)
+        fo = oracle.FusedProjections(P, f.x, f.W, f.A, f.B, f.s, f.dy, f.rank_off, f.seg_off, f.seg_task)
+        dg, ro = base.d_out, f.rank_off
+        Bd = np.zeros((f.R_tot, P * dg), np.uint16)
+        for t in range(f.n_tasks):
+            r = int(f.ranks[t]) // P
+            for j in range(P):
+                rows = slice(ro[t] + j * r, ro[t] + (j + 1) * r)
+                Bd[rows, j * dg:(j + 1) * dg] = f.B[rows]
+        do = oracle.Oracle(f.x, f.W, f.A, Bd, f.s, f.dy, f.rank_off, f.seg_off, f.seg_task)
+        assert np.array_equal(fo.y(), do.y())
+        assert np.allclose(fo.dx(), do.dx(), rtol=1e-13, atol=0)
+        (a1, b1), (a2, b2) = fo.grads(), do.grads()
+        assert np.allclose(a1, a2, rtol=1e-13, atol=0)
+        for t in range(f.n_tasks):
+            r = int(f.ranks[t]) // P
+            for j in range(P):
+                rows = slice(ro[t] + j * r, ro[t] + (j + 1) * r)
+                assert np.allclose(b1[rows], b2[rows, j * dg:(j + 1) * dg], rtol=1e-13, atol=0)
+                off = np.ones(P * dg, bool)
+                off[j * dg:(j + 1) * dg] = False
+                # what the dense layer puts outside the diagonal blocks is the gradient of entries that are
+                # structurally zero: it is not part of the fused layer
+                assert b2[rows][:, off].shape[1] == (P - 1) * dg
