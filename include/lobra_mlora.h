@@ -108,8 +108,8 @@ typedef struct {
  *     B  [R_tot, dg]     row (t, j, rho) is row rho of the up projection of task t in projection j
  *                        (it only ever meets columns of projection j);  dB alike
  * so that  y[:, j] = x W[:, j] + s_t (A_t^j x) B_t^j  and  dx = sum_j dy[:, j] W[:, j]^T + s_t (B_t^j dy[:, j]) A_t^j.
- * Requires LOBRA_BF16 without LOBRA_PLAN_PLAIN_KERNELS (else LOBRA_ERR_DTYPE), d_out a multiple of
- * 8 P, and every stacked rank a multiple of 8 P (else LOBRA_ERR_RANK / LOBRA_ERR_ALIGN). */
+ * Requires d_out a multiple of 8 P (else LOBRA_ERR_ALIGN) and every stacked rank a multiple of 8 P
+ * (else LOBRA_ERR_RANK); 1 <= P <= 16. */
 
 /* Opaque per-batch plan: the validated table plus the device-resident work lists (token
  * blocks, per-tile segment ranges, reduction chunks).  One packed batch passes through every

@@ -215,9 +215,14 @@ lobra_status lobra_mlora_fwd(const lobra_mlora_plan* plan, const void* x, const 
         if (adapters)
             LOBRA_LAUNCH(p, st, LOBRA_K_SHRINK,
                          plain_shrink(pd, dt, x, A, s, static_cast<float*>(hbuf), pd.d_in, st));
-        LOBRA_LAUNCH(p, st, LOBRA_K_GEMM,
-                     plain_gemm(pd, dt, false, x, W, static_cast<const float*>(hbuf), B, y, pd.d_in,
-                                pd.d_out, pd.d_out, st));
+        const size_t esz = dt == LOBRA_F32 ? 4 : 2;
+        for (int32_t j = 0; j < p.n_proj; ++j) {        // one product per projection (one in all when n_proj = 1)
+            const size_t col = size_t(j) * pd.dg * esz;   // bytes into a row of W / y
+            LOBRA_LAUNCH(p, st, LOBRA_K_GEMM,
+                         plain_gemm(pd, dt, false, x, static_cast<const char*>(W) + col,
+                                    static_cast<const float*>(hbuf), B, static_cast<char*>(y) + col, pd.d_in,
+                                    pd.dg, pd.d_out, st, pd.d_out, p.n_proj, j));
+        }
         return LOBRA_OK;
     }
     // bf16 MFMA path
@@ -286,19 +291,26 @@ lobra_status lobra_mlora_bwd(const lobra_mlora_plan* plan, const void* x, const 
                 LOBRA_LAUNCH(p, st, LOBRA_K_SHRINK, plain_shrink(pd, dt, x, A, s, Hr, pd.d_in, st));
                 H = Hr;
             }
-            LOBRA_LAUNCH(p, st, LOBRA_K_SHRINK, plain_shrink(pd, dt, dy, B, s, G, pd.d_out, st));
+            const size_t esz = dt == LOBRA_F32 ? 4 : 2;
+            for (int32_t j = 0; j < p.n_proj; ++j)
+                LOBRA_LAUNCH(p, st, LOBRA_K_SHRINK,
+                             plain_shrink(pd, dt, static_cast<const char*>(dy) + size_t(j) * pd.dg * esz, B, s, G,
+                                          pd.dg, st, pd.d_out, p.n_proj, j));
         }
         if (want_dx && p.desc.T > 0)
             LOBRA_LAUNCH(p, st, LOBRA_K_GEMM,
                          plain_gemm(pd, dt, true, dy, W, G, A, dx, pd.d_out, pd.d_in, pd.d_out, st));
         if (p.R_tot > 0) {
             if (adapters) {
-                LOBRA_LAUNCH(p, st, LOBRA_K_GRAD_STAGE1,
-                             plain_grad_stage1(pd, dt, false, H, dy, part_b, pd.d_out, st));
+                const size_t esz = dt == LOBRA_F32 ? 4 : 2;
+                for (int32_t j = 0; j < p.n_proj; ++j)
+                    LOBRA_LAUNCH(p, st, LOBRA_K_GRAD_STAGE1,
+                                 plain_grad_stage1(pd, dt, false, H, static_cast<const char*>(dy) + size_t(j) * pd.dg * esz,
+                                                   part_b, pd.dg, st, pd.d_out, p.n_proj, j));
                 LOBRA_LAUNCH(p, st, LOBRA_K_GRAD_STAGE1,
                              plain_grad_stage1(pd, dt, false, G, x, part_a, pd.d_in, st));
             }
-            const GradJob jb{H, dy, part_b, dB, pd.d_out}, ja{G, x, part_a, dA, pd.d_in};
+            const GradJob jb{H, dy, part_b, dB, pd.dg}, ja{G, x, part_a, dA, pd.d_in};
             LOBRA_LAUNCH(p, st, LOBRA_K_GRAD_STAGE2, reduce_partials(pd, jb, ja, accumulate, st));
         }
         return LOBRA_OK;

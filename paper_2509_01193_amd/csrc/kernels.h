@@ -22,18 +22,22 @@ struct GradJob {
 
 // ---- plain fp32-FMA kernels (fp32 path; bf16 storage as a cross-check) ---------------------
 // P[row, :r_t] = s_t * Z[row, :] M_t^T for every token of an adapter segment (fp32, stride r_max).
+// (ldz: row pitch of Z, 0 = D.  nproj > 1: projection `proj` of a fused shared-input call - only the
+//  rank window [proj r, (proj+1) r) of every task; the same three arguments below mean the same.)
 hipError_t plain_shrink(const PlanDev& pd, int dtype, const void* Z, const void* M, const float* s,
-                        float* P, int32_t D, hipStream_t st);
+                        float* P, int32_t D, hipStream_t st, int32_t ldz = 0, int32_t nproj = 1,
+                        int32_t proj = 0);
 // C[T, N] = Z[T, K] * op(W) + P[:, :r_t] * M_t ;  transW = false: op(W)[k][n] = W[k*ldw + n]
 // (forward), true: op(W)[k][n] = W[n*ldw + k] (backward).
 hipError_t plain_gemm(const PlanDev& pd, int dtype, bool transW, const void* Z, const void* W,
                       const float* P, const void* M, void* C, int32_t K, int32_t N, int32_t ldw,
-                      hipStream_t st);
+                      hipStream_t st, int32_t ldc = 0, int32_t nproj = 1, int32_t proj = 0);
 // Stage 1 of dM_t = sum over the tokens of task t of P[i, :]^T Z[i, :]: one partial sum per
 // reduction chunk, written to part[chunk.part_row0 + rho, :].
 // P is fp32 [T][r_max], or (p_bf16) bf16 [T][r_pad].
 hipError_t plain_grad_stage1(const PlanDev& pd, int dtype, bool p_bf16, const void* P, const void* Z,
-                             float* part, int32_t D, hipStream_t st);
+                             float* part, int32_t D, hipStream_t st, int32_t ldz = 0, int32_t nproj = 1,
+                             int32_t proj = 0);
 // Stage 2 (also used by the MFMA path): out[R, :] (+)= sum of the partial sums of task(R), in
 // chunk order, so that the result does not depend on scheduling.
 // One launch for up to two gradients (jb.out == nullptr: only ja).

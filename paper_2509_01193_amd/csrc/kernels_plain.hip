@@ -42,18 +42,24 @@ template <typename E, int VW>   // VW: elements per lane and step (4, or 1 for o
 __global__ __launch_bounds__(256) void plain_shrink_kernel(PlanDev pd, const E* __restrict__ Z,
                                                            const E* __restrict__ M,
                                                            const float* __restrict__ s,
-                                                           float* __restrict__ P, int32_t D)
+                                                           float* __restrict__ P, int32_t D, int32_t ldz,
+                                                           int32_t nproj, int32_t proj)
 {
+    // nproj > 1 (fused shared-input projections): projection `proj` only - Z is its column block of
+    // dy (row pitch ldz), M its rows of the compact up factors, and of the task's ranks the window
+    // [proj r, (proj + 1) r) is read and written
     const TokenBlock b = pd.tb[blockIdx.x];
-    const int32_t r = pd.rank_off[b.task + 1] - pd.rank_off[b.task];
+    const int32_t r = (pd.rank_off[b.task + 1] - pd.rank_off[b.task]) / nproj;
+    const int32_t pofs = proj * r;
+    const int32_t plim = proj == nproj - 1 ? pd.r_max - pofs : r;   // ranks (and zero padding) stored here
     const float st = s[b.task];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int32_t rr0 = 8 * wave;
     if (rr0 >= b.nrows) return;
     size_t zoff[8];          // rows beyond the block repeat its last row; their sums are not stored
 #pragma unroll
-    for (int i = 0; i < 8; ++i) zoff[i] = size_t(b.row0 + min(rr0 + i, b.nrows - 1)) * D;
-    for (int32_t p0 = 0; p0 < pd.r_max; p0 += 8) {
+    for (int i = 0; i < 8; ++i) zoff[i] = size_t(b.row0 + min(rr0 + i, b.nrows - 1)) * ldz;
+    for (int32_t p0 = 0; p0 < plim; p0 += 8) {
         float acc[8][8];
 #pragma unroll
         for (int i = 0; i < 8; ++i)
@@ -62,7 +68,7 @@ __global__ __launch_bounds__(256) void plain_shrink_kernel(PlanDev pd, const E* 
         if (p0 < r) {
             size_t moff[8];  // ranks beyond r_t repeat the last rank row; their sums are not stored
 #pragma unroll
-            for (int q = 0; q < 8; ++q) moff[q] = size_t(b.rank_row0 + min(p0 + q, r - 1)) * D;
+            for (int q = 0; q < 8; ++q) moff[q] = size_t(b.rank_row0 + pofs + min(p0 + q, r - 1)) * D;
             for (int32_t k = VW * lane; k < D; k += VW * 64) {
                 float z[8][VW], m[8][VW];
 #pragma unroll
@@ -96,18 +102,19 @@ __global__ __launch_bounds__(256) void plain_shrink_kernel(PlanDev pd, const E* 
             for (int q = 0; q < 8; ++q)
                 if (lane == 8 * i + q) v = acc[i][q];
         const int i = lane >> 3, q = lane & 7;
-        if (rr0 + i < b.nrows && p0 + q < pd.r_max)
-            P[size_t(b.row0 + rr0 + i) * pd.r_max + p0 + q] = (p0 + q < r) ? st * v : 0.f;
+        if (rr0 + i < b.nrows && p0 + q < plim)
+            P[size_t(b.row0 + rr0 + i) * pd.r_max + pofs + p0 + q] = (p0 + q < r) ? st * v : 0.f;
     }
 }
 
 hipError_t plain_shrink(const PlanDev& pd, int dtype, const void* Z, const void* M, const float* s,
-                        float* P, int32_t D, hipStream_t st)
+                        float* P, int32_t D, hipStream_t st, int32_t ldz, int32_t nproj, int32_t proj)
 {
     if (pd.ntb == 0) return hipSuccess;
-    const bool vec = (D & 3) == 0;   // rows then start on 16-byte (fp32) or 8-byte (bf16) boundaries
+    if (ldz == 0) ldz = D;
+    const bool vec = (D & 3) == 0 && (ldz & 3) == 0;   // rows then start on 16-byte (fp32) or 8-byte (bf16) boundaries
 #define LOBRA_PLAIN_SHRINK(E, VW) \
-    plain_shrink_kernel<E, VW><<<pd.ntb, 256, 0, st>>>(pd, (const E*)Z, (const E*)M, s, P, D)
+    plain_shrink_kernel<E, VW><<<pd.ntb, 256, 0, st>>>(pd, (const E*)Z, (const E*)M, s, P, D, ldz, nproj, proj)
     if (dtype == LOBRA_F32) {
         if (vec) LOBRA_PLAIN_SHRINK(float, 4); else LOBRA_PLAIN_SHRINK(float, 1);
     } else {
@@ -125,8 +132,11 @@ __global__ __launch_bounds__(256) void plain_gemm_kernel(PlanDev pd, const E* __
                                                          const E* __restrict__ W,
                                                          const float* __restrict__ P,
                                                          const E* __restrict__ M, E* __restrict__ C,
-                                                         int32_t K, int32_t N, int32_t ldw)
+                                                         int32_t K, int32_t N, int32_t ldw, int32_t ldc,
+                                                         int32_t nproj, int32_t proj)
 {
+    // ldc: row pitch of C.  nproj > 1: projection `proj` of a fused shared-input call - of every task's
+    // ranks only the window [proj r, (proj + 1) r) takes part (columns of P, rows of M; M pitch N)
     __shared__ float Zs[16][64 + 4];
     __shared__ float Ws[16][64 + 4];
     const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
@@ -189,9 +199,10 @@ __global__ __launch_bounds__(256) void plain_gemm_kernel(PlanDev pd, const E* __
         if (row >= T) continue;
         const int32_t t = pd.cseg_task[segment_of_row(pd, row)];
         if (t >= 0) {
-            const int32_t r0 = pd.rank_off[t], r = pd.rank_off[t + 1] - r0;
+            const int32_t r = (pd.rank_off[t + 1] - pd.rank_off[t]) / nproj, pofs = proj * r;
+            const int32_t r0 = pd.rank_off[t] + pofs;
             for (int32_t p = 0; p < r; ++p) {
-                const float pv = P[size_t(row) * pd.r_max + p];
+                const float pv = P[size_t(row) * pd.r_max + pofs + p];
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const int32_t col = col0 + tx * 4 + j;
@@ -202,20 +213,21 @@ __global__ __launch_bounds__(256) void plain_gemm_kernel(PlanDev pd, const E* __
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int32_t col = col0 + tx * 4 + j;
-            if (col < N) Elem<E>::store(C, size_t(row) * N + col, acc[i][j]);
+            if (col < N) Elem<E>::store(C, size_t(row) * ldc + col, acc[i][j]);
         }
     }
 }
 
 hipError_t plain_gemm(const PlanDev& pd, int dtype, bool transW, const void* Z, const void* W,
                       const float* P, const void* M, void* C, int32_t K, int32_t N, int32_t ldw,
-                      hipStream_t st)
+                      hipStream_t st, int32_t ldc, int32_t nproj, int32_t proj)
 {
     if (pd.T == 0) return hipSuccess;
+    if (ldc == 0) ldc = N;
     const dim3 grid((N + 63) / 64, (pd.T + 63) / 64);
     if (grid.y > 65535u) return hipErrorInvalidValue;
 #define LOBRA_LAUNCH(E, TR) \
-    plain_gemm_kernel<E, TR><<<grid, 256, 0, st>>>(pd, (const E*)Z, (const E*)W, P, (const E*)M, (E*)C, K, N, ldw)
+    plain_gemm_kernel<E, TR><<<grid, 256, 0, st>>>(pd, (const E*)Z, (const E*)W, P, (const E*)M, (E*)C, K, N, ldw, ldc, nproj, proj)
     if (dtype == LOBRA_F32) {
         if (transW) LOBRA_LAUNCH(float, true); else LOBRA_LAUNCH(float, false);
     } else {
@@ -231,10 +243,14 @@ hipError_t plain_gemm(const PlanDev& pd, int dtype, bool transW, const void* Z, 
 template <typename E, typename PE>
 __global__ __launch_bounds__(256) void plain_gradreduce_kernel(PlanDev pd, const PE* __restrict__ P,
                                                                int32_t pstride, const E* __restrict__ Z,
-                                                               float* __restrict__ part, int32_t D)
+                                                               float* __restrict__ part, int32_t D, int32_t ldz,
+                                                               int32_t nproj, int32_t proj)
 {
+    // nproj > 1: projection `proj` of a fused call - Z is its column block (row pitch ldz), and of the
+    // task's ranks only the window [proj r, (proj + 1) r) is reduced (columns of P, rows of part)
     const GradChunk c = pd.chunks[blockIdx.x];
-    const int32_t r = pd.rank_off[c.task + 1] - pd.rank_off[c.task];
+    const int32_t r = (pd.rank_off[c.task + 1] - pd.rank_off[c.task]) / nproj;
+    const int32_t pofs = proj * r;
     const int32_t col = blockIdx.y * 256 + threadIdx.x;
     const bool live = col < D;
     for (int32_t p0 = 0; p0 < r; p0 += 16) {
@@ -247,21 +263,21 @@ __global__ __launch_bounds__(256) void plain_gradreduce_kernel(PlanDev pd, const
                 float z[4];
 #pragma unroll
                 for (int u = 0; u < 4; ++u)
-                    z[u] = (live && rr + u < b.nrows) ? Elem<E>::load(Z, size_t(b.row0 + rr + u) * D + col) : 0.f;
+                    z[u] = (live && rr + u < b.nrows) ? Elem<E>::load(Z, size_t(b.row0 + rr + u) * ldz + col) : 0.f;
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
                     if (rr + u >= b.nrows) break;
                     const size_t row = size_t(b.row0 + rr + u);
 #pragma unroll
                     for (int q = 0; q < 16; ++q)
-                        if (p0 + q < r) acc[q] = fmaf(Elem<PE>::load(P, row * pstride + p0 + q), z[u], acc[q]);
+                        if (p0 + q < r) acc[q] = fmaf(Elem<PE>::load(P, row * pstride + pofs + p0 + q), z[u], acc[q]);
                 }
             }
         }
         if (live)
 #pragma unroll
             for (int q = 0; q < 16; ++q)
-                if (p0 + q < r) part[size_t(c.part_row0 + p0 + q) * D + col] = acc[q];
+                if (p0 + q < r) part[size_t(c.part_row0 + pofs + p0 + q) * D + col] = acc[q];
     }
 }
 
@@ -326,17 +342,18 @@ hipError_t reduce_partials(const PlanDev& pd, const GradJob& ja, const GradJob& 
 }
 
 hipError_t plain_grad_stage1(const PlanDev& pd, int dtype, bool p_bf16, const void* P, const void* Z,
-                             float* part, int32_t D, hipStream_t st)
+                             float* part, int32_t D, hipStream_t st, int32_t ldz, int32_t nproj, int32_t proj)
 {
     if (pd.nchunks == 0) return hipSuccess;
+    if (ldz == 0) ldz = D;
     const dim3 grid(pd.nchunks, (D + 255) / 256);
     if (grid.y > 65535u) return hipErrorInvalidValue;
     if (dtype == LOBRA_F32)
-        plain_gradreduce_kernel<float, float><<<grid, 256, 0, st>>>(pd, (const float*)P, pd.r_max, (const float*)Z, part, D);
+        plain_gradreduce_kernel<float, float><<<grid, 256, 0, st>>>(pd, (const float*)P, pd.r_max, (const float*)Z, part, D, ldz, nproj, proj);
     else if (!p_bf16)
-        plain_gradreduce_kernel<uint16_t, float><<<grid, 256, 0, st>>>(pd, (const float*)P, pd.r_max, (const uint16_t*)Z, part, D);
+        plain_gradreduce_kernel<uint16_t, float><<<grid, 256, 0, st>>>(pd, (const float*)P, pd.r_max, (const uint16_t*)Z, part, D, ldz, nproj, proj);
     else
-        plain_gradreduce_kernel<uint16_t, uint16_t><<<grid, 256, 0, st>>>(pd, (const uint16_t*)P, pd.r_pad, (const uint16_t*)Z, part, D);
+        plain_gradreduce_kernel<uint16_t, uint16_t><<<grid, 256, 0, st>>>(pd, (const uint16_t*)P, pd.r_pad, (const uint16_t*)Z, part, D, ldz, nproj, proj);
     return hipGetLastError();
 }
 

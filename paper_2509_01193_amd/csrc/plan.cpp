@@ -21,10 +21,7 @@ lobra_status validate(const lobra_mlora_desc* d)
     if (d->dtype == LOBRA_BF16 && (d->d_in % 8 != 0 || d->d_out % 8 != 0)) return LOBRA_ERR_ALIGN;
     if (d->n_proj < 0 || d->n_proj > 16) return LOBRA_ERR_SHAPE;
     const int32_t P = d->n_proj > 1 ? d->n_proj : 1;
-    if (P > 1) {
-        if (d->dtype != LOBRA_BF16) return LOBRA_ERR_DTYPE;
-        if (d->d_out % (8 * P) != 0) return LOBRA_ERR_ALIGN;
-    }
+    if (P > 1 && d->d_out % (8 * P) != 0) return LOBRA_ERR_ALIGN;
     if (d->n_tasks > 0) {
         if (!d->rank_off) return LOBRA_ERR_NULL;
         if (d->rank_off[0] != 0) return LOBRA_ERR_RANK;
@@ -54,7 +51,7 @@ lobra_status build_host_plan(const lobra_mlora_desc* d, uint32_t flags, Plan* p)
         p->mfma = kMfmaKernels && d->dtype == LOBRA_BF16 && !(flags & LOBRA_PLAN_PLAIN_KERNELS);
         p->n_proj = d->n_proj > 1 ? d->n_proj : 1;
         p->dg = d->d_out / p->n_proj;
-        if (p->n_proj > 1 && !p->mfma) return LOBRA_ERR_DTYPE;   // fused projections: MFMA kernels only
+
         const int32_t n = d->n_tasks;
         p->rank_off.assign(size_t(n) + 1, 0);
         for (int32_t t = 0; t <= n && n > 0; ++t) p->rank_off[t] = d->rank_off[t];

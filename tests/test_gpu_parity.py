@@ -424,6 +424,17 @@ def test_shared_input_projection_fusion_through_the_same_entry_point():
 # ---------------------------------------------------------------------------------------------
 # fused shared-input projections (desc.n_proj > 1): stacked down factors, compact up factors
 # ---------------------------------------------------------------------------------------------
+def _fused_base(d_in, dg, ranks, dtype="bf16"):
+    """Workload 2's token structure on a narrow layer with the given per-projection ranks."""
+    base = wl.make_config(2, "shuffled", d_in=d_in, d_out=dg, fill=False)
+    base.dtype = dtype
+    base.ranks = np.asarray(ranks, np.int32)
+    base.s = np.linspace(0.5, 2.0, len(ranks)).astype(np.float32)
+    base.seg_off, base.seg_task = wl.segments_from_sequences(
+        [(int(base.seg_off[k + 1] - base.seg_off[k]), int(base.seg_task[k]) % len(ranks)) for k in range(base.S)])
+    return base
+
+
 @pytest.mark.parametrize("n_proj,d_in,dg,ranks", [
     (3, 320, 256, [16, 16, 16, 16]),      # q/k/v at the benchmark's rank; whole K tiles
     (2, 264, 192, [8, 16, 32, 64]),       # gate/up, heterogeneous ranks, widths off the tile grid
@@ -432,12 +443,7 @@ def test_shared_input_projection_fusion_through_the_same_entry_point():
 ])
 def test_fused_shared_input_projections(n_proj, d_in, dg, ranks):
     import torch
-    base = wl.make_config(2, "shuffled", d_in=d_in, d_out=dg, fill=False)
-    base.ranks = np.asarray(ranks, np.int32)
-    base.s = np.linspace(0.5, 2.0, len(ranks)).astype(np.float32)
-    base.seg_task = (base.seg_task % len(ranks)).astype(np.int32)
-    base.seg_off, base.seg_task = wl.segments_from_sequences(
-        [(int(base.seg_off[k + 1] - base.seg_off[k]), int(base.seg_task[k])) for k in range(base.S)])
+    base = _fused_base(d_in, dg, ranks)
     f = wl.fuse_projections(base, n_proj)
     dp, _ = check_problem(f, label="fused x%d" % n_proj)
     want = [t.clone() for t in (dp.y, dp.dx, dp.dA, dp.dB)]
@@ -465,3 +471,15 @@ def test_fused_shared_input_projections(n_proj, d_in, dg, ranks):
         assert torch.equal(want[3].index_select(0, idx), dq.dB), j
         ref = dq.dA
         assert float((want[2].index_select(0, idx) - ref).abs().max()) <= 1e-5 * float(ref.abs().max()), j
+
+
+@pytest.mark.parametrize("dtype,flags", [("f32", 0), ("bf16", bd.PLAN_PLAIN_KERNELS)])
+def test_fused_shared_input_projections_on_the_plain_kernels(dtype, flags):
+    f = wl.fuse_projections(_fused_base(136, 72, [8, 16, 24], dtype), 3)
+    dp, _ = check_problem(f, plan_flags=flags, label="fused x3 plain %s" % dtype)
+    import torch
+    want = [t.clone() for t in (dp.dA, dp.dB)]
+    dp.bwd(use_saved_h=False)                     # recomputed H
+    torch.cuda.synchronize()
+    assert torch.equal(dp.dA, want[0]) and torch.equal(dp.dB, want[1])
+
