@@ -10,12 +10,15 @@ int main() {
   for (int it = 0; it < 3000; ++it) {
     int S = rng() % 40, n = rng() % 6;
     std::vector<int32_t> off(1, 0), task, ro(1, 0);
-    for (int t = 0; t < n; ++t) ro.push_back(ro.back() + 1 + rng() % 128);
+    // every third table describes fused shared-input projections: ranks and width multiples of 8 P
+    const int P = it % 3 == 2 ? 2 + int(rng() % 3) : 1;
+    for (int t = 0; t < n; ++t) ro.push_back(ro.back() + (P > 1 ? 8 * P * (1 + int(rng() % (16 / P))) : 1 + int(rng() % 128)));
     static const int L[] = {0, 1, 2, 15, 16, 17, 31, 32, 33, 64, 100, 255, 256, 257, 1000};
     for (int k = 0; k < S; ++k) { off.push_back(off.back() + L[rng() % 15]); task.push_back(int(rng() % (n + 1)) - 1); }
     lobra_mlora_desc d{};
     d.dtype = rng() % 2; d.d_in = 8 * (1 + rng() % 600); d.d_out = 8 * (1 + rng() % 600); d.T = off.back(); d.n_tasks = n; d.S = S;
     d.rank_off = ro.data(); d.seg_off = off.data(); d.seg_task = task.data();
+    if (P > 1) { d.n_proj = P; d.d_out = 8 * P * (1 + rng() % 100); }
     if (S == 0) d.T = 0;
     lobra_status st = lobra::validate(&d);
     if (st != LOBRA_OK) { printf("validate %d at it %d\n", st, it); return 1; }
