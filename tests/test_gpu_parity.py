@@ -483,3 +483,18 @@ def test_fused_shared_input_projections_on_the_plain_kernels(dtype, flags):
     torch.cuda.synchronize()
     assert torch.equal(dp.dA, want[0]) and torch.equal(dp.dB, want[1])
 
+
+
+@pytest.mark.parametrize("name", sorted(adversarial_tables()))
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_fused_projections_adversarial_segment_tables(name, dtype):
+    """The adversarial tables above under a fused two-layer call (per-projection ranks 8, 16, 24, 64)."""
+    seg_off, seg_task = adversarial_tables()[name]
+    base = wl.make_custom(name, dtype, 136, 128, [8, 16, 24, 64], seg_off, seg_task, 99,
+                          s=[2.0, 0.5, -1.0, 3.0], fill=False)
+    f = wl.fuse_projections(base, 2)
+    dp, _ = check_problem(f, label="fused x2 %s" % dtype)
+    if name == "task_without_tokens":
+        ro = f.rank_off
+        for t in (1, 2):
+            assert not dp.dA[ro[t]:ro[t + 1]].any().item() and not dp.dB[ro[t]:ro[t + 1]].any().item()
