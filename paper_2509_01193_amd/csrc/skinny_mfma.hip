@@ -229,7 +229,7 @@ hipError_t shrink_mfma(const PlanDev& pd, const void* Z, const void* M, const fl
 // operands - operand jj holds 8 tokens of column CW c + jj - and multiplies each with the "A"
 // operand P_blk[rank][32 tokens].  MFMA jj therefore produces the columns {CW c + jj}, and a lane
 // ends up with CW consecutive columns.  Rank blocks beyond the task's rank are skipped.
-// The four waves' sums are combined through LDS in two rounds (fixed order: ((w0+w2)+(w1+w3))).
+// The four waves' sums are combined through LDS in two steps (fixed order: ((w0+w2)+(w1+w3))).
 // -------------------------------------------------------------------------------------------------
 template <int NRB, int CW>
 __global__ __launch_bounds__(256) void grad_mfma_kernel(PlanDev pd, GradJob ja, GradJob jb, int32_t tiles_a)
@@ -303,7 +303,7 @@ __global__ __launch_bounds__(256) void grad_mfma_kernel(PlanDev pd, GradJob ja, 
                                                                           acc[rb][jj], 0, 0, 0);
         }
     }
-    // round 1: waves 2, 3 hand their sums to waves 0, 1; round 2: wave 1 hands its sum to wave 0
+    // first waves 2, 3 hand their sums to waves 0, 1; then wave 1 hands its sum to wave 0
     if (wave >= 2)
 #pragma unroll
         for (int rb = 0; rb < NRB; ++rb)
