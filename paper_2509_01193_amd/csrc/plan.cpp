@@ -114,17 +114,16 @@ lobra_status build_host_plan(const lobra_mlora_desc* d, uint32_t flags, Plan* p)
             }
         }
 
-        // 3b. runs of token blocks that one workgroup of the rank-r projection handles.  A run
-        //     shares the adapter rows it loads, so longer runs cut the adapter traffic (r_t rows
-        //     per 32 token rows); they are used when the ranks are large and the batch still
-        //     yields a few workgroups per compute unit.
+        // 3b. runs of token blocks that one workgroup of the rank-r projection handles.  With large
+        //     ranks the adapter rows are most of what a single token block's workgroup reads (r_t rows
+        //     per 32 token rows), so long batches are projected in runs of four blocks that share the
+        //     rows staged in LDS; otherwise every block is its own run.
         {
-            // token-weighted mean rank: runs of two pay off when most of the work is at rank >= 48
-            int64_t wsum = 0;
+            int64_t wsum = 0;                      // token-block-weighted sum of ranks
             const int64_t ntb_all = p->task_tb_off[n];
             for (int32_t t = 0; t < n; ++t)
                 wsum += int64_t(p->task_tb_off[t + 1] - p->task_tb_off[t]) * (p->rank_off[t + 1] - p->rank_off[t]);
-            const int32_t g = (ntb_all >= 2 * 512 && wsum >= 48 * ntb_all) ? 2 : 1;
+            const int32_t g = (p->mfma && ntb_all >= 1024 && wsum >= 48 * ntb_all) ? 4 : 1;
             p->shrink_group = g;
             p->sb_off.assign(1, 0);
             for (int32_t t = 0; t < n; ++t)

@@ -37,7 +37,7 @@ struct Plan {
     std::vector<TokenBlock> tb;         // grouped by task, token order inside a task
     std::vector<int32_t> task_tb_off;   // [n_tasks+1]
     std::vector<int32_t> sb_off;        // [nsb+1] runs of <= shrink_group token blocks of one task
-    int32_t shrink_group = 1;           // token blocks that one shrink workgroup handles
+    int32_t shrink_group = 1;           // token blocks that one shrink workgroup handles (1 or 4)
     std::vector<GradChunk> chunks;      // grouped by task
     std::vector<int32_t> task_chunk_off;// [n_tasks+1]
     int32_t part_rows = 0;              // rows of the partial-sum buffer = sum over chunks of r_t

@@ -25,18 +25,16 @@ __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v)
 }  // namespace
 
 // -------------------------------------------------------------------------------------------------
-// shrink: one workgroup per run of NTB token blocks (<= 32 tokens each, all of one task), 4 waves
-// split K.  v_mfma_f32_16x16x32_bf16 with the MFMA "A" operand = 16 rank rows of M_t and the "B"
-// operand = 16 token rows of Z, so a lane ends up with 4 consecutive ranks of one token.  K is
-// walked in slabs of 128 = 4 MFMA steps of 32: in step q lane (row, kg) loads the 8 elements
+// shrink: one workgroup per token block (<= 32 tokens of one task), 4 waves split K.
+// v_mfma_f32_16x16x32_bf16 with the MFMA "A" operand = 16 rank rows of M_t and the "B" operand =
+// 16 token rows of Z, so a lane ends up with 4 consecutive ranks of one token.  K is walked in
+// slabs of 128 = 4 MFMA steps of 32: in step q lane (row, kg) loads the 8 elements
 // slab + 32 q + 8 kg .. + 7 of its row, so the four lanes of a row read one 64-byte sector per
-// load instruction and a whole 256-byte run per slab.  The rank rows of a slab are loaded once
-// for all token blocks of the run (this matters when r_t is large: r_t adapter rows per 32 token
-// rows); rank blocks beyond the task's rank are skipped.
+// load instruction and a whole 256-byte run per slab.  Rank blocks beyond the task's rank are
+// skipped.
 // -------------------------------------------------------------------------------------------------
-// NRB: rank blocks of 16 (r_t <= 16 NRB); NWV: waves; NTB: token blocks per run; DEPTH: slabs in
-// flight per wave
-template <int NRB, int NWV, int NTB, int DEPTH>
+// NRB: rank blocks of 16 (r_t <= 16 NRB); NWV: waves; DEPTH: slabs in flight per wave
+template <int NRB, int NWV, int DEPTH>
 __global__ __launch_bounds__(64 * NWV) void shrink_mfma_kernel(PlanDev pd, const uint16_t* __restrict__ Z,
                                                           const uint16_t* __restrict__ M,
                                                           const float* __restrict__ s,
@@ -48,43 +46,36 @@ __global__ __launch_bounds__(64 * NWV) void shrink_mfma_kernel(PlanDev pd, const
     // that projection's column block of dy (row pitch ldz), M its rows of the compact up factors,
     // and the task's rank rows it reads and writes are the window [proj r, (proj + 1) r).
     __shared__ float red[NWV][2][NRB][64][4];   // [wave][token half][rank block][lane][4]
-    const int32_t tb0 = NTB == 1 ? int32_t(blockIdx.x) : pd.sb_off[blockIdx.x];
-    const int32_t cnt = NTB == 1 ? 1 : pd.sb_off[blockIdx.x + 1] - tb0;
-    TokenBlock b[NTB];
-#pragma unroll
-    for (int t = 0; t < NTB; ++t) b[t] = pd.tb[tb0 + min(t, cnt - 1)];
-    const int32_t r = (pd.rank_off[b[0].task + 1] - b[0].rank_row0) / nproj;
+    const int32_t bi = blockIdx.x;
+    const TokenBlock b = pd.tb[bi];
+    const int32_t r = (pd.rank_off[b.task + 1] - b.rank_row0) / nproj;
     const int32_t pofs = proj * r;               // first rank of the window inside the task's rows
-    const int32_t rank_row0 = b[0].rank_row0 + pofs;
+    const int32_t rank_row0 = b.rank_row0 + pofs;
     const int32_t plim = proj == nproj - 1 ? pd.r_pad - pofs : r;   // ranks (and zero padding) stored by this launch
     const int32_t nrb_t = (r + 15) >> 4;        // rank blocks this task needs (uniform)
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int j = lane & 15, kg = lane >> 4;
     const u32x4 zero4 = {0u, 0u, 0u, 0u};
 
-    f32x4 acc[NTB][2][NRB];
+    f32x4 acc[2][NRB];
 #pragma unroll
-    for (int t = 0; t < NTB; ++t)
+    for (int h = 0; h < 2; ++h)
 #pragma unroll
-        for (int h = 0; h < 2; ++h)
-#pragma unroll
-            for (int rb = 0; rb < NRB; ++rb) acc[t][h][rb] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int rb = 0; rb < NRB; ++rb) acc[h][rb] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    // rows beyond a block repeat its last row (their results are never stored)
-    const uint16_t* zrow[NTB][2];
+    // rows beyond the block repeat its last row (their results are never stored)
+    const uint16_t* zrow[2];
 #pragma unroll
-    for (int t = 0; t < NTB; ++t)
-#pragma unroll
-        for (int h = 0; h < 2; ++h)
-            zrow[t][h] = Z + size_t(b[t].row0 + min(16 * h + j, b[t].nrows - 1)) * ldz;
+    for (int h = 0; h < 2; ++h)
+        zrow[h] = Z + size_t(b.row0 + min(16 * h + j, b.nrows - 1)) * ldz;
     const uint16_t* mrow[NRB];
 #pragma unroll
     for (int rb = 0; rb < NRB; ++rb) mrow[rb] = M + size_t(rank_row0 + min(16 * rb + j, r - 1)) * D;
 
-    // operands of one slab: 4 steps x (2 token halves of Z per block, NRB rank blocks of M).
+    // operands of one slab: 4 steps x (2 token halves of Z, NRB rank blocks of M).
     // Rank rows beyond r_t and token rows beyond the block repeat a valid row: what they produce
     // is dropped at the store, so the loads of a whole slab need no per-lane condition.
-    struct Slab { u32x4 zv[NTB][2][4], mv[NRB][4]; };
+    struct Slab { u32x4 zv[2][4], mv[NRB][4]; };
     auto load = [&](Slab& sl, int32_t slab) {
         const int32_t k = slab + 8 * kg;
         if (slab + 128 <= D) {
@@ -95,11 +86,8 @@ __global__ __launch_bounds__(64 * NWV) void shrink_mfma_kernel(PlanDev pd, const
                     if (NRB == 1 || rb < nrb_t)
                         sl.mv[rb][q] = *reinterpret_cast<const u32x4*>(mrow[rb] + k + 32 * q);
 #pragma unroll
-                for (int t = 0; t < NTB; ++t)
-                    if (NTB == 1 || t < cnt)
-#pragma unroll
-                        for (int h = 0; h < 2; ++h)
-                            sl.zv[t][h][q] = *reinterpret_cast<const u32x4*>(zrow[t][h] + k + 32 * q);
+                for (int h = 0; h < 2; ++h)
+                    sl.zv[h][q] = *reinterpret_cast<const u32x4*>(zrow[h] + k + 32 * q);
             }
         } else {   // the last slab of a width that is not a multiple of 128: columns beyond D read as 0
 #pragma unroll
@@ -110,27 +98,21 @@ __global__ __launch_bounds__(64 * NWV) void shrink_mfma_kernel(PlanDev pd, const
                     if (NRB == 1 || rb < nrb_t)
                         sl.mv[rb][q] = kin ? *reinterpret_cast<const u32x4*>(mrow[rb] + k + 32 * q) : zero4;
 #pragma unroll
-                for (int t = 0; t < NTB; ++t)
-                    if (NTB == 1 || t < cnt)
-#pragma unroll
-                        for (int h = 0; h < 2; ++h)
-                            sl.zv[t][h][q] = kin ? *reinterpret_cast<const u32x4*>(zrow[t][h] + k + 32 * q) : zero4;
+                for (int h = 0; h < 2; ++h)
+                    sl.zv[h][q] = kin ? *reinterpret_cast<const u32x4*>(zrow[h] + k + 32 * q) : zero4;
             }
         }
     };
     auto mac = [&](const Slab& sl) {
 #pragma unroll
-        for (int t = 0; t < NTB; ++t)
-            if (NTB == 1 || t < cnt)
+        for (int q = 0; q < 4; ++q)
 #pragma unroll
-                for (int q = 0; q < 4; ++q)
+            for (int h = 0; h < 2; ++h)
 #pragma unroll
-                    for (int h = 0; h < 2; ++h)
-#pragma unroll
-                        for (int rb = 0; rb < NRB; ++rb)
-                            if (NRB == 1 || rb < nrb_t)
-                                acc[t][h][rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                                    as_bf16x8(sl.mv[rb][q]), as_bf16x8(sl.zv[t][h][q]), acc[t][h][rb], 0, 0, 0);
+                for (int rb = 0; rb < NRB; ++rb)
+                    if (NRB == 1 || rb < nrb_t)
+                        acc[h][rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                            as_bf16x8(sl.mv[rb][q]), as_bf16x8(sl.zv[h][q]), acc[h][rb], 0, 0, 0);
     };
     // DEPTH slabs in flight per wave: the loads of slab i + DEPTH - 1 are issued before the MFMAs
     // of slab i (DEPTH = 1: load, then multiply).
@@ -147,47 +129,171 @@ __global__ __launch_bounds__(64 * NWV) void shrink_mfma_kernel(PlanDev pd, const
             if (i + NWV * d < nsl) mac(buf[d]);
         }
     }
-    // per token block: cross-wave sum through LDS, then lane (token j, rank group kg) of wave 0/1
-    // stores half h
-    const float st = s[b[0].task];
+    // cross-wave sum through LDS, then lane (token j, rank group kg) of wave 0/1 stores half h
 #pragma unroll
-    for (int t = 0; t < NTB; ++t) {
-        if (t >= cnt) break;
-        if (t > 0) __syncthreads();
+    for (int h = 0; h < 2; ++h)
 #pragma unroll
-        for (int h = 0; h < 2; ++h)
+        for (int rb = 0; rb < NRB; ++rb)
+            if (rb < nrb_t)
 #pragma unroll
-            for (int rb = 0; rb < NRB; ++rb)
+                for (int v = 0; v < 4; ++v) red[wave][h][rb][lane][v] = acc[h][rb][v];
+    __syncthreads();
+    if (wave < 2) {
+        const int h = wave;
+        const int32_t tok = 16 * h + j;
+        const float st = s[b.task];
+#pragma unroll
+        for (int rb = 0; rb < NRB; ++rb) {
+            bf16x4 o;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                float sum = 0.f;
                 if (rb < nrb_t)
 #pragma unroll
-                    for (int v = 0; v < 4; ++v) red[wave][h][rb][lane][v] = acc[t][h][rb][v];
-        __syncthreads();
-        if (wave < 2) {
-            const int h = wave;
-            const int32_t tok = 16 * h + j;
-#pragma unroll
-            for (int rb = 0; rb < NRB; ++rb) {
-                bf16x4 o;
+                    for (int w = 0; w < NWV; ++w) sum += red[w][h][rb][lane][v];   // fixed order
+                const int32_t p = 16 * rb + 4 * kg + v;
+                o[v] = (__bf16)((p < r && tok < b.nrows) ? st * sum : 0.f);
+            }
+            const int32_t p0 = 16 * rb + 4 * kg;
+            if (p0 < plim) {
+                if (tok < b.nrows)
+                    *reinterpret_cast<bf16x4*>(P_tok + size_t(b.row0 + tok) * pd.r_pad + pofs + p0) = o;
+                // block-transposed copy [block][rank][32 tokens]; tokens beyond the block hold 0
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
-                    float sum = 0.f;
-                    if (rb < nrb_t)
-#pragma unroll
-                        for (int w = 0; w < NWV; ++w) sum += red[w][h][rb][lane][v];   // fixed order
-                    const int32_t p = 16 * rb + 4 * kg + v;
-                    o[v] = (__bf16)((p < r && tok < b[t].nrows) ? st * sum : 0.f);
+                    union { __bf16 b; uint16_t u; } c;
+                    c.b = o[v];
+                    P_blk[(size_t(bi) * pd.r_pad + pofs + p0 + v) * kTokenBlock + tok] = c.u;
                 }
-                const int32_t p0 = 16 * rb + 4 * kg;
-                if (p0 < plim) {
-                    if (tok < b[t].nrows)
-                        *reinterpret_cast<bf16x4*>(P_tok + size_t(b[t].row0 + tok) * pd.r_pad + pofs + p0) = o;
-                    // block-transposed copy [block][rank][32 tokens]; tokens beyond the block hold 0
+            }
+        }
+    }
+}
+
+// -------------------------------------------------------------------------------------------------
+// shrink for large ranks: one workgroup per run of up to 4 token blocks of one task, wave w owns
+// block w over the whole of K.  The rank rows of a slab (16 NRB x 128 columns) are staged in LDS once
+// per workgroup and read by all four waves, so the adapter traffic is r_t rows per 128 token rows
+// instead of per 32; a wave's sums are complete when its loop ends (no cross-wave reduction).
+// LDS layout of a staged slab: [rank row][16 chunks of 16 bytes], chunk c of row R at c ^ (R & 15), so
+// that the 16 rank rows of one ds_read_b128 pass hit 16 different bank groups; two slabs are staged
+// alternately (one barrier per slab).
+// -------------------------------------------------------------------------------------------------
+template <int NRB, int DEPTH>
+__global__ __launch_bounds__(256) void shrink_lds_kernel(PlanDev pd, const uint16_t* __restrict__ Z,
+                                                      const uint16_t* __restrict__ M,
+                                                      const float* __restrict__ s,
+                                                      uint16_t* __restrict__ P_tok,
+                                                      uint16_t* __restrict__ P_blk, int32_t D)
+{
+    constexpr int ROWS = 16 * NRB;                       // staged rank rows
+    constexpr int CH = ROWS * 16;                        // 16-byte chunks per staged slab
+    constexpr int MLD = (CH + 255) / 256;                // chunks per thread
+    __shared__ __attribute__((aligned(16))) unsigned char ms[2][ROWS * 256];
+    const int32_t tb0 = pd.sb_off[blockIdx.x];
+    const int32_t cnt = pd.sb_off[blockIdx.x + 1] - tb0;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const bool active = wave < cnt;                      // wave-uniform: this wave has a token block
+    const TokenBlock b = pd.tb[tb0 + min(wave, cnt - 1)];
+    const int32_t r = pd.rank_off[b.task + 1] - b.rank_row0;
+    const int32_t nrb_t = (r + 15) >> 4;
+    const int j = lane & 15, kg = lane >> 4;
+    const u32x4 zero4 = {0u, 0u, 0u, 0u};
+
+    f32x4 acc[2][NRB];
 #pragma unroll
-                    for (int v = 0; v < 4; ++v) {
-                        union { __bf16 b; uint16_t u; } c;
-                        c.b = o[v];
-                        P_blk[(size_t(tb0 + t) * pd.r_pad + pofs + p0 + v) * kTokenBlock + tok] = c.u;
-                    }
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int rb = 0; rb < NRB; ++rb) acc[h][rb] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const uint16_t* zrow[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) zrow[h] = Z + size_t(b.row0 + min(16 * h + j, b.nrows - 1)) * D;
+
+    // staging: thread tid moves chunks tid, tid + 256, ...: chunk id = (rank row, 16-byte column chunk)
+    u32x4 mreg[MLD];
+    auto fetch_m = [&](int32_t slab) {
+#pragma unroll
+        for (int u = 0; u < MLD; ++u) {
+            const int ch = threadIdx.x + 256 * u, R = ch >> 4, c = ch & 15;
+            const int32_t k = slab + 8 * c;
+            mreg[u] = (ch < CH && R < 16 * nrb_t && k < D)
+                          ? *reinterpret_cast<const u32x4*>(M + size_t(b.rank_row0 + min(R, r - 1)) * D + k) : zero4;
+        }
+    };
+    auto stash_m = [&](int buf) {
+#pragma unroll
+        for (int u = 0; u < MLD; ++u) {
+            const int ch = threadIdx.x + 256 * u, R = ch >> 4, c = ch & 15;
+            if (ch < CH) *reinterpret_cast<u32x4*>(&ms[buf][R * 256 + ((c ^ (R & 15)) << 4)]) = mreg[u];
+        }
+    };
+    struct ZSlab { u32x4 zv[2][4]; };
+    auto load_z = [&](ZSlab& sl, int32_t slab) {
+        const int32_t k = slab + 8 * kg;
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+                sl.zv[h][q] = (slab + 128 <= D || k + 32 * q < D)
+                                  ? *reinterpret_cast<const u32x4*>(zrow[h] + min(k + 32 * q, D - 8)) : zero4;
+    };
+    auto mac = [&](const ZSlab& sl, int buf) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+            for (int rb = 0; rb < NRB; ++rb)
+                if (rb < nrb_t) {
+                    const int R = 16 * rb + j;
+                    const u32x4 mv = *reinterpret_cast<const u32x4*>(&ms[buf][R * 256 + (((4 * q + kg) ^ (R & 15)) << 4)]);
+#pragma unroll
+                    for (int h = 0; h < 2; ++h)
+                        acc[h][rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(mv), as_bf16x8(sl.zv[h][q]),
+                                                                         acc[h][rb], 0, 0, 0);
+                }
+    };
+    const int32_t nsl = (D + 127) >> 7;
+    ZSlab zb[DEPTH];
+#pragma unroll
+    for (int d = 0; d < DEPTH - 1; ++d)
+        if (d < nsl && active) load_z(zb[d], d << 7);
+    fetch_m(0);
+    for (int32_t i = 0; i < nsl; i += DEPTH) {
+#pragma unroll
+        for (int d = 0; d < DEPTH; ++d) {
+            const int32_t sl = i + d;
+            if (sl >= nsl) break;                            // uniform
+            stash_m(sl & 1);
+            __syncthreads();                                 // slab sl is staged; slab sl - 1 has been consumed
+            if (sl + 1 < nsl) fetch_m((sl + 1) << 7);
+            if (active) {
+                if (sl + DEPTH - 1 < nsl) load_z(zb[(d + DEPTH - 1) % DEPTH], (sl + DEPTH - 1) << 7);
+                mac(zb[d], sl & 1);
+            }
+        }
+    }
+    if (!active) return;
+    const float st = s[b.task];
+    const int32_t bi = tb0 + wave;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int32_t tok = 16 * h + j;
+#pragma unroll
+        for (int rb = 0; rb < NRB; ++rb) {
+            bf16x4 o;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int32_t p = 16 * rb + 4 * kg + v;
+                o[v] = (__bf16)((p < r && tok < b.nrows) ? st * acc[h][rb][v] : 0.f);
+            }
+            const int32_t p0 = 16 * rb + 4 * kg;
+            if (p0 < pd.r_pad) {
+                if (tok < b.nrows)
+                    *reinterpret_cast<bf16x4*>(P_tok + size_t(b.row0 + tok) * pd.r_pad + p0) = o;
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    union { __bf16 b; uint16_t u; } c;
+                    c.b = o[v];
+                    P_blk[(size_t(bi) * pd.r_pad + p0 + v) * kTokenBlock + tok] = c.u;
                 }
             }
         }
@@ -201,20 +307,23 @@ hipError_t shrink_mfma(const PlanDev& pd, const void* Z, const void* M, const fl
     if (pd.ntb == 0) return hipSuccess;
     // rank blocks of the widest window (nproj = 1: of the widest task)
     const int nrb = (pd.r_max / nproj + 15) / 16;
-#define LOBRA_SHRINK(NRB, NTB, DEPTH)                                                                  \
-    shrink_mfma_kernel<NRB, 4, NTB, DEPTH><<<(NTB == 1 ? pd.ntb : pd.nsb), 256, 0, st>>>(                \
-        pd, (const uint16_t*)Z, (const uint16_t*)M, s, (uint16_t*)P_tok, (uint16_t*)P_blk, D, ldz, nproj, proj)
-    if (pd.shrink_group == 1 || nproj > 1) {
-        if (nrb <= 1) LOBRA_SHRINK(1, 1, 3);
-        else if (nrb <= 2) LOBRA_SHRINK(2, 1, 2);
-        else if (nrb <= 4) LOBRA_SHRINK(4, 1, 2);
-        else LOBRA_SHRINK(8, 1, 1);
-    } else if (pd.shrink_group == 2) {
-        if (nrb <= 4) LOBRA_SHRINK(4, 2, 1);
-        else LOBRA_SHRINK(8, 2, 1);
-    } else {
-        return hipErrorInvalidValue;
+    if (pd.shrink_group == 4 && nproj == 1 && ldz == D) {
+        // large ranks and a long batch: runs of four token blocks share the staged adapter rows
+        if (nrb <= 4)
+            shrink_lds_kernel<4, 2><<<pd.nsb, 256, 0, st>>>(pd, (const uint16_t*)Z, (const uint16_t*)M, s,
+                                                            (uint16_t*)P_tok, (uint16_t*)P_blk, D);
+        else
+            shrink_lds_kernel<8, 2><<<pd.nsb, 256, 0, st>>>(pd, (const uint16_t*)Z, (const uint16_t*)M, s,
+                                                            (uint16_t*)P_tok, (uint16_t*)P_blk, D);
+        return hipGetLastError();
     }
+#define LOBRA_SHRINK(NRB, DEPTH)                                                                       \
+    shrink_mfma_kernel<NRB, 4, DEPTH><<<pd.ntb, 256, 0, st>>>(                                           \
+        pd, (const uint16_t*)Z, (const uint16_t*)M, s, (uint16_t*)P_tok, (uint16_t*)P_blk, D, ldz, nproj, proj)
+    if (nrb <= 1) LOBRA_SHRINK(1, 3);
+    else if (nrb <= 2) LOBRA_SHRINK(2, 2);
+    else if (nrb <= 4) LOBRA_SHRINK(4, 2);
+    else LOBRA_SHRINK(8, 1);
 #undef LOBRA_SHRINK
     return hipGetLastError();
 }
