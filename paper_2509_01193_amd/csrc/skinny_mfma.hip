@@ -459,12 +459,133 @@ __global__ __launch_bounds__(256) void grad_mfma_kernel(PlanDev pd, GradJob ja, 
     }
 }
 
+// -------------------------------------------------------------------------------------------------
+// grad stage 1 for large ranks (r_pad >= 48): partial dM over one reduction chunk and 256 columns per
+// workgroup.  Wave w owns the 64 columns 64 w .. of the tile for ALL token blocks of the chunk (so its
+// sums are final: no cross-wave reduction), and the P_blk tile of a token block ([64 ranks][32 tokens],
+// 4 KiB) is staged in LDS once for the four waves instead of being fetched by each of them - with 64
+// ranks it is as many bytes as the wave's own slice of Z.  Two LDS buffers alternate, one barrier per
+// token block; the next block's Z rows and P tile are fetched before the current block is multiplied.
+// Operand layouts as in grad_mfma_kernel with CW = 4.
+// -------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void grad_lds_kernel(PlanDev pd, GradJob ja, GradJob jb, int32_t tiles_a)
+{
+    constexpr int NRB = 4, CW = 4, TW = 4 * 16 * CW;     // rank blocks per pass, columns per lane, tile width
+    typedef uint32_t zvec __attribute__((ext_vector_type(CW / 2)));
+    typedef float ovec __attribute__((ext_vector_type(4)));
+    __shared__ __attribute__((aligned(16))) unsigned char ps[2][16 * NRB * 64];
+    const bool first = int32_t(blockIdx.y) < tiles_a;
+    const uint16_t* __restrict__ P_blk = static_cast<const uint16_t*>(first ? ja.P : jb.P);
+    const uint16_t* __restrict__ Z = static_cast<const uint16_t*>(first ? ja.Z : jb.Z);
+    float* __restrict__ part = first ? ja.part : jb.part;
+    const int32_t D = first ? ja.D : jb.D;
+    const int32_t ldz = (first ? ja.ldz : jb.ldz) ? (first ? ja.ldz : jb.ldz) : D;
+    const int32_t nproj = first ? ja.nproj : jb.nproj;
+    const int32_t coltile = first ? int32_t(blockIdx.y) : int32_t(blockIdx.y) - tiles_a;
+    const int32_t proj_in = first ? ja.proj : jb.proj;
+    const int32_t proj = proj_in >= 0 ? proj_in : coltile * TW / pd.dg;   // pd.dg is a multiple of TW then
+    const int32_t pcol0 = proj_in >= 0 ? 0 : proj * pd.dg;
+    const int32_t ldp = (first ? ja.ldp : jb.ldp) ? (first ? ja.ldp : jb.ldp) : D;
+    const GradChunk ch = pd.chunks[blockIdx.x];
+    const int32_t r = (pd.rank_off[ch.task + 1] - pd.rank_off[ch.task]) / nproj;
+    const int32_t pofs = proj * r;
+    const int32_t rb0 = blockIdx.z * NRB;
+    if (16 * rb0 >= r) return;                            // uniform
+    const int32_t nrb_t = min(NRB, (r - 16 * rb0 + 15) >> 4);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int c = lane & 15, g = lane >> 4;
+    const int32_t col = coltile * TW + wave * (16 * CW) + CW * c;
+    const bool col_in = col < D;
+
+    f32x4 acc[NRB][CW];
+#pragma unroll
+    for (int rb = 0; rb < NRB; ++rb)
+#pragma unroll
+        for (int jj = 0; jj < CW; ++jj) acc[rb][jj] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    // staging: thread tid moves 16 bytes: rank row tid / 4 of the pass, tokens 8 (tid % 4) ..
+    const int prow = threadIdx.x >> 2, pchunk = threadIdx.x & 3;
+    const int32_t prank = min(pofs + 16 * rb0 + prow, pd.r_pad - 1);
+    auto fetch_p = [&](int32_t bi) {
+        return *reinterpret_cast<const u32x4*>(P_blk + (size_t(bi) * pd.r_pad + prank) * kTokenBlock + 8 * pchunk);
+    };
+    auto load_z = [&](zvec (&zin)[8], int32_t bi) {
+        const TokenBlock b = pd.tb[bi];
+#pragma unroll
+        for (int q = 0; q < 8; ++q)   // rows beyond the block repeat its last row; their P entries are zero
+            zin[q] = col_in ? *reinterpret_cast<const zvec*>(Z + size_t(b.row0 + min(8 * g + q, b.nrows - 1)) * ldz + col)
+                            : zvec(0u);
+    };
+    auto mac = [&](const zvec (&zin)[8], int buf) {
+        u32x4 pf[NRB];
+#pragma unroll
+        for (int rb = 0; rb < NRB; ++rb)
+            if (rb < nrb_t) pf[rb] = *reinterpret_cast<const u32x4*>(&ps[buf][(16 * rb + c) * 64 + 16 * g]);
+#pragma unroll
+        for (int jj = 0; jj < CW; ++jj) {
+            u32x4 f;
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                f[e] = __builtin_amdgcn_perm(zin[2 * e + 1][jj >> 1], zin[2 * e][jj >> 1],
+                                             (jj & 1) ? 0x07060302u : 0x05040100u);
+#pragma unroll
+            for (int rb = 0; rb < NRB; ++rb)
+                if (rb < nrb_t)
+                    acc[rb][jj] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(pf[rb]), as_bf16x8(f),
+                                                                          acc[rb][jj], 0, 0, 0);
+        }
+    };
+    const int32_t n = ch.tb_end - ch.tb_begin;
+    zvec za[8], zb[8];
+    u32x4 preg = fetch_p(ch.tb_begin);
+    load_z(za, ch.tb_begin);
+    for (int32_t i = 0; i < n; i += 2) {
+        // block i (Z rows in za), then block i + 1 (zb): the buffers alternate without register copies
+        *reinterpret_cast<u32x4*>(&ps[0][prow * 64 + 16 * pchunk]) = preg;
+        __syncthreads();                                 // tile i is staged; tile i - 1 has been consumed
+        if (i + 1 < n) {
+            preg = fetch_p(ch.tb_begin + i + 1);
+            load_z(zb, ch.tb_begin + i + 1);
+        }
+        mac(za, 0);
+        if (i + 1 >= n) break;                           // uniform
+        *reinterpret_cast<u32x4*>(&ps[1][prow * 64 + 16 * pchunk]) = preg;
+        __syncthreads();
+        if (i + 2 < n) {
+            preg = fetch_p(ch.tb_begin + i + 2);
+            load_z(za, ch.tb_begin + i + 2);
+        }
+        mac(zb, 1);
+    }
+    if (!col_in) return;
+#pragma unroll
+    for (int rb = 0; rb < NRB; ++rb)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int32_t p = 16 * (rb0 + rb) + 4 * g + v;
+            if (p >= r) continue;
+            ovec o;
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) o[jj] = acc[rb][jj][v];
+            *reinterpret_cast<ovec*>(part + size_t(ch.part_row0 + pofs + p) * ldp + (col - pcol0)) = o;
+        }
+}
+
 hipError_t grad_mfma(const PlanDev& pd, const GradJob& ja, const GradJob& jb, hipStream_t st)
 {
     if (pd.nchunks == 0) return hipSuccess;
     // rank blocks of the widest window (both jobs of a launch have the same nproj)
     const int nrb = ja.nproj > 1 ? (pd.r_max / ja.nproj + 15) / 16 : pd.r_pad / 16;
     const int NRB = nrb <= 1 ? 1 : (nrb <= 2 ? 2 : 4);
+    // large ranks: the kernel that stages P_blk in LDS (its 256-column tiles must not straddle projections)
+    if (NRB == 4 &&
+        (ja.proj >= 0 || pd.dg % 256 == 0) && (!jb.P || jb.proj >= 0 || pd.dg % 256 == 0)) {
+        const int32_t ta = (ja.D + 255) / 256, tb = jb.P ? (jb.D + 255) / 256 : 0;
+        const dim3 grid(pd.nchunks, ta + tb, (nrb + 3) / 4);
+        if (grid.y > 65535u) return hipErrorInvalidValue;
+        grad_lds_kernel<<<grid, 256, 0, st>>>(pd, ja, jb, ta);
+        return hipGetLastError();
+    }
     const int cw = NRB == 4 ? 4 : 8;
     const int32_t tw = 16 * cw;
     const int32_t tiles_a = (ja.D + tw - 1) / tw, tiles_b = jb.P ? (jb.D + tw - 1) / tw : 0;
