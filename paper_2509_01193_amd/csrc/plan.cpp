@@ -114,8 +114,8 @@ lobra_status build_host_plan(const lobra_mlora_desc* d, uint32_t flags, Plan* p)
             }
         }
 
-        // 3b. runs of token blocks that one workgroup of the rank-r projection handles.  With large
-        //     ranks the adapter rows are most of what a single token block's workgroup reads (r_t rows
+        // 3b. runs of token blocks that one workgroup of the rank-r projection handles.  From rank 24 or
+        //     so the adapter rows are most of what a single token block's workgroup reads (r_t rows
         //     per 32 token rows), so long batches are projected in runs of four blocks that share the
         //     rows staged in LDS; otherwise every block is its own run.
         {
@@ -123,7 +123,7 @@ lobra_status build_host_plan(const lobra_mlora_desc* d, uint32_t flags, Plan* p)
             const int64_t ntb_all = p->task_tb_off[n];
             for (int32_t t = 0; t < n; ++t)
                 wsum += int64_t(p->task_tb_off[t + 1] - p->task_tb_off[t]) * (p->rank_off[t + 1] - p->rank_off[t]);
-            const int32_t g = (p->mfma && ntb_all >= 1024 && wsum >= 48 * ntb_all) ? 4 : 1;
+            const int32_t g = (p->mfma && ntb_all >= 1024 && wsum >= 24 * ntb_all) ? 4 : 1;
             p->shrink_group = g;
             p->sb_off.assign(1, 0);
             for (int32_t t = 0; t < n; ++t)

@@ -171,7 +171,7 @@ __global__ __launch_bounds__(64 * NWV) void shrink_mfma_kernel(PlanDev pd, const
 }
 
 // -------------------------------------------------------------------------------------------------
-// shrink for large ranks: one workgroup per run of up to 4 token blocks of one task, wave w owns
+// shrink for ranks from about 24 up (chosen by the plan for long batches): one workgroup per run of up to 4 token blocks of one task, wave w owns
 // block w over the whole of K.  The rank rows of a slab (16 NRB x 128 columns) are staged in LDS once
 // per workgroup and read by all four waves, so the adapter traffic is r_t rows per 128 token rows
 // instead of per 32; a wave's sums are complete when its loop ends (no cross-wave reduction).
@@ -308,8 +308,11 @@ hipError_t shrink_mfma(const PlanDev& pd, const void* Z, const void* M, const fl
     // rank blocks of the widest window (nproj = 1: of the widest task)
     const int nrb = (pd.r_max / nproj + 15) / 16;
     if (pd.shrink_group == 4 && nproj == 1 && ldz == D) {
-        // large ranks and a long batch: runs of four token blocks share the staged adapter rows
-        if (nrb <= 4)
+        // ranks from about 24 up and a long batch: runs of four token blocks share the staged adapter rows
+        if (nrb <= 2)
+            shrink_lds_kernel<2, 2><<<pd.nsb, 256, 0, st>>>(pd, (const uint16_t*)Z, (const uint16_t*)M, s,
+                                                            (uint16_t*)P_tok, (uint16_t*)P_blk, D);
+        else if (nrb <= 4)
             shrink_lds_kernel<4, 2><<<pd.nsb, 256, 0, st>>>(pd, (const uint16_t*)Z, (const uint16_t*)M, s,
                                                             (uint16_t*)P_tok, (uint16_t*)P_blk, D);
         else
@@ -460,17 +463,19 @@ __global__ __launch_bounds__(256) void grad_mfma_kernel(PlanDev pd, GradJob ja, 
 }
 
 // -------------------------------------------------------------------------------------------------
-// grad stage 1 for large ranks (r_pad >= 48): partial dM over one reduction chunk and 256 columns per
+// grad stage 1 for ranks above 16 (NRB = 2: r_pad = 32, NRB = 4: r_pad >= 48, in passes of 64 ranks):
+// partial dM over one reduction chunk and 256 columns per
 // workgroup.  Wave w owns the 64 columns 64 w .. of the tile for ALL token blocks of the chunk (so its
-// sums are final: no cross-wave reduction), and the P_blk tile of a token block ([64 ranks][32 tokens],
-// 4 KiB) is staged in LDS once for the four waves instead of being fetched by each of them - with 64
+// sums are final: no cross-wave reduction), and the P_blk tile of a token block ([16 NRB ranks][32
+// tokens]) is staged in LDS once for the four waves instead of being fetched by each of them - with 64
 // ranks it is as many bytes as the wave's own slice of Z.  Two LDS buffers alternate, one barrier per
 // token block; the next block's Z rows and P tile are fetched before the current block is multiplied.
 // Operand layouts as in grad_mfma_kernel with CW = 4.
 // -------------------------------------------------------------------------------------------------
+template <int NRB>
 __global__ __launch_bounds__(256) void grad_lds_kernel(PlanDev pd, GradJob ja, GradJob jb, int32_t tiles_a)
 {
-    constexpr int NRB = 4, CW = 4, TW = 4 * 16 * CW;     // rank blocks per pass, columns per lane, tile width
+    constexpr int CW = 4, TW = 4 * 16 * CW;     // rank blocks per pass, columns per lane, tile width
     typedef uint32_t zvec __attribute__((ext_vector_type(CW / 2)));
     typedef float ovec __attribute__((ext_vector_type(4)));
     __shared__ __attribute__((aligned(16))) unsigned char ps[2][16 * NRB * 64];
@@ -504,7 +509,7 @@ __global__ __launch_bounds__(256) void grad_lds_kernel(PlanDev pd, GradJob ja, G
         for (int jj = 0; jj < CW; ++jj) acc[rb][jj] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     // staging: thread tid moves 16 bytes: rank row tid / 4 of the pass, tokens 8 (tid % 4) ..
-    const int prow = threadIdx.x >> 2, pchunk = threadIdx.x & 3;
+    const int prow = min(int(threadIdx.x >> 2), 16 * NRB - 1), pchunk = threadIdx.x & 3;
     const int32_t prank = min(pofs + 16 * rb0 + prow, pd.r_pad - 1);
     auto fetch_p = [&](int32_t bi) {
         return *reinterpret_cast<const u32x4*>(P_blk + (size_t(bi) * pd.r_pad + prank) * kTokenBlock + 8 * pchunk);
@@ -577,13 +582,14 @@ hipError_t grad_mfma(const PlanDev& pd, const GradJob& ja, const GradJob& jb, hi
     // rank blocks of the widest window (both jobs of a launch have the same nproj)
     const int nrb = ja.nproj > 1 ? (pd.r_max / ja.nproj + 15) / 16 : pd.r_pad / 16;
     const int NRB = nrb <= 1 ? 1 : (nrb <= 2 ? 2 : 4);
-    // large ranks: the kernel that stages P_blk in LDS (its 256-column tiles must not straddle projections)
-    if (NRB == 4 &&
+    // ranks above 16: the kernel that stages P_blk in LDS (its 256-column tiles must not straddle projections)
+    if (NRB >= 2 &&
         (ja.proj >= 0 || pd.dg % 256 == 0) && (!jb.P || jb.proj >= 0 || pd.dg % 256 == 0)) {
         const int32_t ta = (ja.D + 255) / 256, tb = jb.P ? (jb.D + 255) / 256 : 0;
         const dim3 grid(pd.nchunks, ta + tb, (nrb + 3) / 4);
         if (grid.y > 65535u) return hipErrorInvalidValue;
-        grad_lds_kernel<<<grid, 256, 0, st>>>(pd, ja, jb, ta);
+        if (NRB == 2) grad_lds_kernel<2><<<dim3(pd.nchunks, ta + tb, 1), 256, 0, st>>>(pd, ja, jb, ta);
+        else grad_lds_kernel<4><<<grid, 256, 0, st>>>(pd, ja, jb, ta);
         return hipGetLastError();
     }
     const int cw = NRB == 4 ? 4 : 8;

@@ -112,6 +112,19 @@ def test_token_structure_on_a_narrow_layer_whole_k_tiles(cfg):
     check_problem(p, label="k64")
 
 
+@pytest.mark.parametrize("rank", [24, 32])
+def test_long_batch_at_medium_rank_takes_the_lds_staged_kernels(rank):
+    """Workload 5's tokens at a uniform rank of 24 / 32: runs of four token blocks in the projection
+    (two rank blocks staged in LDS) and the 256-column tiles of the gradient reduction."""
+    p = wl.make_config(5, "shuffled", d_in=200, d_out=264, fill=False)
+    p.ranks = np.full_like(p.ranks, rank)
+    p.fill()
+    plan = bd.Plan.for_problem(p, bd.PLAN_HOST_ONLY)
+    assert int(np.diff(plan.query(bd.Q_BLOCK_RUNS)).max()) == 4
+    plan.close()
+    check_problem(p, label="rank %d" % rank)
+
+
 @pytest.mark.parametrize("dims", [(8, 8), (16, 24), (64, 64), (72, 8), (8, 1032), (1024, 64), (2048, 256)])
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_extreme_layer_widths(dims, dtype):
@@ -468,9 +481,9 @@ def test_fused_shared_input_projections(n_proj, d_in, dg, ranks):
         torch.cuda.synchronize()
         idx = torch.from_numpy(rows).to(dp.dev)
         assert torch.equal(want[0][:, j * dg:(j + 1) * dg], dq.y), j
-        assert torch.equal(want[3].index_select(0, idx), dq.dB), j
-        ref = dq.dA
-        assert float((want[2].index_select(0, idx) - ref).abs().max()) <= 1e-5 * float(ref.abs().max()), j
+        # (the reductions may run in another kernel instantiation, i.e. another fixed summation order)
+        for got, ref in ((want[3].index_select(0, idx), dq.dB), (want[2].index_select(0, idx), dq.dA)):
+            assert float((got - ref).abs().max()) <= 1e-5 * float(ref.abs().max()), j
 
 
 @pytest.mark.parametrize("dtype,flags", [("f32", 0), ("bf16", bd.PLAN_PLAIN_KERNELS)])
