@@ -112,10 +112,11 @@ def test_token_structure_on_a_narrow_layer_whole_k_tiles(cfg):
     check_problem(p, label="k64")
 
 
-@pytest.mark.parametrize("rank", [24, 32])
-def test_long_batch_at_medium_rank_takes_the_lds_staged_kernels(rank):
-    """Workload 5's tokens at a uniform rank of 24 / 32: runs of four token blocks in the projection
-    (two rank blocks staged in LDS) and the 256-column tiles of the gradient reduction."""
+@pytest.mark.parametrize("rank", [24, 32, 96])
+def test_long_batch_at_medium_and_large_rank_takes_the_lds_staged_kernels(rank):
+    """Workload 5's tokens at a uniform rank of 24 / 32 / 96: runs of four token blocks in the projection
+    (two or eight rank blocks staged in LDS) and the 256-column tiles of the gradient reduction (rank 96:
+    two passes of 64 ranks)."""
     p = wl.make_config(5, "shuffled", d_in=200, d_out=264, fill=False)
     p.ranks = np.full_like(p.ranks, rank)
     p.fill()
