@@ -512,3 +512,16 @@ def test_fused_projections_adversarial_segment_tables(name, dtype):
         ro = f.rank_off
         for t in (1, 2):
             assert not dp.dA[ro[t]:ro[t + 1]].any().item() and not dp.dB[ro[t]:ro[t + 1]].any().item()
+
+
+def test_fused_projections_on_a_long_batch_with_large_stacked_ranks():
+    """Two fused layers on workload 5's tokens, rank 32 each (stacked 64): the forward projection takes the
+    LDS-staged kernel on runs of four blocks, dA the LDS-staged reduction over the stacked ranks, and dB the
+    same kernel with every 256-column tile in its projection's rank window."""
+    base = wl.make_config(5, "shuffled", d_in=136, d_out=256, fill=False)
+    base.ranks = np.full_like(base.ranks, 32)
+    f = wl.fuse_projections(base, 2)
+    plan = bd.Plan.for_problem(f, bd.PLAN_HOST_ONLY)
+    assert int(np.diff(plan.query(bd.Q_BLOCK_RUNS)).max()) == 4
+    plan.close()
+    check_problem(f, label="fused x2 long")
