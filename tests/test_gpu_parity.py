@@ -525,3 +525,25 @@ def test_fused_projections_on_a_long_batch_with_large_stacked_ranks():
     assert int(np.diff(plan.query(bd.Q_BLOCK_RUNS)).max()) == 4
     plan.close()
     check_problem(f, label="fused x2 long")
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_random_long_batches(seed):
+    """Long packed batches (tens of thousands of tokens) of random shape: ranks up to 128, one to three
+    fused projections, sampled rows of y and dx, dA and dB in full."""
+    rng = np.random.default_rng(77000 + seed)
+    P = int(rng.choice([1, 1, 2, 3]))
+    d_in = int(rng.integers(1, 60)) * 8
+    dg = int(rng.integers(1, 50)) * 8
+    n_tasks = int(rng.integers(1, 6))
+    ranks = rng.choice([8, 16, 24, 32, 40], n_tasks) if P > 1 else rng.choice([1, 3, 8, 16, 17, 24, 32, 48, 64, 96, 128], n_tasks)
+    S = int(rng.integers(20, 60))
+    lens = rng.choice([1, 33, 200, 700, 1500, 3000, 5000], S)
+    seg_task = rng.integers(-1, n_tasks, S)
+    seg_off = np.concatenate([[0], np.cumsum(lens)])
+    s = rng.uniform(-2, 2, n_tasks).astype(np.float32)
+    kw = dict(std_x=1.0, std_w=0.05, std_a=0.05, std_b=0.05)
+    base = wl.make_custom("long%d" % seed, "bf16", d_in, dg, ranks, seg_off, seg_task, 900 + seed, s=s,
+                          fill=(P == 1), **kw)
+    p = base if P == 1 else wl.fuse_projections(base, P, **kw)
+    check_problem(p, rows=sample_rows(p, 400, seed=seed), label="T=%d P=%d ranks=%s" % (p.T, P, list(map(int, p.ranks))))
