@@ -46,7 +46,7 @@
 #define LOBRA_GEMM_ISSUE_AT 2      // K step of the tile after which the next tile's copies are issued
 #endif
 #ifndef LOBRA_GEMM_GM
-#define LOBRA_GEMM_GM 8
+#define LOBRA_GEMM_GM 0      // 0: chosen from K by the launcher
 #endif
 #ifndef LOBRA_GEMM_NT_STORE
 #define LOBRA_GEMM_NT_STORE 1
@@ -129,7 +129,7 @@ __global__ __launch_bounds__(64 * WM * WN)
 void gemm_mfma_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const uint16_t* __restrict__ W,
                       const uint16_t* __restrict__ P, const uint16_t* __restrict__ M,
                       uint16_t* __restrict__ C, int32_t K, int32_t N, int32_t ldw, int32_t ldc,
-                      int32_t nproj, int32_t proj, int32_t tiles_m, int32_t tiles_n)
+                      int32_t nproj, int32_t proj, int32_t tiles_m, int32_t tiles_n, int32_t GM)
 {
     // ldc: row pitch of C.  nproj > 1: this launch is projection `proj` of a fused shared-input
     // call: of every task's rank rows (in M) and rank columns (in P) only the window
@@ -152,7 +152,7 @@ void gemm_mfma_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const uint16_t
     const int32_t T = pd.T;
 
     // ---- workgroup -> tile: consecutive ids go to different XCDs, so give each XCD a contiguous
-    //      range of the tile order; inside it, 8 tile-rows share one sweep over the tile-columns.
+    //      range of the tile order; inside it, GM tile-rows share one sweep over the tile-columns.
     int32_t tile_m, tile_n;
     {
         const int32_t ntiles = tiles_m * tiles_n;
@@ -160,7 +160,6 @@ void gemm_mfma_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const uint16_t
         const int32_t xcd = wg & 7, idx = wg >> 3;
         const int32_t per = ntiles >> 3, rem = ntiles & 7;
         const int32_t id = xcd * per + (xcd < rem ? xcd : rem) + idx;   // XCD x holds per + (x < rem)
-        constexpr int GM = LOBRA_GEMM_GM;
         const int32_t group = id / (GM * tiles_n);
         const int32_t first_m = group * GM;
         const int32_t gsz = min(tiles_m - first_m, GM);
@@ -560,7 +559,8 @@ void gemm_mfma_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const uint16_t
 template <bool W_KN, int WM, int WN, bool DMA>
 static hipError_t launch_gemm(const PlanDev& pd, const void* Z, const void* W, const void* P,
                               const void* M, void* C, int32_t K, int32_t N, int32_t ldw, int32_t ldc,
-                              int32_t nproj, int32_t proj, int32_t tiles_m, int32_t tiles_n, hipStream_t st)
+                              int32_t nproj, int32_t proj, int32_t tiles_m, int32_t tiles_n, int32_t gm,
+                              hipStream_t st)
 {
     constexpr int bytes = lds_bytes<W_KN, WN, DMA>();
     // the kernel needs more dynamic LDS than the default limit: raise it once per device
@@ -577,7 +577,7 @@ static hipError_t launch_gemm(const PlanDev& pd, const void* Z, const void* W, c
     }
     gemm_mfma_kernel<W_KN, WM, WN, DMA><<<dim3(uint32_t(tiles_m) * uint32_t(tiles_n)), 64 * WM * WN, bytes, st>>>(
         pd, (const uint16_t*)Z, (const uint16_t*)W, (const uint16_t*)P, (const uint16_t*)M, (uint16_t*)C,
-        K, N, ldw, ldc, nproj, proj, tiles_m, tiles_n);
+        K, N, ldw, ldc, nproj, proj, tiles_m, tiles_n, gm);
     return hipGetLastError();
 }
 
@@ -593,14 +593,18 @@ hipError_t gemm_mfma(const PlanDev& pd, bool transW, const void* Z, const void* 
     if (int64_t(K) * 512 >= (int64_t(1) << 32) || int64_t(ldw) * 512 >= (int64_t(1) << 32))
         return hipErrorInvalidValue;
     if (N < 8 || K < 8) return hipErrorInvalidValue;
+    // tile rows per sweep of the tile order: the workgroups that run on an XCD at one time share their
+    // x and W panels through its L2 only while they walk K nearly in step; measured on the five workloads,
+    // long K wants shorter sweeps (K = 8192 .. 28672: 4 rows up to 7 % faster than 8; K = 4096: 5 .. 8 alike)
+    const int32_t gm = LOBRA_GEMM_GM > 0 ? LOBRA_GEMM_GM : (K > 4096 ? 4 : 6);
     // the direct-to-LDS pipeline needs whole K tiles of 32; other K take the register-staged kernel
     const bool dma = LOBRA_GEMM_DMA && K % DBK == 0;
     if (!transW) {
-        if (dma) return launch_gemm<true, LOBRA_GEMM_WM, LOBRA_GEMM_WN, true>(pd, Z, W, P, M, C, K, N, ldw, ldc, nproj, proj, tiles_m, tiles_n, st);
-        return launch_gemm<true, LOBRA_GEMM_WM, LOBRA_GEMM_WN, false>(pd, Z, W, P, M, C, K, N, ldw, ldc, nproj, proj, tiles_m, tiles_n, st);
+        if (dma) return launch_gemm<true, LOBRA_GEMM_WM, LOBRA_GEMM_WN, true>(pd, Z, W, P, M, C, K, N, ldw, ldc, nproj, proj, tiles_m, tiles_n, gm, st);
+        return launch_gemm<true, LOBRA_GEMM_WM, LOBRA_GEMM_WN, false>(pd, Z, W, P, M, C, K, N, ldw, ldc, nproj, proj, tiles_m, tiles_n, gm, st);
     }
-    if (dma) return launch_gemm<false, LOBRA_GEMM_WM, LOBRA_GEMM_WN, true>(pd, Z, W, P, M, C, K, N, ldw, ldc, nproj, proj, tiles_m, tiles_n, st);
-    return launch_gemm<false, LOBRA_GEMM_WM, LOBRA_GEMM_WN, false>(pd, Z, W, P, M, C, K, N, ldw, ldc, nproj, proj, tiles_m, tiles_n, st);
+    if (dma) return launch_gemm<false, LOBRA_GEMM_WM, LOBRA_GEMM_WN, true>(pd, Z, W, P, M, C, K, N, ldw, ldc, nproj, proj, tiles_m, tiles_n, gm, st);
+    return launch_gemm<false, LOBRA_GEMM_WM, LOBRA_GEMM_WN, false>(pd, Z, W, P, M, C, K, N, ldw, ldc, nproj, proj, tiles_m, tiles_n, gm, st);
 }
 
 }  // namespace lobra
