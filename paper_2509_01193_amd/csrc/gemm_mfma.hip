@@ -594,8 +594,10 @@ hipError_t gemm_mfma(const PlanDev& pd, bool transW, const void* Z, const void* 
         return hipErrorInvalidValue;
     if (N < 8 || K < 8) return hipErrorInvalidValue;
     // tile rows per sweep of the tile order: the workgroups that run on an XCD at one time share their
-    // x and W panels through its L2 only while they walk K nearly in step; measured on the five workloads,
-    // long K wants shorter sweeps (K = 8192 .. 28672: 4 rows up to 7 % faster than 8; K = 4096: 5 .. 8 alike)
+    // Z and W panels through its L2 only while they walk K nearly in step, and the row bands that the 8
+    // XCDs sweep at one time (8 x rows x 256 x K x 2 bytes) should stay in the 256 MB infinity cache for
+    // their re-reads; measured on the five workloads, long K wants shorter sweeps (K = 8192 .. 28672:
+    // 4 rows up to 7 % faster than 8; K = 4096: 5 .. 8 alike)
     const int32_t gm = LOBRA_GEMM_GM > 0 ? LOBRA_GEMM_GM : (K > 4096 ? 4 : 6);
     // the direct-to-LDS pipeline needs whole K tiles of 32; other K take the register-staged kernel
     const bool dma = LOBRA_GEMM_DMA && K % DBK == 0;
