@@ -43,7 +43,10 @@
 #define LOBRA_GEMM_DST 2
 #endif
 #ifndef LOBRA_GEMM_ISSUE_AT
-#define LOBRA_GEMM_ISSUE_AT 2      // K step of the tile after which the next tile's copies are issued
+#define LOBRA_GEMM_ISSUE_AT 2      // K step of the tile after which the next tile's copies are issued (forward)
+#endif
+#ifndef LOBRA_GEMM_ISSUE_AT_NK
+#define LOBRA_GEMM_ISSUE_AT_NK 1   // the same for the backward product (W read along K)
 #endif
 #ifndef LOBRA_GEMM_GM
 #define LOBRA_GEMM_GM 0      // 0: chosen from K by the launcher
@@ -298,11 +301,13 @@ void gemm_mfma_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const uint16_t
             else if (DST >= 3 && kt + 1 < KT) wait_vmcnt<(DST >= 3 ? 1 : 0) * NPW>();
             else wait_vmcnt<0>();
             __builtin_amdgcn_s_barrier();
-            // the copies of the tile that reuses the freed stage go out after K step ISSUE_AT of this
-            // tile: right after the barrier they would compete with the tile's first LDS reads
-            compute(kt % DST, 0, LOBRA_GEMM_ISSUE_AT);
+            // the copies of the tile that reuses the freed stage go out after K step IA of this tile:
+            // right after the barrier they would compete with the tile's first LDS reads (forward: after
+            // two of the four steps; backward, where long K gains 2-5 % from it, after one)
+            constexpr int IA = W_KN ? LOBRA_GEMM_ISSUE_AT : LOBRA_GEMM_ISSUE_AT_NK;
+            compute(kt % DST, 0, IA);
             if (kt + DST - 1 < KT) issue(kt + DST - 1);
-            compute(kt % DST, LOBRA_GEMM_ISSUE_AT, DBK / 16);
+            compute(kt % DST, IA, DBK / 16);
         }
         wait_vmcnt<0>();
         __syncthreads();
