@@ -5,7 +5,7 @@
 // (paper section 2.1: X W + X (down)(up); section 1: one shared base product for the fused batch,
 // a per-task adapter product on top of it).
 //
-// Tiling: 256 x 256 x 64 per workgroup of WM x WN waves (default 2 x 4 = 512 threads, two waves per
+// Tiling: 256 x 256 x 64 per workgroup of WM x WN waves (default 4 x 2 = 512 threads, two waves per
 // SIMD), every wave owns (256/WM) x (256/WN) as blocks of v_mfma_f32_32x32x16_bf16 with fp32
 // accumulators.  The MFMA "A" operand is fed from W and the "B" operand from Z, so a lane ends up
 // with four consecutive output columns of one row, which packs into 8-byte LDS writes in the epilogue.
@@ -55,10 +55,10 @@
 #define LOBRA_GEMM_NT_STORE 1
 #endif
 #ifndef LOBRA_GEMM_WM
-#define LOBRA_GEMM_WM 2
+#define LOBRA_GEMM_WM 4
 #endif
 #ifndef LOBRA_GEMM_WN
-#define LOBRA_GEMM_WN 4
+#define LOBRA_GEMM_WN 2
 #endif
 
 namespace lobra {
