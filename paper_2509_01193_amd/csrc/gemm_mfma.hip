@@ -43,10 +43,7 @@
 #define LOBRA_GEMM_DST 2
 #endif
 #ifndef LOBRA_GEMM_ISSUE_AT
-#define LOBRA_GEMM_ISSUE_AT 2      // K step of the tile after which the next tile's copies are issued (forward)
-#endif
-#ifndef LOBRA_GEMM_ISSUE_AT_NK
-#define LOBRA_GEMM_ISSUE_AT_NK 1   // the same for the backward product (W read along K)
+#define LOBRA_GEMM_ISSUE_AT 0      // 1 or 2: K step of a tile after which the next tile's copies go out; 0: from K
 #endif
 #ifndef LOBRA_GEMM_GM
 #define LOBRA_GEMM_GM 0      // 0: chosen from K by the launcher
@@ -127,7 +124,7 @@ template <int N> __device__ __forceinline__ void wait_vmcnt()
 
 }  // namespace
 
-template <bool W_KN, int WM, int WN, bool DMA>
+template <bool W_KN, int WM, int WN, bool DMA, int IA>
 __global__ __launch_bounds__(64 * WM * WN)
 void gemm_mfma_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const uint16_t* __restrict__ W,
                       const uint16_t* __restrict__ P, const uint16_t* __restrict__ M,
@@ -301,10 +298,9 @@ void gemm_mfma_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const uint16_t
             else if (DST >= 3 && kt + 1 < KT) wait_vmcnt<(DST >= 3 ? 1 : 0) * NPW>();
             else wait_vmcnt<0>();
             __builtin_amdgcn_s_barrier();
-            // the copies of the tile that reuses the freed stage go out after K step IA of this tile:
-            // right after the barrier they would compete with the tile's first LDS reads (forward: after
-            // two of the four steps; backward, where long K gains 2-5 % from it, after one)
-            constexpr int IA = W_KN ? LOBRA_GEMM_ISSUE_AT : LOBRA_GEMM_ISSUE_AT_NK;
+            // the copies of the tile that reuses the freed stage go out after one or two of this tile's
+            // four K steps (right after the barrier they would compete with the tile's first LDS reads);
+            // which of the two is faster depends on K, so the launcher chooses the instantiation
             compute(kt % DST, 0, IA);
             if (kt + DST - 1 < KT) issue(kt + DST - 1);
             compute(kt % DST, IA, DBK / 16);
@@ -561,7 +557,7 @@ void gemm_mfma_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const uint16_t
     }
 }
 
-template <bool W_KN, int WM, int WN, bool DMA>
+template <bool W_KN, int WM, int WN, bool DMA, int IA>
 static hipError_t launch_gemm(const PlanDev& pd, const void* Z, const void* W, const void* P,
                               const void* M, void* C, int32_t K, int32_t N, int32_t ldw, int32_t ldc,
                               int32_t nproj, int32_t proj, int32_t tiles_m, int32_t tiles_n, int32_t gm,
@@ -575,12 +571,12 @@ static hipError_t launch_gemm(const PlanDev& pd, const void* Z, const void* W, c
     if (e != hipSuccess) return e;
     const uint64_t bit = uint64_t(1) << (dev & 63);
     if (!(raised.load(std::memory_order_acquire) & bit)) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mfma_kernel<W_KN, WM, WN, DMA>),
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mfma_kernel<W_KN, WM, WN, DMA, IA>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
         if (e != hipSuccess) return e;
         raised.fetch_or(bit, std::memory_order_release);
     }
-    gemm_mfma_kernel<W_KN, WM, WN, DMA><<<dim3(uint32_t(tiles_m) * uint32_t(tiles_n)), 64 * WM * WN, bytes, st>>>(
+    gemm_mfma_kernel<W_KN, WM, WN, DMA, IA><<<dim3(uint32_t(tiles_m) * uint32_t(tiles_n)), 64 * WM * WN, bytes, st>>>(
         pd, (const uint16_t*)Z, (const uint16_t*)W, (const uint16_t*)P, (const uint16_t*)M, (uint16_t*)C,
         K, N, ldw, ldc, nproj, proj, tiles_m, tiles_n, gm);
     return hipGetLastError();
@@ -604,14 +600,21 @@ hipError_t gemm_mfma(const PlanDev& pd, bool transW, const void* Z, const void* 
     // their re-reads; measured on the five workloads, long K wants shorter sweeps (K = 8192 .. 28672:
     // 4 rows up to 7 % faster than 8; K = 4096: 5 .. 8 alike)
     const int32_t gm = LOBRA_GEMM_GM > 0 ? LOBRA_GEMM_GM : (K > 4096 ? 4 : 6);
+    // K step of a tile after which the next tile's copies are issued: long K gains 2-5 % from the earlier one
+    const int32_t issue_at = LOBRA_GEMM_ISSUE_AT > 0 ? LOBRA_GEMM_ISSUE_AT : (K > 4096 ? 1 : 2);
     // the direct-to-LDS pipeline needs whole K tiles of 32; other K take the register-staged kernel
     const bool dma = LOBRA_GEMM_DMA && K % DBK == 0;
+#define LOBRA_GEMM_GO(KN, DM, IA_) \
+    return launch_gemm<KN, LOBRA_GEMM_WM, LOBRA_GEMM_WN, DM, IA_>(pd, Z, W, P, M, C, K, N, ldw, ldc, nproj, proj, tiles_m, tiles_n, gm, st)
     if (!transW) {
-        if (dma) return launch_gemm<true, LOBRA_GEMM_WM, LOBRA_GEMM_WN, true>(pd, Z, W, P, M, C, K, N, ldw, ldc, nproj, proj, tiles_m, tiles_n, gm, st);
-        return launch_gemm<true, LOBRA_GEMM_WM, LOBRA_GEMM_WN, false>(pd, Z, W, P, M, C, K, N, ldw, ldc, nproj, proj, tiles_m, tiles_n, gm, st);
+        if (!dma) LOBRA_GEMM_GO(true, false, 2);
+        if (issue_at == 1) LOBRA_GEMM_GO(true, true, 1);
+        LOBRA_GEMM_GO(true, true, 2);
     }
-    if (dma) return launch_gemm<false, LOBRA_GEMM_WM, LOBRA_GEMM_WN, true>(pd, Z, W, P, M, C, K, N, ldw, ldc, nproj, proj, tiles_m, tiles_n, gm, st);
-    return launch_gemm<false, LOBRA_GEMM_WM, LOBRA_GEMM_WN, false>(pd, Z, W, P, M, C, K, N, ldw, ldc, nproj, proj, tiles_m, tiles_n, gm, st);
+    if (!dma) LOBRA_GEMM_GO(false, false, 2);
+    if (issue_at == 1) LOBRA_GEMM_GO(false, true, 1);
+    LOBRA_GEMM_GO(false, true, 2);
+#undef LOBRA_GEMM_GO
 }
 
 }  // namespace lobra
