@@ -158,7 +158,8 @@ LOBRA_API lobra_status lobra_mlora_plan_query(const lobra_mlora_plan *plan, int3
  *   s             : device fp32 [n_tasks]
  *   h_save        : device, h_save_bytes, or NULL.  When given, bwd can reuse the
  *                   down-projected activations instead of recomputing them
- *   ws, ws_bytes  : device scratch of at least fwd_ws_bytes (NULL allowed when that is 0)
+ *   ws, ws_bytes  : device scratch of at least fwd_ws_bytes; only used (and only checked) when
+ *                   h_save is NULL
  *   hip_stream    : hipStream_t (NULL = default stream); work is enqueued, not awaited
  * x, W, A, B, s are read only; y and h_save are overwritten. */
 LOBRA_API lobra_status lobra_mlora_fwd(const lobra_mlora_plan *plan, const void *x, const void *W,
@@ -170,7 +171,7 @@ LOBRA_API lobra_status lobra_mlora_fwd(const lobra_mlora_plan *plan, const void 
  *   dy      : device [T, d_out], element type desc.dtype
  *   h_saved : what the matching fwd call wrote into h_save, or NULL to recompute from x
  *   dx      : device [T, d_in], overwritten (ignored, may be NULL, with LOBRA_FLAG_NO_DX)
- *   dA, dB  : device fp32 [R_tot, d_in] / [R_tot, d_out]; overwritten (rows of a task without
+ *   dA, dB  : device fp32 [R_tot, d_in] / [R_tot, d_out / n_proj]; overwritten (rows of a task without
  *             tokens become 0), or added to with LOBRA_FLAG_ACCUMULATE_GRADS
  *   ws      : device scratch of at least bwd_ws_bytes
  * The reductions run in a fixed order: results are bit-identical from run to run. */
