@@ -146,9 +146,13 @@ LOBRA_API lobra_status lobra_mlora_plan_sizes(const lobra_mlora_plan *plan, size
  *   LOBRA_Q_GRAD_CHUNKS  n x {block_begin, block_end, task, partial_row0}: reduction work items
  *   LOBRA_Q_TASK_CHUNKS  [n_tasks+1]: prefix of chunks per task
  *   LOBRA_Q_BLOCK_RUNS   [n_runs+1]: token blocks run[k] .. run[k+1]-1 (all of one task) are
- *                        projected by one workgroup */
+ *                        projected by one workgroup
+ *   LOBRA_Q_BLOCK_ORDER  order in which the token blocks are handed to the down-projection's
+ *   LOBRA_Q_RUN_ORDER    workgroups, and the same for the runs: a permutation by descending rank
+ *                        (stable), or empty when that is the stored order (e.g. equal ranks) */
 enum { LOBRA_Q_SEGMENTS = 0, LOBRA_Q_ROWBLOCK_SEG = 1, LOBRA_Q_TOKEN_BLOCKS = 2,
-       LOBRA_Q_GRAD_CHUNKS = 3, LOBRA_Q_TASK_CHUNKS = 4, LOBRA_Q_BLOCK_RUNS = 5 };
+       LOBRA_Q_GRAD_CHUNKS = 3, LOBRA_Q_TASK_CHUNKS = 4, LOBRA_Q_BLOCK_RUNS = 5,
+       LOBRA_Q_BLOCK_ORDER = 6, LOBRA_Q_RUN_ORDER = 7 };
 LOBRA_API lobra_status lobra_mlora_plan_query(const lobra_mlora_plan *plan, int32_t what, int32_t *out,
                                     size_t capacity, size_t *count);
 

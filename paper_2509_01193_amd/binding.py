@@ -19,6 +19,7 @@ F32, BF16 = 0, 1
 FLAG_ACCUMULATE_GRADS, FLAG_NO_DX = 1, 2
 PLAN_HOST_ONLY, PLAN_PLAIN_KERNELS = 1, 2
 Q_SEGMENTS, Q_ROWBLOCK_SEG, Q_TOKEN_BLOCKS, Q_GRAD_CHUNKS, Q_TASK_CHUNKS, Q_BLOCK_RUNS = 0, 1, 2, 3, 4, 5
+Q_BLOCK_ORDER, Q_RUN_ORDER = 6, 7
 MAX_RANK = 128
 
 EXPORTS = [

@@ -29,6 +29,8 @@ PlanDev device_view(const Plan& p)
     d.rank_off = b + p.o_rank_off;
     d.task_tb_off = b + p.o_task_tb;
     d.sb_off = b + p.o_sb;
+    d.tb_order = p.tb_order.empty() ? nullptr : b + p.o_tb_order;
+    d.sb_order = p.sb_order.empty() ? nullptr : b + p.o_sb_order;
     d.T = int32_t(p.desc.T);
     d.d_in = p.desc.d_in;
     d.d_out = p.desc.d_out;
@@ -180,6 +182,14 @@ lobra_status lobra_mlora_plan_query(const lobra_mlora_plan* plan, int32_t what, 
     case LOBRA_Q_BLOCK_RUNS:
         src = plan->sb_off.data();
         n = plan->sb_off.size();
+        break;
+    case LOBRA_Q_BLOCK_ORDER:
+        src = plan->tb_order.data();
+        n = plan->tb_order.size();
+        break;
+    case LOBRA_Q_RUN_ORDER:
+        src = plan->sb_order.data();
+        n = plan->sb_order.size();
         break;
     default:
         return LOBRA_ERR_SHAPE;

@@ -18,6 +18,8 @@ struct PlanDev {
     const int32_t* rank_off;       // [n_tasks+1]
     const int32_t* task_tb_off;    // [n_tasks+1]
     const int32_t* sb_off;         // [nsb+1]
+    const int32_t* tb_order;       // [ntb] launch order of the token blocks, or NULL = as stored
+    const int32_t* sb_order;       // [nsb] launch order of the runs, or NULL = as stored
     int32_t T, d_in, d_out, n_tasks, nseg, ntb, nchunks, r_max, r_pad, R_tot, nsb, shrink_group, n_proj, dg;
 };
 

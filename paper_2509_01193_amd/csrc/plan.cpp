@@ -129,6 +129,21 @@ lobra_status build_host_plan(const lobra_mlora_desc* d, uint32_t flags, Plan* p)
             for (int32_t t = 0; t < n; ++t)
                 for (int32_t b = p->task_tb_off[t]; b < p->task_tb_off[t + 1]; b += g)
                     p->sb_off.push_back(std::min(b + g, p->task_tb_off[t + 1]));
+            // 3c. launch order by descending rank.  A workgroup's cost grows with its task's rank (the
+            //     adapter rows it reads next to its 32 token rows), and the lists above are in task
+            //     order, so with mixed ranks whichever task comes last would make up the launch's tail.
+            auto by_rank = [&](size_t count, auto task_of, std::vector<int32_t>& order) {
+                order.resize(count);
+                for (size_t i = 0; i < count; ++i) order[i] = int32_t(i);
+                auto rank_of = [&](int32_t i) { const int32_t t = task_of(i); return p->rank_off[t + 1] - p->rank_off[t]; };
+                std::stable_sort(order.begin(), order.end(),
+                                 [&](int32_t a, int32_t b) { return rank_of(a) > rank_of(b); });
+                bool identity = true;
+                for (size_t i = 0; i < count && identity; ++i) identity = order[i] == int32_t(i);
+                if (identity) order.clear();
+            };
+            by_rank(p->tb.size(), [&](int32_t i) { return p->tb[size_t(i)].task; }, p->tb_order);
+            by_rank(p->sb_off.size() - 1, [&](int32_t i) { return p->tb[size_t(p->sb_off[size_t(i)])].task; }, p->sb_order);
         }
 
         // 4. reduction chunks: runs of token blocks of one task.  The chunk length is chosen so
@@ -199,6 +214,8 @@ std::vector<int32_t> pack_blob(Plan* p)
     p->o_rank_off = put(p->rank_off.data(), p->rank_off.size());
     p->o_task_tb = put(p->task_tb_off.data(), p->task_tb_off.size());
     p->o_sb = put(p->sb_off.data(), p->sb_off.size());
+    p->o_tb_order = put(p->tb_order.data(), p->tb_order.size());
+    p->o_sb_order = put(p->sb_order.data(), p->sb_order.size());
     while (blob.size() % 4) blob.push_back(0);
     return blob;
 }

@@ -38,6 +38,9 @@ struct Plan {
     std::vector<int32_t> task_tb_off;   // [n_tasks+1]
     std::vector<int32_t> sb_off;        // [nsb+1] runs of <= shrink_group token blocks of one task
     int32_t shrink_group = 1;           // token blocks that one shrink workgroup handles (1 or 4)
+    // launch order of the shrink workgroups when ranks differ: token blocks / runs by descending rank
+    // (stable), so that the most expensive ones do not form the tail of the launch.  Empty: as stored.
+    std::vector<int32_t> tb_order, sb_order;
     std::vector<GradChunk> chunks;      // grouped by task
     std::vector<int32_t> task_chunk_off;// [n_tasks+1]
     int32_t part_rows = 0;              // rows of the partial-sum buffer = sum over chunks of r_t
@@ -60,7 +63,7 @@ struct Plan {
     size_t blob_bytes = 0;
     // offsets (in int32 units) of the lists inside the blob
     size_t o_cseg_off = 0, o_cseg_task = 0, o_rowblk = 0, o_tb = 0, o_chunks = 0,
-           o_task_chunk = 0, o_rank_off = 0, o_task_tb = 0, o_sb = 0;
+           o_task_chunk = 0, o_rank_off = 0, o_task_tb = 0, o_sb = 0, o_tb_order = 0, o_sb_order = 0;
 };
 
 lobra_status validate(const lobra_mlora_desc* d);

@@ -46,7 +46,7 @@ __global__ __launch_bounds__(64 * NWV) void shrink_mfma_kernel(PlanDev pd, const
     // that projection's column block of dy (row pitch ldz), M its rows of the compact up factors,
     // and the task's rank rows it reads and writes are the window [proj r, (proj + 1) r).
     __shared__ float red[NWV][2][NRB][64][4];   // [wave][token half][rank block][lane][4]
-    const int32_t bi = blockIdx.x;
+    const int32_t bi = pd.tb_order ? pd.tb_order[blockIdx.x] : int32_t(blockIdx.x);
     const TokenBlock b = pd.tb[bi];
     const int32_t r = (pd.rank_off[b.task + 1] - b.rank_row0) / nproj;
     const int32_t pofs = proj * r;               // first rank of the window inside the task's rows
@@ -190,8 +190,9 @@ __global__ __launch_bounds__(256) void shrink_lds_kernel(PlanDev pd, const uint1
     constexpr int CH = ROWS * 16;                        // 16-byte chunks per staged slab
     constexpr int MLD = (CH + 255) / 256;                // chunks per thread
     __shared__ __attribute__((aligned(16))) unsigned char ms[2][ROWS * 256];
-    const int32_t tb0 = pd.sb_off[blockIdx.x];
-    const int32_t cnt = pd.sb_off[blockIdx.x + 1] - tb0;
+    const int32_t run = pd.sb_order ? pd.sb_order[blockIdx.x] : int32_t(blockIdx.x);
+    const int32_t tb0 = pd.sb_off[run];
+    const int32_t cnt = pd.sb_off[run + 1] - tb0;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const bool active = wave < cnt;                      // wave-uniform: this wave has a token block
     const TokenBlock b = pd.tb[tb0 + min(wave, cnt - 1)];

@@ -130,6 +130,15 @@ def check_plan(p):
     assert runs[0] == 0 and runs[-1] == len(tb) and (np.diff(runs) >= 1).all() and (np.diff(runs) <= 4).all()
     for r0, r1 in zip(runs[:-1], runs[1:]):
         assert (tb[r0:r1, 2] == tb[r0, 2]).all()
+    # launch order of blocks and runs: by descending rank, ties in stored order; empty = stored order
+    ranks = np.asarray(p.ranks)
+    for what, tasks in ((bd.Q_BLOCK_ORDER, tb[:, 2]), (bd.Q_RUN_ORDER, tb[runs[:-1], 2] if len(tb) else tb[:0, 2])):
+        order = plan.query(what)
+        expect = np.argsort(-ranks[tasks], kind="stable") if len(tasks) else np.zeros(0, np.int64)
+        if len(order) == 0:
+            assert (expect == np.arange(len(tasks))).all()
+        else:
+            assert (order == expect).all() and not (expect == np.arange(len(tasks))).all()
     a, b, c = plan.h_save_bytes, plan.fwd_ws_bytes, plan.bwd_ws_bytes
     assert c >= prow * max(p.d_in, p.d_out) * 4
     plan.close()
