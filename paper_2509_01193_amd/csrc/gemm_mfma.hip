@@ -5,16 +5,22 @@
 // (paper section 2.1: X W + X (down)(up); section 1: one shared base product for the fused batch,
 // a per-task adapter product on top of it).
 //
-// Tiling: 256 x 256 x 64 per workgroup of WM x WN waves (default 4 x 2 = 512 threads, two waves per
-// SIMD), every wave owns (256/WM) x (256/WN) as blocks of v_mfma_f32_32x32x16_bf16 with fp32
-// accumulators.  The MFMA "A" operand is fed from W and the "B" operand from Z, so a lane ends up
-// with four consecutive output columns of one row, which packs into 8-byte LDS writes in the epilogue.
+// Tiling: 256 x 256 x 64 per workgroup, blocks of v_mfma_f32_32x32x16_bf16 with fp32 accumulators.  The
+// MFMA "A" operand is fed from W and the "B" operand from Z, so a lane ends up with four consecutive
+// output columns of one row, which packs into 8-byte LDS writes in the epilogue.
 //
-// Two loaders behind one kernel template:
-//   DMA  (K a multiple of 64): K tiles go global -> LDS with global_load_lds_dwordx4, no registers
-//        and no ds_write in between; two LDS stages; the copies of tile kt+1 are issued in the middle
-//        of tile kt, after the barrier that freed their stage; every row segment is one 128-byte line.
-//   register-staged (any K that is a multiple of 8): global -> VGPR -> LDS with a zero-filled K tail.
+// Two main loops behind one kernel template:
+//   DMA  (K a multiple of 64): four waves of 128 x 128 (one per SIMD, the accumulators in the 256 AGPRs).
+//        K tiles go global -> LDS with global_load_lds_dwordx4 (no registers, no ds_write) into two LDS
+//        stages; every row segment a copy fetches is one 128-byte line.  With one wave per SIMD nothing
+//        hides a wave's own latencies, so the loop is software-pipelined by hand and its order is pinned
+//        (sched_barrier): a K step is eight sections of {MFMA, copy, MFMA, fragment read}; the fragments
+//        of K step s + 1 are read during step s; the barrier of a tile stands in front of its last K step,
+//        whose fragments are already in registers, so MFMAs and not LDS latency follow the barrier; the
+//        stage it frees is refilled by copies spread over the next three K steps (one every section or
+//        two: issued back to back they block their wave for as long as the texture unit takes to accept them).
+//   register-staged (any K that is a multiple of 8): eight waves of 64 x 128, global -> VGPR -> LDS with
+//        a zero-filled K tail; the compiler schedules it.
 //
 // LDS layouts (DMA path; the register-staged path pads the forward W tile instead of swizzling it)
 //   Z tile, and the W tile when K is fastest (backward): [256 rows][64 k], 16-byte chunk c of a row
@@ -26,9 +32,8 @@
 //       address each lane fetches from.
 //   C staging in the epilogue: per wave [rows][cols + 8] bf16, written back with non-temporal stores.
 //
-// Tuning macros (defaults are what the measurements chose): LOBRA_GEMM_WM/WN wave grid, LOBRA_GEMM_DBK/
-// DST K-tile width and stage count of the DMA path, LOBRA_GEMM_ISSUE_AT, LOBRA_GEMM_GM tile-rows per
-// sweep of the XCD-aware tile order, LOBRA_GEMM_NT_STORE, LOBRA_GEMM_DMA.
+// Tuning macros (defaults are what the measurements chose): LOBRA_GEMM_GM tile-rows per sweep of the
+// XCD-aware tile order, LOBRA_GEMM_NT_STORE, LOBRA_GEMM_DMA.
 #include <atomic>
 
 #include "kernels.h"
@@ -36,26 +41,11 @@
 #ifndef LOBRA_GEMM_DMA
 #define LOBRA_GEMM_DMA 1
 #endif
-#ifndef LOBRA_GEMM_DBK
-#define LOBRA_GEMM_DBK 64
-#endif
-#ifndef LOBRA_GEMM_DST
-#define LOBRA_GEMM_DST 2
-#endif
-#ifndef LOBRA_GEMM_ISSUE_AT
-#define LOBRA_GEMM_ISSUE_AT 0      // 1 or 2: K step of a tile after which the next tile's copies go out; 0: from K
-#endif
 #ifndef LOBRA_GEMM_GM
 #define LOBRA_GEMM_GM 0      // 0: chosen from K by the launcher
 #endif
 #ifndef LOBRA_GEMM_NT_STORE
 #define LOBRA_GEMM_NT_STORE 1
-#endif
-#ifndef LOBRA_GEMM_WM
-#define LOBRA_GEMM_WM 4
-#endif
-#ifndef LOBRA_GEMM_WN
-#define LOBRA_GEMM_WN 2
 #endif
 
 namespace lobra {
@@ -74,14 +64,14 @@ constexpr int WKN_PITCH = BN + 32;                  // elements
 constexpr int WT_KN_BYTES = BK * WKN_PITCH * 2;     // 36 KiB
 constexpr int WT_NK_BYTES = BN * BK * 2;            // 32 KiB
 
-// direct-to-LDS variant: K tile of DBK, DST stages of (Z tile + W tile)
-constexpr int DBK = LOBRA_GEMM_DBK, DST = LOBRA_GEMM_DST;
+// direct-to-LDS loop: two stages of (Z tile + W tile)
+constexpr int DBK = BK;
 constexpr int DZT_BYTES = BM * DBK * 2, DSTAGE_BYTES = 2 * DZT_BYTES;
-static_assert((DBK == 32 || DBK == 64) && DST >= 2 && DST <= 4 && DST * DSTAGE_BYTES <= 160 * 1024, "LDS budget");
+static_assert(2 * DSTAGE_BYTES <= 160 * 1024, "LDS budget");
 
 template <bool W_KN, int WN, bool DMA> constexpr int lds_bytes()
 {
-    const int loop = DMA ? DST * DSTAGE_BYTES : 2 * ZT_BYTES + 2 * (W_KN ? WT_KN_BYTES : WT_NK_BYTES);
+    const int loop = DMA ? 2 * DSTAGE_BYTES : 2 * ZT_BYTES + 2 * (W_KN ? WT_KN_BYTES : WT_NK_BYTES);
     const int cs = BM * (BN + 8 * WN) * 2;          // all waves' C staging
     return loop > cs ? loop : cs;
 }
@@ -124,7 +114,7 @@ template <int N> __device__ __forceinline__ void wait_vmcnt()
 
 }  // namespace
 
-template <bool W_KN, int WM, int WN, bool DMA, int IA>
+template <bool W_KN, int WM, int WN, bool DMA>
 __global__ __launch_bounds__(64 * WM * WN)
 void gemm_mfma_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const uint16_t* __restrict__ W,
                       const uint16_t* __restrict__ P, const uint16_t* __restrict__ M,
@@ -195,27 +185,29 @@ void gemm_mfma_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const uint16_t
 
     const u32x4 zero4 = {0u, 0u, 0u, 0u};
     if constexpr (DMA) {
-        // ---- direct-to-LDS pipeline: K tiles of DBK, DST LDS stages, loads issued DST-1 tiles ahead
-        // Stage layout: Z [256 rows][DBK k] (DBK*2 bytes per row, 16-byte chunk c stored at c ^ f(row)),
-        // then W either [256 n][DBK k] in the same layout (backward) or [DBK k][256 n] (forward, 512
-        // bytes per k row, 16-byte chunk c stored at c ^ ((k & 3) << 2) so that the 4 k rows of one
-        // transpose read sit in different bank quarters).  f spreads the 16 rows of one ds_read_b128
-        // pass over all banks: (row >> 2) & 3 for 64-byte rows, (row >> 1) & 7 for 128-byte rows.
-        // A wave-wide copy fills 1 KiB of LDS in lane order, so the swizzle is applied to the global
-        // address each lane fetches from.
+        // ---- direct-to-LDS pipeline, four waves of 128 x 128
+        // Stage layout: Z [256 rows][64 k] (128 bytes per row, 16-byte chunk c stored at c ^ f(row)), then W
+        // either [256 n][64 k] in the same layout (backward) or [64 k][256 n] (forward, 512 bytes per k row,
+        // 16-byte chunk c stored at c ^ ((k & 3) << 2) so that the 4 k rows of one transpose read sit in
+        // different bank quarters).  f(row) = (row >> 1) & 7 spreads the 16 rows of one ds_read_b128 pass
+        // over all banks.  A wave-wide copy fills 1 KiB of LDS in lane order, so the swizzle is applied to
+        // the global address each lane fetches from.
         constexpr int NW = WM * WN;
-        constexpr int CPRW = DBK / 8;               // 16-byte chunks per row of the [rows][DBK] layout
-        constexpr int RPB = 64 / CPRW;              // rows per 1 KiB block
         constexpr int NBZ = (DBK / 2) / NW;         // 1 KiB blocks per wave, for Z and for W each
+        constexpr int NU = MB + NB;                 // fragments per K step = sections per K step
+        constexpr int KS = DBK / 16;                // K steps per tile
+        static_assert(NW == 4 && MB * NB == 2 * NU && 2 * NBZ == 2 * NU && KS == 4,
+                      "four waves of 128 x 128: two MFMAs and at most one copy per section");
+        const int wave_u = __builtin_amdgcn_readfirstlane(wave);
         const uint32_t lds0 = uint32_t(uintptr_t((__attribute__((address_space(3))) unsigned char*)lds));
-        auto fz = [](int row) { return DBK == 32 ? (row >> 2) & 3 : (row >> 1) & 7; };
-        uint32_t zvo[NBZ], wvo[NBZ];
+        auto fz = [](int row) { return (row >> 1) & 7; };
+        uint32_t zvo[NBZ], wvo[NBZ];                // per-lane source offsets of this wave's copies
 #pragma unroll
         for (int j = 0; j < NBZ; ++j) {
             const int blk = wave + NW * j;
             {
-                const int row = RPB * blk + lane / CPRW;
-                const int c = (lane % CPRW) ^ fz(row);
+                const int row = 8 * blk + lane / 8;
+                const int c = (lane % 8) ^ fz(row);
                 zvo[j] = (uint32_t(min(row, T - 1 - row0)) * uint32_t(K) + 8u * c) * 2u;
                 if (!W_KN) wvo[j] = (uint32_t(min(row, N - 1 - col0)) * uint32_t(ldw) + 8u * c) * 2u;
             }
@@ -227,83 +219,102 @@ void gemm_mfma_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const uint16_t
         }
         const unsigned char* zbase = reinterpret_cast<const unsigned char*>(Z + size_t(row0) * K);
         const unsigned char* wbase = reinterpret_cast<const unsigned char*>(W_KN ? W + col0 : W + size_t(col0) * ldw);
-        auto issue = [&](int32_t kt) {              // all of this wave's copies for K tile kt
-            const uint32_t st = lds0 + uint32_t(kt % DST) * DSTAGE_BYTES;
-            const unsigned char* zb = zbase + size_t(kt) * (DBK * 2);
-            const unsigned char* wb = W_KN ? wbase + size_t(kt) * DBK * ldw * 2 : wbase + size_t(kt) * (DBK * 2);
-#pragma unroll
-            for (int j = 0; j < NBZ; ++j) dma16(st + (wave + NW * j) * 1024, zb, zvo[j]);
-#pragma unroll
-            for (int j = 0; j < NBZ; ++j) dma16(st + DZT_BYTES + (wave + NW * j) * 1024, wb, wvo[j]);
+        const int32_t KT = K / DBK;                 // the launcher guarantees K % DBK == 0
+        auto zsrc = [&](int32_t kt) { return zbase + size_t(kt) * (DBK * 2); };
+        auto wsrc = [&](int32_t kt) { return W_KN ? wbase + size_t(kt) * DBK * ldw * 2 : wbase + size_t(kt) * (DBK * 2); };
+        // copy c of a tile: c < NBZ is a Z block, the others are W blocks
+        auto copy = [&](uint32_t stage_addr, const unsigned char* zb, const unsigned char* wb, int c) {
+            if (c < NBZ) dma16(stage_addr + (wave_u + NW * c) * 1024, zb, zvo[c]);
+            else dma16(stage_addr + DZT_BYTES + (wave_u + NW * (c - NBZ)) * 1024, wb, wvo[c - NBZ]);
         };
-        // operand fragments of K step ks of a stage
-        auto load_frags = [&](int stage, int ks, bf16x8 (&zf)[MB], bf16x8 (&wf)[NB]) {
+        // operand fragment u of K step ks of a stage: u < MB is zf[u], MB + nb is wf[nb]
+        auto read_unit = [&](int stage, int ks, int u, bf16x8 (&zf)[MB], bf16x8 (&wf)[NB]) {
             const unsigned char* zs = lds + stage * DSTAGE_BYTES;
             const unsigned char* ws = zs + DZT_BYTES;
-#pragma unroll
-            for (int mb = 0; mb < MB; ++mb) {
-                const int row = wm * TM + mb * 32 + l32;
-                zf[mb] = *reinterpret_cast<const bf16x8*>(zs + row * (DBK * 2) + ((2 * ks + lh) ^ fz(row)) * 16);
-            }
-            if (W_KN) {
+            if (u < MB) {
+                const int row = wm * TM + u * 32 + l32;
+                zf[u] = *reinterpret_cast<const bf16x8*>(zs + row * (DBK * 2) + ((2 * ks + lh) ^ fz(row)) * 16);
+            } else if (W_KN) {
+                const int nb = u - MB;
                 const int s = lane & 15, g = lane >> 4;
                 const int krow = 16 * ks + 8 * (g >> 1) + (s >> 2);
-#pragma unroll
-                for (int nb = 0; nb < NB; ++nb) {
-                    const int n = wn * TN + nb * 32 + 16 * (g & 1) + 4 * (s & 3);
-                    const int c = (n >> 3) ^ ((krow & 3) << 2);
-                    const unsigned char* p0 = ws + krow * 512 + c * 16 + (n & 7) * 2;
-                    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                        (s16x4 __attribute__((address_space(3)))*)(p0));
-                    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                        (s16x4 __attribute__((address_space(3)))*)(p0 + 4 * 512));
-                    union { s16x4 h[2]; bf16x8 b; } cv;
-                    cv.h[0] = lo;
-                    cv.h[1] = hi;
-                    wf[nb] = cv.b;
-                }
+                const int n = wn * TN + nb * 32 + 16 * (g & 1) + 4 * (s & 3);
+                const int c = (n >> 3) ^ ((krow & 3) << 2);
+                const unsigned char* p0 = ws + krow * 512 + c * 16 + (n & 7) * 2;
+                const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p0));
+                const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p0 + 4 * 512));
+                union { s16x4 h[2]; bf16x8 b; } cv;
+                cv.h[0] = lo;
+                cv.h[1] = hi;
+                wf[nb] = cv.b;
             } else {
+                const int nb = u - MB;
+                const int row = wn * TN + nb * 32 + l32;
+                wf[nb] = *reinterpret_cast<const bf16x8*>(ws + row * (DBK * 2) + ((2 * ks + lh) ^ fz(row)) * 16);
+            }
+        };
+        // One K step: the 16 MFMAs on fragments (zc, wc) in eight sections, each {MFMA, copy, MFMA, read}:
+        // what is not an MFMA is issued while one runs.  The reads fetch the fragments (zn, wn_) of K step rks
+        // of stage rstage, one per section, or (early) two per section in the first half, so that the last
+        // one has arrived when the step ends.  Copies: those sections whose bit is set in `mask` issue the
+        // next copy of the tile at (zb, wb) into the stage at cst, counting from copy c0.
+        auto kstep = [&](int rstage, int rks, bf16x8 (&zc)[MB], bf16x8 (&wc)[NB], bf16x8 (&zn)[MB], bf16x8 (&wn_)[NB],
+                         int mask, int c0, uint32_t cst, const unsigned char* zb, const unsigned char* wb, bool early) {
+            int c = c0;
 #pragma unroll
-                for (int nb = 0; nb < NB; ++nb) {
-                    const int row = wn * TN + nb * 32 + l32;
-                    wf[nb] = *reinterpret_cast<const bf16x8*>(ws + row * (DBK * 2) + ((2 * ks + lh) ^ fz(row)) * 16);
+            for (int u = 0; u < NU; ++u) {
+                {
+                    const int m = 2 * u, mb = m / NB, nb = m % NB;
+                    acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wc[nb], zc[mb], acc[mb][nb], 0, 0, 0);
                 }
+                __builtin_amdgcn_sched_barrier(0);
+                if ((mask >> u) & 1) copy(cst, zb, wb, c++);
+                if (early && 2 * u < NU) read_unit(rstage, rks, 2 * u, zn, wn_);
+                __builtin_amdgcn_sched_barrier(0);
+                {
+                    const int m = 2 * u + 1, mb = m / NB, nb = m % NB;
+                    acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wc[nb], zc[mb], acc[mb][nb], 0, 0, 0);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                if (!early) read_unit(rstage, rks, u, zn, wn_);
+                else if (2 * u + 1 < NU) read_unit(rstage, rks, 2 * u + 1, zn, wn_);
+                __builtin_amdgcn_sched_barrier(0);
             }
         };
-        auto mma = [&](const bf16x8 (&zf)[MB], const bf16x8 (&wf)[NB]) {
+        // the 2 NBZ = 16 copies of a tile go out after the barrier that freed their stage: 6 in the K step
+        // behind it, 5 in each of the next two; the K step in front of the next barrier issues none
+        constexpr int M3 = 0xDB, M0 = 0xB5, M1 = 0xB5;
+        constexpr int C0 = __builtin_popcount(M3), C1 = C0 + __builtin_popcount(M0);
+        static_assert(C1 + __builtin_popcount(M1) == 2 * NBZ, "every copy once");
+
+        bf16x8 zf[2][MB], wf[2][NB];
 #pragma unroll
-            for (int mb = 0; mb < MB; ++mb)
+        for (int c = 0; c < 2 * NBZ; ++c) copy(lds0, zsrc(0), wsrc(0), c);
+        if (KT > 1) {
 #pragma unroll
-                for (int nb = 0; nb < NB; ++nb)
-                    acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[nb], zf[mb], acc[mb][nb], 0, 0, 0);
-        };
-        // K steps ks0 .. ks1-1 of a stage (the compiler interleaves the LDS reads of a step with the MFMAs of the one before)
-        auto compute = [&](int stage, int ks0, int ks1) {
+            for (int c = 0; c < 2 * NBZ; ++c) copy(lds0 + DSTAGE_BYTES, zsrc(1), wsrc(1), c);
+            wait_vmcnt<2 * NBZ>();
+        } else {
+            wait_vmcnt<0>();
+        }
+        __builtin_amdgcn_s_barrier();
 #pragma unroll
-            for (int ks = ks0; ks < ks1; ++ks) {
-                bf16x8 zf[MB], wf[NB];
-                load_frags(stage, ks, zf, wf);
-                mma(zf, wf);
-            }
-        };
-        constexpr int NPW = 2 * NBZ;                // copies per wave and K tile
-        const int32_t KT = K / DBK;                 // the launcher guarantees K % DBK == 0
-        for (int32_t s0 = 0; s0 < DST - 1; ++s0)
-            if (s0 < KT) issue(s0);
+        for (int u = 0; u < NU; ++u) read_unit(0, 0, u, zf[0], wf[0]);
         for (int32_t kt = 0; kt < KT; ++kt) {
-            // this wave's copies of tile kt have landed once at most the copies of the (up to DST-2)
-            // tiles issued after it are still outstanding; the barrier then covers the other waves'
-            // copies and tells that everybody is done reading the stage that is refilled next
-            if (DST >= 4 && kt + 2 < KT) wait_vmcnt<(DST >= 4 ? 2 : 0) * NPW>();
-            else if (DST >= 3 && kt + 1 < KT) wait_vmcnt<(DST >= 3 ? 1 : 0) * NPW>();
-            else wait_vmcnt<0>();
+            const int stg = kt & 1;
+            // Tile kt + 1 goes into the other stage (its first copies went out behind the previous barrier),
+            // tile kt + 2 into this one once the barrier below has freed it.  Past the end a valid tile is
+            // copied once more into a stage nobody reads any more, which keeps the loop free of branches.
+            const int32_t k1 = min(kt + 1, KT - 1), k2 = min(kt + 2, KT - 1);
+            const uint32_t st1 = lds0 + uint32_t(stg ^ 1) * DSTAGE_BYTES, st2 = lds0 + uint32_t(stg) * DSTAGE_BYTES;
+            kstep(stg, 1, zf[0], wf[0], zf[1], wf[1], M0, C0, st1, zsrc(k1), wsrc(k1), false);
+            kstep(stg, 2, zf[1], wf[1], zf[0], wf[0], M1, C1, st1, zsrc(k1), wsrc(k1), false);
+            kstep(stg, 3, zf[0], wf[0], zf[1], wf[1], 0, 0, st1, zsrc(k1), wsrc(k1), true);
+            // every wave has read the last fragments of this stage and its copies of tile kt + 1 have landed
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            wait_vmcnt<0>();
             __builtin_amdgcn_s_barrier();
-            // the copies of the tile that reuses the freed stage go out after one or two of this tile's
-            // four K steps (right after the barrier they would compete with the tile's first LDS reads);
-            // which of the two is faster depends on K, so the launcher chooses the instantiation
-            compute(kt % DST, 0, IA);
-            if (kt + DST - 1 < KT) issue(kt + DST - 1);
-            compute(kt % DST, IA, DBK / 16);
+            kstep(stg ^ 1, 0, zf[1], wf[1], zf[0], wf[0], M3, 0, st2, zsrc(k2), wsrc(k2), false);
         }
         wait_vmcnt<0>();
         __syncthreads();
@@ -557,7 +568,7 @@ void gemm_mfma_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const uint16_t
     }
 }
 
-template <bool W_KN, int WM, int WN, bool DMA, int IA>
+template <bool W_KN, int WM, int WN, bool DMA>
 static hipError_t launch_gemm(const PlanDev& pd, const void* Z, const void* W, const void* P,
                               const void* M, void* C, int32_t K, int32_t N, int32_t ldw, int32_t ldc,
                               int32_t nproj, int32_t proj, int32_t tiles_m, int32_t tiles_n, int32_t gm,
@@ -571,12 +582,12 @@ static hipError_t launch_gemm(const PlanDev& pd, const void* Z, const void* W, c
     if (e != hipSuccess) return e;
     const uint64_t bit = uint64_t(1) << (dev & 63);
     if (!(raised.load(std::memory_order_acquire) & bit)) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mfma_kernel<W_KN, WM, WN, DMA, IA>),
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mfma_kernel<W_KN, WM, WN, DMA>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
         if (e != hipSuccess) return e;
         raised.fetch_or(bit, std::memory_order_release);
     }
-    gemm_mfma_kernel<W_KN, WM, WN, DMA, IA><<<dim3(uint32_t(tiles_m) * uint32_t(tiles_n)), 64 * WM * WN, bytes, st>>>(
+    gemm_mfma_kernel<W_KN, WM, WN, DMA><<<dim3(uint32_t(tiles_m) * uint32_t(tiles_n)), 64 * WM * WN, bytes, st>>>(
         pd, (const uint16_t*)Z, (const uint16_t*)W, (const uint16_t*)P, (const uint16_t*)M, (uint16_t*)C,
         K, N, ldw, ldc, nproj, proj, tiles_m, tiles_n, gm);
     return hipGetLastError();
@@ -600,20 +611,17 @@ hipError_t gemm_mfma(const PlanDev& pd, bool transW, const void* Z, const void* 
     // their re-reads; measured on the five workloads, long K wants shorter sweeps (K = 8192 .. 28672:
     // 4 rows up to 7 % faster than 8; K = 4096: 5 .. 8 alike)
     const int32_t gm = LOBRA_GEMM_GM > 0 ? LOBRA_GEMM_GM : (K > 4096 ? 4 : 6);
-    // K step of a tile after which the next tile's copies are issued: long K gains 2-5 % from the earlier one
-    const int32_t issue_at = LOBRA_GEMM_ISSUE_AT > 0 ? LOBRA_GEMM_ISSUE_AT : (K > 4096 ? 1 : 2);
-    // the direct-to-LDS pipeline needs whole K tiles of 32; other K take the register-staged kernel
+    // the direct-to-LDS pipeline (four waves) needs whole K tiles of 64; other K take the register-staged
+    // kernel (eight waves)
     const bool dma = LOBRA_GEMM_DMA && K % DBK == 0;
-#define LOBRA_GEMM_GO(KN, DM, IA_) \
-    return launch_gemm<KN, LOBRA_GEMM_WM, LOBRA_GEMM_WN, DM, IA_>(pd, Z, W, P, M, C, K, N, ldw, ldc, nproj, proj, tiles_m, tiles_n, gm, st)
+#define LOBRA_GEMM_GO(KN, WM_, WN_, DM) \
+    return launch_gemm<KN, WM_, WN_, DM>(pd, Z, W, P, M, C, K, N, ldw, ldc, nproj, proj, tiles_m, tiles_n, gm, st)
     if (!transW) {
-        if (!dma) LOBRA_GEMM_GO(true, false, 2);
-        if (issue_at == 1) LOBRA_GEMM_GO(true, true, 1);
-        LOBRA_GEMM_GO(true, true, 2);
+        if (dma) LOBRA_GEMM_GO(true, 2, 2, true);
+        LOBRA_GEMM_GO(true, 4, 2, false);
     }
-    if (!dma) LOBRA_GEMM_GO(false, false, 2);
-    if (issue_at == 1) LOBRA_GEMM_GO(false, true, 1);
-    LOBRA_GEMM_GO(false, true, 2);
+    if (dma) LOBRA_GEMM_GO(false, 2, 2, true);
+    LOBRA_GEMM_GO(false, 4, 2, false);
 #undef LOBRA_GEMM_GO
 }
 
