@@ -8,10 +8,6 @@
 // each task of the fused batch has its own pair.)
 #include "kernels.h"
 
-#ifndef LOBRA_GRAD_STREAM_LOAD
-#define LOBRA_GRAD_STREAM_LOAD 1
-#endif
-
 namespace lobra {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -21,16 +17,14 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 namespace {
 // Load of data that is read once per launch and in whole cache lines (the gradient kernels' token
-// rows): marked non-temporal, so that it does not displace the rank-r operand that every workgroup re-reads.
-// Measured 7-11 % on the gradient kernels at ranks from 32; the projection kernels read half lines per
-// instruction and lose 15-20 % with it.
-template <typename V> __device__ __forceinline__ V stream_load(const V* p)
+// rows): marked non-temporal (STREAM), it does not displace the rank-r operand that every workgroup
+// re-reads.  Measured 7-11 % on the gradient kernels at ranks from 32 and on batches far larger than the
+// 256 MB infinity cache; a batch that fits that cache is better left in it for the kernels that follow
+// (the projection kernels, which read half lines per instruction, lose 15-20 % with the hint and never use it).
+template <bool STREAM, typename V> __device__ __forceinline__ V stream_load(const V* p)
 {
-#if LOBRA_GRAD_STREAM_LOAD
-    return __builtin_nontemporal_load(p);
-#else
-    return *p;
-#endif
+    if constexpr (STREAM) return __builtin_nontemporal_load(p);
+    else return *p;
 }
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v)
 {
@@ -360,7 +354,7 @@ hipError_t shrink_mfma(const PlanDev& pd, const void* Z, const void* M, const fl
 // ends up with CW consecutive columns.  Rank blocks beyond the task's rank are skipped.
 // The four waves' sums are combined through LDS in two steps (fixed order: ((w0+w2)+(w1+w3))).
 // -------------------------------------------------------------------------------------------------
-template <int NRB, int CW>
+template <int NRB, int CW, bool STREAM>
 __global__ __launch_bounds__(256) void grad_mfma_kernel(PlanDev pd, GradJob ja, GradJob jb, int32_t tiles_a)
 {
     typedef uint32_t zvec __attribute__((ext_vector_type(CW / 2)));
@@ -404,12 +398,12 @@ __global__ __launch_bounds__(256) void grad_mfma_kernel(PlanDev pd, GradJob ja, 
         if (tile_full) {
 #pragma unroll
             for (int q = 0; q < 8; ++q)
-                zin[q] = stream_load(reinterpret_cast<const zvec*>(Z + size_t(b.row0 + min(8 * g + q, b.nrows - 1)) * ldz + col));
+                zin[q] = stream_load<STREAM>(reinterpret_cast<const zvec*>(Z + size_t(b.row0 + min(8 * g + q, b.nrows - 1)) * ldz + col));
         } else {
 #pragma unroll
             for (int q = 0; q < 8; ++q) {
                 const int32_t row = b.row0 + min(8 * g + q, b.nrows - 1);
-                zin[q] = col_in ? stream_load(reinterpret_cast<const zvec*>(Z + size_t(row) * ldz + col)) : zvec(0u);
+                zin[q] = col_in ? stream_load<STREAM>(reinterpret_cast<const zvec*>(Z + size_t(row) * ldz + col)) : zvec(0u);
             }
         }
         u32x4 pf[NRB];
@@ -535,7 +529,7 @@ __global__ __launch_bounds__(256) void grad_lds_kernel(PlanDev pd, GradJob ja, G
         const TokenBlock b = pd.tb[bi];
 #pragma unroll
         for (int q = 0; q < 8; ++q)   // rows beyond the block repeat its last row; their P entries are zero
-            zin[q] = col_in ? stream_load(reinterpret_cast<const zvec*>(Z + size_t(b.row0 + min(8 * g + q, b.nrows - 1)) * ldz + col))
+            zin[q] = col_in ? stream_load<true>(reinterpret_cast<const zvec*>(Z + size_t(b.row0 + min(8 * g + q, b.nrows - 1)) * ldz + col))
                             : zvec(0u);
     };
     auto mac = [&](const zvec (&zin)[8], int buf) {
@@ -614,12 +608,17 @@ hipError_t grad_mfma(const PlanDev& pd, const GradJob& ja, const GradJob& jb, hi
     const int32_t tiles_a = (ja.D + tw - 1) / tw, tiles_b = jb.P ? (jb.D + tw - 1) / tw : 0;
     const dim3 grid(pd.nchunks, tiles_a + tiles_b, (nrb + NRB - 1) / NRB);
     if (grid.y > 65535u) return hipErrorInvalidValue;
-    if (NRB == 1)
-        grad_mfma_kernel<1, 8><<<grid, 256, 0, st>>>(pd, ja, jb, tiles_a);
-    else if (NRB == 2)
-        grad_mfma_kernel<2, 8><<<grid, 256, 0, st>>>(pd, ja, jb, tiles_a);
-    else
-        grad_mfma_kernel<4, 4><<<grid, 256, 0, st>>>(pd, ja, jb, tiles_a);
+    // token rows that cannot stay in the 256 MB infinity cache anyway are streamed past the caches
+    const bool stream = int64_t(pd.T) * (int64_t(ja.D) + (jb.P ? jb.D : 0)) * 2 > (int64_t(512) << 20);
+#define LOBRA_GRAD(NRB_, CW_)                                                                  \
+    do {                                                                                       \
+        if (stream) grad_mfma_kernel<NRB_, CW_, true><<<grid, 256, 0, st>>>(pd, ja, jb, tiles_a);  \
+        else grad_mfma_kernel<NRB_, CW_, false><<<grid, 256, 0, st>>>(pd, ja, jb, tiles_a);        \
+    } while (0)
+    if (NRB == 1) LOBRA_GRAD(1, 8);
+    else if (NRB == 2) LOBRA_GRAD(2, 8);
+    else LOBRA_GRAD(4, 4);
+#undef LOBRA_GRAD
     return hipGetLastError();
 }
 
