@@ -5,20 +5,26 @@
 // (paper section 2.1: X W + X (down)(up); section 1: one shared base product for the fused batch,
 // a per-task adapter product on top of it).
 //
-// Tiling: 256 x 256 x 64 per workgroup, blocks of v_mfma_f32_32x32x16_bf16 with fp32 accumulators.  The
-// MFMA "A" operand is fed from W and the "B" operand from Z, so a lane ends up with four consecutive
-// output columns of one row, which packs into 8-byte LDS writes in the epilogue.
+// Tiling: 256 x 256 x 64 per workgroup, blocks of v_mfma_f32_16x16x32_bf16 with fp32 accumulators (on this
+// chip a loop of nothing but these sustains 2.05 PFLOP/s, one of 32x32x16 blocks 1.79: the deeper K step
+// moves each accumulator half as often per flop).  The MFMA "A" operand is fed from W and the "B" operand from
+// Z, so a lane ends up with four consecutive output columns of one row, which packs into 8-byte LDS writes in
+// the epilogue.
 //
 // Two main loops behind one kernel template:
-//   DMA  (K a multiple of 64): four waves of 128 x 128 (one per SIMD, the accumulators in the 256 AGPRs).
+//   DMA  (K a multiple of 64): four waves of 128 x 128 (one per SIMD, the 64 accumulators in the 256 AGPRs).
 //        K tiles go global -> LDS with global_load_lds_dwordx4 (no registers, no ds_write) into two LDS
 //        stages; every row segment a copy fetches is one 128-byte line.  With one wave per SIMD nothing
 //        hides a wave's own latencies, so the loop is software-pipelined by hand and its order is pinned
-//        (sched_barrier): a K step is eight sections of {MFMA, copy, MFMA, fragment read}; the fragments
-//        of K step s + 1 are read during step s; the barrier of a tile stands in front of its last K step,
-//        whose fragments are already in registers, so MFMAs and not LDS latency follow the barrier; the
-//        stage it frees is refilled by copies spread over the next three K steps (one every section or
-//        two: issued back to back they block their wave for as long as the texture unit takes to accept them).
+//        (the MFMAs are volatile asm statements, sched_barrier between the slots): a K step of 32 is 16
+//        sections of four MFMAs with one other piece of work behind each MFMA (an MFMA of this shape keeps
+//        its pipe for 16 cycles, of which 12 are free for the wave to issue something else): the two
+//        instructions of a copy, the address arithmetic, a fragment read.  The fragments of K step s + 1 are
+//        read during step s (the token-side fragment of a row block straight back into its register once the
+//        block is done, the other operand into a second register set); the barrier of a tile stands in front
+//        of its last K step, whose fragments are already in registers, so MFMAs and not LDS latency follow
+//        the barrier; the stage it frees is refilled by copies spread over the next one and a half K steps
+//        (issued back to back they block their wave for as long as the texture unit takes to accept them).
 //   register-staged (any K that is a multiple of 8): eight waves of 64 x 128, global -> VGPR -> LDS with
 //        a zero-filled K tail; the compiler schedules it.
 //
@@ -53,7 +59,7 @@ namespace lobra {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 namespace {
@@ -107,6 +113,30 @@ __device__ __forceinline__ void dma16(uint32_t lds_addr, const unsigned char* gb
                  : "memory");     // m0 is a reserved register: the compiler re-loads it before each of its own uses
 }
 
+// acc += a * b with the accumulator pinned to the AGPRs and updated in place.  (With 64 accumulators of four
+// registers the register allocator otherwise rotates them through VGPRs inside the main loop.)  The order of
+// these statements is the order of the instructions.
+__device__ __forceinline__ void mfma_acc(f32x4& acc, bf16x8 a, bf16x8 b)
+{
+    asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+}
+
+// The same copy in two instructions with room for another instruction between them (which also provides the
+// wait state the M0 write needs): nothing that writes M0 may be scheduled between the two.
+__device__ __forceinline__ void dma16_set_m0(uint32_t lds_addr)
+{
+    const uint32_t la = __builtin_amdgcn_readfirstlane(lds_addr);
+    asm volatile("s_mov_b32 m0, %0" : : "s"(la) : "memory");
+}
+__device__ __forceinline__ void dma16_issue(const unsigned char* gbase, uint32_t voff)
+{
+    const uint64_t gp = reinterpret_cast<uint64_t>(gbase);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane(uint32_t(gp));
+    const uint32_t hi = __builtin_amdgcn_readfirstlane(uint32_t(gp >> 32));
+    const uint64_t gu = (uint64_t(hi) << 32) | lo;
+    asm volatile("global_load_lds_dwordx4 %0, %1" : : "v"(voff), "s"(gu) : "memory");
+}
+
 template <int N> __device__ __forceinline__ void wait_vmcnt()
 {
     asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
@@ -128,7 +158,7 @@ void gemm_mfma_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const uint16_t
     // the projection its columns lie in; M is then the compact [R_tot][pd.dg] array.
     constexpr int NT = 64 * WM * WN;                // threads
     constexpr int TM = BM / WM, TN = BN / WN;       // wave tile
-    constexpr int MB = TM / 32, NB = TN / 32;       // 32 x 32 blocks per wave
+    constexpr int MB = TM / 16, NB = TN / 16;       // 16 x 16 blocks per wave
     constexpr int ZL = 2048 / NT;                   // 16-byte chunks per thread and tile
     constexpr int ZROWS = NT / 8;                   // rows covered by one pass of the [rows][64 k] loader
     constexpr int WKROWS = NT / 32;                 // k rows covered by one pass of the [64 k][256 n] loader
@@ -138,7 +168,9 @@ void gemm_mfma_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const uint16_t
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
-    const int l32 = lane & 31, lh = lane >> 5;
+    // MFMA 16x16x32 lanes: j = row of the "B" operand (a token) and of the result, kg = group of 8 k
+    // (operands) or of 4 result columns
+    const int j = lane & 15, kg = lane >> 4;
     const int32_t T = pd.T;
 
     // ---- workgroup -> tile: consecutive ids go to different XCDs, so give each XCD a contiguous
@@ -175,13 +207,23 @@ void gemm_mfma_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const uint16_t
     auto zs = [&](int buf) { return lds + buf * ZT_BYTES; };
     auto ws = [&](int buf) { return lds + 2 * ZT_BYTES + buf * WT_BYTES; };
 
-    f32x16 acc[MB][NB];
+    // acc[mb][nb][v]: token row mb 16 + j of the wave tile, column nb 16 + 4 kg + v
+    f32x4 acc[MB][NB];
 #pragma unroll
     for (int i = 0; i < MB; ++i)
 #pragma unroll
-        for (int j = 0; j < NB; ++j)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+        for (int jj = 0; jj < NB; ++jj) acc[i][jj] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    // W operand (8 consecutive k of one column) out of a [k][n] tile with k rows `pitch` bytes apart:
+    // two transpose reads of 4 k rows x 16 columns each.  `chunk_of(krow, c)` is the tile's swizzle.
+    auto tr_pair = [&](const unsigned char* p0, int pitch) {
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p0));
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p0 + 4 * pitch));
+        union { s16x4 h[2]; bf16x8 b; } cv;
+        cv.h[0] = lo;
+        cv.h[1] = hi;
+        return cv.b;
+    };
 
     const u32x4 zero4 = {0u, 0u, 0u, 0u};
     if constexpr (DMA) {
@@ -194,27 +236,26 @@ void gemm_mfma_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const uint16_t
         // the global address each lane fetches from.
         constexpr int NW = WM * WN;
         constexpr int NBZ = (DBK / 2) / NW;         // 1 KiB blocks per wave, for Z and for W each
-        constexpr int NU = MB + NB;                 // fragments per K step = sections per K step
-        constexpr int KS = DBK / 16;                // K steps per tile
-        static_assert(NW == 4 && MB * NB == 2 * NU && 2 * NBZ == 2 * NU && KS == 4,
-                      "four waves of 128 x 128: two MFMAs and at most one copy per section");
+        constexpr int NU = MB + NB;                 // fragments per K step of 32 = sections per K step
+        static_assert(NW == 4 && MB * NB == 4 * NU && 2 * NBZ == NU && DBK == 64,
+                      "four waves of 128 x 128: four MFMAs and at most one copy per section");
         const int wave_u = __builtin_amdgcn_readfirstlane(wave);
         const uint32_t lds0 = uint32_t(uintptr_t((__attribute__((address_space(3))) unsigned char*)lds));
         auto fz = [](int row) { return (row >> 1) & 7; };
         uint32_t zvo[NBZ], wvo[NBZ];                // per-lane source offsets of this wave's copies
 #pragma unroll
-        for (int j = 0; j < NBZ; ++j) {
-            const int blk = wave + NW * j;
+        for (int c = 0; c < NBZ; ++c) {
+            const int blk = wave + NW * c;
             {
                 const int row = 8 * blk + lane / 8;
-                const int c = (lane % 8) ^ fz(row);
-                zvo[j] = (uint32_t(min(row, T - 1 - row0)) * uint32_t(K) + 8u * c) * 2u;
-                if (!W_KN) wvo[j] = (uint32_t(min(row, N - 1 - col0)) * uint32_t(ldw) + 8u * c) * 2u;
+                const int ch = (lane % 8) ^ fz(row);
+                zvo[c] = (uint32_t(min(row, T - 1 - row0)) * uint32_t(K) + 8u * ch) * 2u;
+                if (!W_KN) wvo[c] = (uint32_t(min(row, N - 1 - col0)) * uint32_t(ldw) + 8u * ch) * 2u;
             }
             if (W_KN) {
                 const int krow = 2 * blk + (lane >> 5);
-                const int c = (lane & 31) ^ ((krow & 3) << 2);
-                wvo[j] = (uint32_t(krow) * uint32_t(ldw) + uint32_t(min(8 * c, N - 8 - col0))) * 2u;
+                const int ch = (lane & 31) ^ ((krow & 3) << 2);
+                wvo[c] = (uint32_t(krow) * uint32_t(ldw) + uint32_t(min(8 * ch, N - 8 - col0))) * 2u;
             }
         }
         const unsigned char* zbase = reinterpret_cast<const unsigned char*>(Z + size_t(row0) * K);
@@ -227,67 +268,72 @@ void gemm_mfma_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const uint16_t
             if (c < NBZ) dma16(stage_addr + (wave_u + NW * c) * 1024, zb, zvo[c]);
             else dma16(stage_addr + DZT_BYTES + (wave_u + NW * (c - NBZ)) * 1024, wb, wvo[c - NBZ]);
         };
-        // operand fragment u of K step ks of a stage: u < MB is zf[u], MB + nb is wf[nb]
-        auto read_unit = [&](int stage, int ks, int u, bf16x8 (&zf)[MB], bf16x8 (&wf)[NB]) {
-            const unsigned char* zs = lds + stage * DSTAGE_BYTES;
-            const unsigned char* ws = zs + DZT_BYTES;
-            if (u < MB) {
-                const int row = wm * TM + u * 32 + l32;
-                zf[u] = *reinterpret_cast<const bf16x8*>(zs + row * (DBK * 2) + ((2 * ks + lh) ^ fz(row)) * 16);
-            } else if (W_KN) {
-                const int nb = u - MB;
-                const int s = lane & 15, g = lane >> 4;
-                const int krow = 16 * ks + 8 * (g >> 1) + (s >> 2);
-                const int n = wn * TN + nb * 32 + 16 * (g & 1) + 4 * (s & 3);
-                const int c = (n >> 3) ^ ((krow & 3) << 2);
-                const unsigned char* p0 = ws + krow * 512 + c * 16 + (n & 7) * 2;
-                const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p0));
-                const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p0 + 4 * 512));
-                union { s16x4 h[2]; bf16x8 b; } cv;
-                cv.h[0] = lo;
-                cv.h[1] = hi;
-                wf[nb] = cv.b;
+        // Operand fragments of K step ks (32 k) of a stage.  Block mb of a [rows][64 k] tile lies 16 rows =
+        // 2048 bytes behind block 0 and (row >> 1) & 7 does not depend on mb, so one per-lane address per
+        // step serves all blocks through the instruction's offset field.
+        const int fzj = (j >> 1) & 7;
+        auto zaddr = [&](int stage, int ks) {
+            return lds + stage * DSTAGE_BYTES + (wm * TM + j) * (DBK * 2) + ((4 * ks + kg) ^ fzj) * 16;
+        };
+        auto waddr = [&](int stage, int ks) {       // backward layout only
+            return lds + stage * DSTAGE_BYTES + DZT_BYTES + (wn * TN + j) * (DBK * 2) + ((4 * ks + kg) ^ fzj) * 16;
+        };
+        auto read_z = [&](const unsigned char* za, int mb, bf16x8 (&zf)[MB]) {
+            zf[mb] = *reinterpret_cast<const bf16x8*>(za + mb * 16 * (DBK * 2));
+        };
+        auto read_w = [&](const unsigned char* wa, int stage, int ks, int nb, bf16x8 (&wf)[NB]) {
+            if (W_KN) {
+                const unsigned char* wst = lds + stage * DSTAGE_BYTES + DZT_BYTES;
+                const int krow = 32 * ks + 8 * kg + (j >> 2);
+                const int n = wn * TN + nb * 16 + 4 * (j & 3);
+                const int ch = (n >> 3) ^ ((krow & 3) << 2);
+                wf[nb] = tr_pair(wst + krow * 512 + ch * 16 + (n & 7) * 2, 512);
             } else {
-                const int nb = u - MB;
-                const int row = wn * TN + nb * 32 + l32;
-                wf[nb] = *reinterpret_cast<const bf16x8*>(ws + row * (DBK * 2) + ((2 * ks + lh) ^ fz(row)) * 16);
+                wf[nb] = *reinterpret_cast<const bf16x8*>(wa + nb * 16 * (DBK * 2));
             }
         };
-        // One K step: the 16 MFMAs on fragments (zc, wc) in eight sections, each {MFMA, copy, MFMA, read}:
-        // what is not an MFMA is issued while one runs.  The reads fetch the fragments (zn, wn_) of K step rks
-        // of stage rstage, one per section, or (early) two per section in the first half, so that the last
-        // one has arrived when the step ends.  Copies: those sections whose bit is set in `mask` issue the
-        // next copy of the tile at (zb, wb) into the stage at cst, counting from copy c0.
-        auto kstep = [&](int rstage, int rks, bf16x8 (&zc)[MB], bf16x8 (&wc)[NB], bf16x8 (&zn)[MB], bf16x8 (&wn_)[NB],
-                         int mask, int c0, uint32_t cst, const unsigned char* zb, const unsigned char* wb, bool early) {
+        // One K step of 32: the MB NB = 64 MFMAs in NU = 16 sections, each {2 MFMAs, copy, 2 MFMAs, fragment
+        // read}: what is not an MFMA is issued while one runs.  Token-row block mb is done in sections 2 mb and
+        // 2 mb + 1, after which its fragment zf[mb] is dead and is re-read at once for K step rks of stage
+        // rstage (the step that follows); the other operand lives through the whole step, so its next
+        // fragments go to a second register set (wn_), one in every even section.  Copies: the sections whose
+        // bit is set in `mask` issue the next copy of the tile at (zb, wb) into the stage at cst, from copy c0 on.
+        auto kstep = [&](int rstage, int rks, bf16x8 (&zf)[MB], bf16x8 (&wc)[NB], bf16x8 (&wn_)[NB],
+                         int mask, int c0, uint32_t cst, const unsigned char* zb, const unsigned char* wb) {
             int c = c0;
+            const unsigned char* za = zaddr(rstage, rks);
+            const unsigned char* wa = waddr(rstage, rks);
 #pragma unroll
             for (int u = 0; u < NU; ++u) {
-                {
-                    const int m = 2 * u, mb = m / NB, nb = m % NB;
-                    acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wc[nb], zc[mb], acc[mb][nb], 0, 0, 0);
+                const int mb = u / 2, nb0 = (NB / 2) * (u % 2);
+                const bool cp = (mask >> u) & 1;
+                // an MFMA of this shape keeps its pipe for 16 cycles, 12 of which are free to issue something
+                // else: the copy goes out in two parts, each behind an MFMA
+                mfma_acc(acc[mb][nb0], wc[nb0], zf[mb]);
+                if (cp) dma16_set_m0(c < NBZ ? cst + (wave_u + NW * c) * 1024 : cst + DZT_BYTES + (wave_u + NW * (c - NBZ)) * 1024);
+                __builtin_amdgcn_sched_barrier(0);
+                mfma_acc(acc[mb][nb0 + 1], wc[nb0 + 1], zf[mb]);
+                if (cp) {
+                    if (c < NBZ) dma16_issue(zb, zvo[c]); else dma16_issue(wb, wvo[c - NBZ]);
+                    ++c;
                 }
                 __builtin_amdgcn_sched_barrier(0);
-                if ((mask >> u) & 1) copy(cst, zb, wb, c++);
-                if (early && 2 * u < NU) read_unit(rstage, rks, 2 * u, zn, wn_);
+                mfma_acc(acc[mb][nb0 + 2], wc[nb0 + 2], zf[mb]);
                 __builtin_amdgcn_sched_barrier(0);
-                {
-                    const int m = 2 * u + 1, mb = m / NB, nb = m % NB;
-                    acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wc[nb], zc[mb], acc[mb][nb], 0, 0, 0);
-                }
-                __builtin_amdgcn_sched_barrier(0);
-                if (!early) read_unit(rstage, rks, u, zn, wn_);
-                else if (2 * u + 1 < NU) read_unit(rstage, rks, 2 * u + 1, zn, wn_);
+                mfma_acc(acc[mb][nb0 + 3], wc[nb0 + 3], zf[mb]);
+                if (u % 2 == 0) read_w(wa, rstage, rks, u / 2, wn_);
+                else read_z(za, mb, zf);
                 __builtin_amdgcn_sched_barrier(0);
             }
         };
-        // the 2 NBZ = 16 copies of a tile go out after the barrier that freed their stage: 6 in the K step
-        // behind it, 5 in each of the next two; the K step in front of the next barrier issues none
-        constexpr int M3 = 0xDB, M0 = 0xB5, M1 = 0xB5;
-        constexpr int C0 = __builtin_popcount(M3), C1 = C0 + __builtin_popcount(M0);
-        static_assert(C1 + __builtin_popcount(M1) == 2 * NBZ, "every copy once");
+        static_assert(NB == 8 && MB == 8, "two sections of four MFMAs per token-row block");
+        // the 2 NBZ = 16 copies of a tile go out after the barrier that freed their stage: ten in the K step
+        // behind it, six in the first half of the next one; the half step in front of the barrier issues none
+        constexpr int MD = 0x5B6D, MA = 0x00DB;
+        constexpr int CD = __builtin_popcount(MD);
+        static_assert(CD + __builtin_popcount(MA) == 2 * NBZ, "every copy once");
 
-        bf16x8 zf[2][MB], wf[2][NB];
+        bf16x8 zf[MB], wf[2][NB];
 #pragma unroll
         for (int c = 0; c < 2 * NBZ; ++c) copy(lds0, zsrc(0), wsrc(0), c);
         if (KT > 1) {
@@ -299,7 +345,9 @@ void gemm_mfma_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const uint16_t
         }
         __builtin_amdgcn_s_barrier();
 #pragma unroll
-        for (int u = 0; u < NU; ++u) read_unit(0, 0, u, zf[0], wf[0]);
+        for (int u = 0; u < MB; ++u) read_z(zaddr(0, 0), u, zf);
+#pragma unroll
+        for (int u = 0; u < NB; ++u) read_w(waddr(0, 0), 0, 0, u, wf[0]);
         for (int32_t kt = 0; kt < KT; ++kt) {
             const int stg = kt & 1;
             // Tile kt + 1 goes into the other stage (its first copies went out behind the previous barrier),
@@ -307,14 +355,12 @@ void gemm_mfma_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const uint16_t
             // copied once more into a stage nobody reads any more, which keeps the loop free of branches.
             const int32_t k1 = min(kt + 1, KT - 1), k2 = min(kt + 2, KT - 1);
             const uint32_t st1 = lds0 + uint32_t(stg ^ 1) * DSTAGE_BYTES, st2 = lds0 + uint32_t(stg) * DSTAGE_BYTES;
-            kstep(stg, 1, zf[0], wf[0], zf[1], wf[1], M0, C0, st1, zsrc(k1), wsrc(k1), false);
-            kstep(stg, 2, zf[1], wf[1], zf[0], wf[0], M1, C1, st1, zsrc(k1), wsrc(k1), false);
-            kstep(stg, 3, zf[0], wf[0], zf[1], wf[1], 0, 0, st1, zsrc(k1), wsrc(k1), true);
+            kstep(stg, 1, zf, wf[0], wf[1], MA, CD, st1, zsrc(k1), wsrc(k1));
             // every wave has read the last fragments of this stage and its copies of tile kt + 1 have landed
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
             wait_vmcnt<0>();
             __builtin_amdgcn_s_barrier();
-            kstep(stg ^ 1, 0, zf[1], wf[1], zf[0], wf[0], M3, 0, st2, zsrc(k2), wsrc(k2), false);
+            kstep(stg ^ 1, 0, zf, wf[1], wf[0], MD, 0, st2, zsrc(k2), wsrc(k2));
         }
         wait_vmcnt<0>();
         __syncthreads();
@@ -373,44 +419,32 @@ void gemm_mfma_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const uint16_t
                 }
             }
         };
-        // one K tile: 4 K steps of 16, each MB + NB operand fragments and MB * NB MFMAs
+        // one K tile: 2 K steps of 32, each MB + NB operand fragments and MB * NB MFMAs
         auto compute = [&](int buf) {
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks) {
+            for (int ks = 0; ks < 2; ++ks) {
                 bf16x8 zf[MB], wf[NB];
 #pragma unroll
                 for (int mb = 0; mb < MB; ++mb) {
-                    const int row = wm * TM + mb * 32 + l32;
-                    zf[mb] = *reinterpret_cast<const bf16x8*>(zs(buf) + row * (BK * 2) + swz(row, 2 * ks + lh) * 16);
+                    const int row = wm * TM + mb * 16 + j;
+                    zf[mb] = *reinterpret_cast<const bf16x8*>(zs(buf) + row * (BK * 2) + swz(row, 4 * ks + kg) * 16);
                 }
-                if (W_KN) {
-                    const int s = lane & 15, g = lane >> 4;
-                    const int krow = 16 * ks + 8 * (g >> 1) + (s >> 2);
 #pragma unroll
-                    for (int nb = 0; nb < NB; ++nb) {
-                        const int n = wn * TN + nb * 32 + 16 * (g & 1) + 4 * (s & 3);
-                        const unsigned char* p0 = ws(buf) + krow * (WKN_PITCH * 2) + n * 2;
-                        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                            (s16x4 __attribute__((address_space(3)))*)(p0));
-                        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                            (s16x4 __attribute__((address_space(3)))*)(p0 + 4 * (WKN_PITCH * 2)));
-                        union { s16x4 h[2]; bf16x8 b; } c;
-                        c.h[0] = lo;
-                        c.h[1] = hi;
-                        wf[nb] = c.b;
-                    }
-                } else {
-#pragma unroll
-                    for (int nb = 0; nb < NB; ++nb) {
-                        const int row = wn * TN + nb * 32 + l32;
-                        wf[nb] = *reinterpret_cast<const bf16x8*>(ws(buf) + row * (BK * 2) + swz(row, 2 * ks + lh) * 16);
+                for (int nb = 0; nb < NB; ++nb) {
+                    if (W_KN) {
+                        const int krow = 32 * ks + 8 * kg + (j >> 2);
+                        const int n = wn * TN + nb * 16 + 4 * (j & 3);
+                        wf[nb] = tr_pair(ws(buf) + krow * (WKN_PITCH * 2) + n * 2, WKN_PITCH * 2);
+                    } else {
+                        const int row = wn * TN + nb * 16 + j;
+                        wf[nb] = *reinterpret_cast<const bf16x8*>(ws(buf) + row * (BK * 2) + swz(row, 4 * ks + kg) * 16);
                     }
                 }
 #pragma unroll
                 for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
                     for (int nb = 0; nb < NB; ++nb)
-                        acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[nb], zf[mb], acc[mb][nb], 0, 0, 0);
+                        acc[mb][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[nb], zf[mb], acc[mb][nb], 0, 0, 0);
             }
         };
 
@@ -430,13 +464,13 @@ void gemm_mfma_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const uint16_t
         }
     }
 
-    // ---- fused up projection: for every adapter segment that crosses this tile, ceil(r_t / 16) extra
+    // ---- fused up projection: for every adapter segment that crosses this tile, ceil(r_t / 32) extra
     //      K steps acc += M_t^T[:, cols] * P[rows, :]^T with the rows outside the segment masked to zero.
     //      The M_t slice [r_t][256 cols] is staged in LDS (free now) in the [k][n] layout of the forward W
-    //      tile and gathered with the transpose read; P comes straight from global memory, 16 bytes per lane.
+    //      tile (rank rows up to the next multiple of 32 zero) and gathered with the transpose read; P comes
+    //      straight from global memory, 16 bytes per lane.
     //      The segment loop and its barriers are uniform over the workgroup.
     {
-        constexpr int NT2 = 64 * WM * WN;
         const int32_t row_end = min(row0 + BM, T);
         const int32_t wrow0 = row0 + wm * TM;       // the wave's rows are wrow0 .. wrow0 + TM - 1
         for (int32_t sg = sg_first; sg < pd.nseg; ++sg) {
@@ -449,34 +483,30 @@ void gemm_mfma_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const uint16_t
             const int32_t lo = max(seg_lo, row0), hi = min(seg_hi, row_end);
             const int32_t r = cached ? sf_r1 - sf_r0 : (pd.rank_off[t + 1] - pd.rank_off[t]) / nproj;
             const int32_t r0 = cached ? sf_r0 : pd.rank_off[t] + pj * r;
-            const int32_t rp = (r + 15) & ~15;
+            const int32_t rp = (r + 31) & ~31;
             const bool mine = hi > wrow0 && lo < wrow0 + TM;   // wave-uniform: the segment crosses this wave's rows
-            // P fragments of up to two rank steps are fetched before the adapter slice is staged, so
-            // that their latency overlaps the staging and its barriers
-            constexpr int KG = 2;
-            u32x4 pv[KG][MB];
-            auto load_p = [&](int32_t kk0) {
+            // the P fragments of a rank step: lane (j, kg) holds the ranks kk + 8 kg .. + 7 of token row j of
+            // each 16-row block; groups that start beyond r_t hold padding, or another projection's ranks,
+            // and are not read.  The first step is fetched before the adapter slice is staged, so that its
+            // latency overlaps the staging and its barriers
+            u32x4 pv[MB];
+            auto load_p = [&](int32_t kk) {
 #pragma unroll
-                for (int q = 0; q < KG; ++q)
-#pragma unroll
-                    for (int mb = 0; mb < MB; ++mb) {
-                        const int32_t row = wrow0 + mb * 32 + l32;
-                        const int32_t kk = kk0 + 16 * q;
-                        // (a lane's 8 ranks start at kk + 8 lh: groups that start beyond r_t hold padding,
-                        //  or another projection's ranks, and are not read)
-                        pv[q][mb] = (mine && kk + 8 * lh < r && row >= lo && row < hi)
-                            ? *reinterpret_cast<const u32x4*>(P + size_t(row) * pd.r_pad + pj * r + kk + 8 * lh) : zero4;
-                    }
+                for (int mb = 0; mb < MB; ++mb) {
+                    const int32_t row = wrow0 + mb * 16 + j;
+                    pv[mb] = (mine && kk + 8 * kg < r && row >= lo && row < hi)
+                                 ? *reinterpret_cast<const u32x4*>(P + size_t(row) * pd.r_pad + pj * r + kk + 8 * kg) : zero4;
+                }
             };
             load_p(0);
-            // the adapter slice is rp * 32 chunks of 16 bytes; the first MCH * NT2 of them (ranks up to
-            // 64 with 512 threads) are fetched before the barrier that frees the LDS and written after it
+            // the adapter slice is rp * 32 chunks of 16 bytes; the first MCH * NT of them are fetched before
+            // the barrier that frees the LDS and written after it
             constexpr int MCH = 4;
             u32x4 mreg[MCH];
             auto fetch_m = [&](int32_t base) {
 #pragma unroll
                 for (int q = 0; q < MCH; ++q) {
-                    const int32_t ch = base + tid + q * NT2, kr = ch >> 5, n = col0 + 8 * (ch & 31);
+                    const int32_t ch = base + tid + q * NT, kr = ch >> 5, n = col0 + 8 * (ch & 31);
                     mreg[q] = (ch < rp * 32 && kr < r && n < N)
                                   ? *reinterpret_cast<const u32x4*>(M + size_t(r0 + kr) * mpitch + (n - mcol0)) : zero4;
                 }
@@ -484,51 +514,37 @@ void gemm_mfma_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const uint16_t
             auto store_m = [&](int32_t base) {
 #pragma unroll
                 for (int q = 0; q < MCH; ++q) {
-                    const int32_t ch = base + tid + q * NT2, kr = ch >> 5, c = ch & 31;
+                    const int32_t ch = base + tid + q * NT, kr = ch >> 5, c = ch & 31;
                     if (ch < rp * 32) *reinterpret_cast<u32x4*>(lds + kr * 512 + ((c ^ ((kr & 3) << 2)) << 4)) = mreg[q];
                 }
             };
             fetch_m(0);
             __syncthreads();                        // everybody is done with what the LDS held before
             store_m(0);
-            for (int32_t base = MCH * NT2; base < rp * 32; base += MCH * NT2) {
+            for (int32_t base = MCH * NT; base < rp * 32; base += MCH * NT) {
                 fetch_m(base);
                 store_m(base);
             }
             __syncthreads();
             if (!mine) continue;                    // wave-uniform; the barriers are above
-            const int s16 = lane & 15, g16 = lane >> 4;
-            for (int32_t kk0 = 0; kk0 < rp; kk0 += 16 * KG) {
-                if (kk0 > 0) load_p(kk0);
+            for (int32_t kk = 0; kk < rp; kk += 32) {
+                if (kk > 0) load_p(kk);
+                bf16x8 wf[NB];
+                const int krow = kk + 8 * kg + (j >> 2);
 #pragma unroll
-                for (int q = 0; q < KG; ++q) {
-                    const int32_t kk = kk0 + 16 * q;
-                    if (kk >= rp) break;            // wave-uniform
-                    bf16x8 wf[NB];
-                    const int krow = kk + 8 * (g16 >> 1) + (s16 >> 2);
+                for (int nb = 0; nb < NB; ++nb) {
+                    const int n = wn * TN + nb * 16 + 4 * (j & 3);
+                    const int c = (n >> 3) ^ ((krow & 3) << 2);
+                    wf[nb] = tr_pair(lds + krow * 512 + c * 16 + (n & 7) * 2, 512);
+                }
 #pragma unroll
-                    for (int nb = 0; nb < NB; ++nb) {
-                        const int n = wn * TN + nb * 32 + 16 * (g16 & 1) + 4 * (s16 & 3);
-                        const int c = (n >> 3) ^ ((krow & 3) << 2);
-                        const unsigned char* p0 = lds + krow * 512 + c * 16 + (n & 7) * 2;
-                        const s16x4 vlo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                            (s16x4 __attribute__((address_space(3)))*)(p0));
-                        const s16x4 vhi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                            (s16x4 __attribute__((address_space(3)))*)(p0 + 4 * 512));
-                        union { s16x4 h[2]; bf16x8 b; } cv;
-                        cv.h[0] = vlo;
-                        cv.h[1] = vhi;
-                        wf[nb] = cv.b;
-                    }
+                for (int mb = 0; mb < MB; ++mb) {
+                    const int32_t rb = wrow0 + mb * 16;
+                    if (hi <= rb || lo >= rb + 16) continue;        // wave-uniform
+                    const bf16x8 pf = as_bf16x8(pv[mb]);
 #pragma unroll
-                    for (int mb = 0; mb < MB; ++mb) {
-                        const int32_t rb = wrow0 + mb * 32;
-                        if (hi <= rb || lo >= rb + 32) continue;        // wave-uniform
-                        const bf16x8 pf = as_bf16x8(pv[q][mb]);
-#pragma unroll
-                        for (int nb = 0; nb < NB; ++nb)
-                            acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[nb], pf, acc[mb][nb], 0, 0, 0);
-                    }
+                    for (int nb = 0; nb < NB; ++nb)
+                        acc[mb][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[nb], pf, acc[mb][nb], 0, 0, 0);
                 }
             }
         }
@@ -541,15 +557,13 @@ void gemm_mfma_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const uint16_t
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb)
+            for (int nb = 0; nb < NB; ++nb) {
+                bf16x4 o;
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    bf16x4 o;
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) o[q] = (__bf16)acc[mb][nb][4 * g + q];
-                    const int m = mb * 32 + l32, n = nb * 32 + 8 * g + 4 * lh;
-                    *reinterpret_cast<bf16x4*>(cs + (m * CS_PITCH + n) * 2) = o;
-                }
+                for (int q = 0; q < 4; ++q) o[q] = (__bf16)acc[mb][nb][q];
+                const int m = mb * 16 + j, n = nb * 16 + 4 * kg;
+                *reinterpret_cast<bf16x4*>(cs + (m * CS_PITCH + n) * 2) = o;
+            }
         __syncthreads();
         constexpr int CPR = TN / 8;                  // 16-byte chunks per row of the wave tile
         constexpr int RPI = 64 / CPR;                // rows per store instruction
