@@ -327,9 +327,10 @@ void gemm_mfma_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const uint16_t
             }
         };
         static_assert(NB == 8 && MB == 8, "two sections of four MFMAs per token-row block");
-        // the 2 NBZ = 16 copies of a tile go out after the barrier that freed their stage: ten in the K step
-        // behind it, six in the first half of the next one; the half step in front of the barrier issues none
-        constexpr int MD = 0x5B6D, MA = 0x00DB;
+        // the 2 NBZ = 16 copies of a tile go out in the K step behind the barrier that freed their stage, one
+        // per section (measured against 14 + 2, 11 + 5, 10 + 6, 8 + 8 over this and the next step: the
+        // earlier the better, by 1-4 %)
+        constexpr int MD = 0xFFFF, MA = 0;
         constexpr int CD = __builtin_popcount(MD);
         static_assert(CD + __builtin_popcount(MA) == 2 * NBZ, "every copy once");
 
