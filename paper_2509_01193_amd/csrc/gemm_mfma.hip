@@ -31,9 +31,9 @@
 // LDS layouts (DMA path; the register-staged path pads the forward W tile instead of swizzling it)
 //   Z tile, and the W tile when K is fastest (backward): [256 rows][64 k], 16-byte chunk c of a row
 //       stored at c ^ ((row >> 1) & 7): the 16 rows of one ds_read_b128 pass hit 16 bank groups.
-//   W tile when N is fastest (forward): [64 k][256 n], chunk c of k-row k stored at c ^ ((k & 3) << 2);
+//   W tile when N is fastest (forward): [64 k][256 n], chunk c of k-row k stored at c ^ kn_swz(k);
 //       the MFMA operand (8 consecutive k of one column) is gathered with two ds_read_b64_tr_b16 and
-//       the 4 k-rows of one such read sit in different bank quarters.
+//       the k-rows that one such read touches sit in different bank groups.
 //   A wave-wide direct-to-LDS copy lands in lane order, so the swizzle is applied to the global
 //       address each lane fetches from.
 //   C staging in the epilogue: per wave [rows][cols + 8] bf16, written back with non-temporal stores.
@@ -83,6 +83,11 @@ template <bool W_KN, int WN, bool DMA> constexpr int lds_bytes()
 }
 
 __device__ __forceinline__ int swz(int row, int chunk) { return chunk ^ ((row >> 1) & 7); }
+
+// Swizzle of a [k][256 n] tile (512 bytes per k row): 16-byte chunk c of row k is stored at c ^ kn_swz(k).
+// One transpose read of a 16-lane group takes 32 bytes from each of the k rows k0 .. k0 + 3, and the groups
+// of a wave sit 8 rows apart: bits 0-1 of k pick the 64-byte quarter, bit 3 the 32-byte half of it.
+__device__ __forceinline__ int kn_swz(int k) { return ((k & 3) << 2) | (((k >> 3) & 1) << 1); }
 
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v)
 {
@@ -230,8 +235,8 @@ void gemm_mfma_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const uint16_t
         // ---- direct-to-LDS pipeline, four waves of 128 x 128
         // Stage layout: Z [256 rows][64 k] (128 bytes per row, 16-byte chunk c stored at c ^ f(row)), then W
         // either [256 n][64 k] in the same layout (backward) or [64 k][256 n] (forward, 512 bytes per k row,
-        // 16-byte chunk c stored at c ^ ((k & 3) << 2) so that the 4 k rows of one transpose read sit in
-        // different bank quarters).  f(row) = (row >> 1) & 7 spreads the 16 rows of one ds_read_b128 pass
+        // 16-byte chunk c stored at c ^ kn_swz(k) so that the k rows one transpose read touches sit in
+        // different bank groups).  f(row) = (row >> 1) & 7 spreads the 16 rows of one ds_read_b128 pass
         // over all banks.  A wave-wide copy fills 1 KiB of LDS in lane order, so the swizzle is applied to
         // the global address each lane fetches from.
         constexpr int NW = WM * WN;
@@ -254,7 +259,7 @@ void gemm_mfma_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const uint16_t
             }
             if (W_KN) {
                 const int krow = 2 * blk + (lane >> 5);
-                const int ch = (lane & 31) ^ ((krow & 3) << 2);
+                const int ch = (lane & 31) ^ kn_swz(krow);
                 wvo[c] = (uint32_t(krow) * uint32_t(ldw) + uint32_t(min(8 * ch, N - 8 - col0))) * 2u;
             }
         }
@@ -286,7 +291,7 @@ void gemm_mfma_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const uint16_t
                 const unsigned char* wst = lds + stage * DSTAGE_BYTES + DZT_BYTES;
                 const int krow = 32 * ks + 8 * kg + (j >> 2);
                 const int n = wn * TN + nb * 16 + 4 * (j & 3);
-                const int ch = (n >> 3) ^ ((krow & 3) << 2);
+                const int ch = (n >> 3) ^ kn_swz(krow);
                 wf[nb] = tr_pair(wst + krow * 512 + ch * 16 + (n & 7) * 2, 512);
             } else {
                 wf[nb] = *reinterpret_cast<const bf16x8*>(wa + nb * 16 * (DBK * 2));
@@ -516,7 +521,7 @@ void gemm_mfma_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const uint16_t
 #pragma unroll
                 for (int q = 0; q < MCH; ++q) {
                     const int32_t ch = base + tid + q * NT, kr = ch >> 5, c = ch & 31;
-                    if (ch < rp * 32) *reinterpret_cast<u32x4*>(lds + kr * 512 + ((c ^ ((kr & 3) << 2)) << 4)) = mreg[q];
+                    if (ch < rp * 32) *reinterpret_cast<u32x4*>(lds + kr * 512 + ((c ^ kn_swz(kr)) << 4)) = mreg[q];
                 }
             };
             fetch_m(0);
@@ -535,7 +540,7 @@ void gemm_mfma_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const uint16_t
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb) {
                     const int n = wn * TN + nb * 16 + 4 * (j & 3);
-                    const int c = (n >> 3) ^ ((krow & 3) << 2);
+                    const int c = (n >> 3) ^ kn_swz(krow);
                     wf[nb] = tr_pair(lds + krow * 512 + c * 16 + (n & 7) * 2, 512);
                 }
 #pragma unroll
