@@ -21,9 +21,9 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_FP32_TFLOPS = 157.3      # MI355X fp32 vector
 PEAK_HBM_GBS = 8000.0
-# measured on this chip with random bf16 operands and nothing but back-to-back 32x32x16 MFMAs: the
-# matrix cores sustain this much before the power limit pulls the clock down (context for `frac`)
-MFMA_ONLY_SUSTAINED_TFLOPS = 1840.0
+# measured on this chip with random bf16 operands and nothing but back-to-back 16x16x32 MFMAs (the shape
+# the GEMM uses; 32x32x16 blocks: 1790): what the matrix cores sustain under the power limit (context for `frac`)
+MFMA_ONLY_SUSTAINED_TFLOPS = 2050.0
 
 
 def cpu_baseline(p, budget_rows):
