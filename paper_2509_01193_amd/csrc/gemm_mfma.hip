@@ -369,6 +369,9 @@ void gemm_mfma_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const uint16_t
             kstep(stg ^ 1, 0, zf, wf[1], wf[0], MD, 0, st2, zsrc(k2), wsrc(k2));
         }
         wait_vmcnt<0>();
+        // the loop's MFMAs are asm statements, so the compiler does not know that the accumulators come out of
+        // the matrix pipeline: keep its first read of them the documented number of wait states away
+        asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
         __syncthreads();
     } else {
         u32x4 zreg[ZL], wreg[ZL];
