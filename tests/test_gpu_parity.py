@@ -126,7 +126,8 @@ def test_long_batch_at_medium_and_large_rank_takes_the_lds_staged_kernels(rank):
     check_problem(p, label="rank %d" % rank)
 
 
-@pytest.mark.parametrize("dims", [(8, 8), (16, 24), (64, 64), (72, 8), (8, 1032), (1024, 64), (2048, 256)])
+@pytest.mark.parametrize("dims", [(8, 8), (16, 24), (64, 64), (72, 8), (8, 1032), (1024, 64), (2048, 256),
+                                  (128, 192), (192, 320), (320, 128)])   # 2, 3 and 5 K tiles of the direct-to-LDS loop
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_extreme_layer_widths(dims, dtype):
     """Smallest legal widths, one K tile, K tails of 8, a single column chunk, long K."""
