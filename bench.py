@@ -105,6 +105,10 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true",
                     help="time eager launches instead of replays of a HIP graph of one step")
+    ap.add_argument("--vendor-gemm", action="store_true",
+                    help="context only (the library never calls it): time torch.matmul on the two base products "
+                         "of the workload, x @ W and dy @ W^T, next to this library's base-only step; prints its "
+                         "own JSON line and exits")
     ap.add_argument("--pmc-probe", action="store_true",
                     help="for rocprofv3 --pmc runs: 2 steps and one plain device copy of x (a kernel of "
                          "known traffic that calibrates FETCH_SIZE / WRITE_SIZE), then exit")
@@ -178,6 +182,35 @@ def main():
                           "ms_per_step_separate_calls": ms_sep, "ms_dx_sum_after_separate_calls": ms_sum,
                           "tokens_per_s_fused": p.T / (ms_fused * 1e-3),
                           "speedup_vs_separate_plus_sum": (ms_sep + ms_sum) / ms_fused}))
+        return
+
+    if a.vendor_gemm:
+        if p.dtype != "bf16":
+            sys.exit("--vendor-gemm: bf16 workloads only")
+        base = dp.base_only()
+        x, W, dy = base.x, base.W, base.dy
+        y, dx = torch.empty_like(dy), torch.empty_like(x)
+
+        def t_of(fn):
+            for _ in range(a.warmup):
+                fn()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(a.steps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / a.steps
+        ms_fwd = t_of(lambda: torch.matmul(x, W, out=y))
+        ms_bwd = t_of(lambda: torch.matmul(dy, W.t(), out=dx))
+        ms_own = t_of(base.step)
+        fl = 2.0 * p.T * p.d_in * p.d_out
+        print(json.dumps({"vendor_gemm_context": True, "workload": p.name, "T": p.T, "d_in": p.d_in, "d_out": p.d_out,
+                          "torch_matmul_x_W_ms": ms_fwd, "torch_matmul_x_W_tflops": fl / ms_fwd / 1e9,
+                          "torch_matmul_dy_Wt_ms": ms_bwd, "torch_matmul_dy_Wt_tflops": fl / ms_bwd / 1e9,
+                          "this_library_base_only_step_ms": ms_own,
+                          "this_library_base_only_tflops": 2 * fl / ms_own / 1e9}))
         return
 
     if a.pmc_probe:

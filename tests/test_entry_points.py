@@ -93,6 +93,17 @@ def test_bench_padded_layout_counts_real_tokens_only():
 
 
 @pytest.mark.gpu
+def test_bench_vendor_gemm_context_line():
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--steps", "2", "--warmup", "1", "--vendor-gemm"],
+                       capture_output=True, text=True, timeout=600)
+    assert r.returncode == 0, r.stdout[-2000:] + r.stderr[-2000:]
+    d = json.loads([l for l in r.stdout.splitlines() if l.startswith("{")][0])
+    assert d["vendor_gemm_context"] and d["T"] == 16384
+    for k in ("torch_matmul_x_W_tflops", "torch_matmul_dy_Wt_tflops", "this_library_base_only_tflops"):
+        assert 100.0 < d[k] < 2500.0, (k, d[k])
+
+
+@pytest.mark.gpu
 def test_smoke_entry_point():
     sys.path.insert(0, ROOT)
     import __graft_entry__ as ge
