@@ -125,7 +125,7 @@ hipError_t plain_shrink(const PlanDev& pd, int dtype, const void* Z, const void*
 }
 
 // -------------------------------------------------------------------------------------------
-// gemm: 64 x 64 tile, K step 16, 4 x 4 outputs per thread, adapter term added per element
+// gemm: 64 x 64 tile, K step 16, 4 x 4 outputs per thread, the adapter term as further K steps per segment
 // -------------------------------------------------------------------------------------------
 template <typename E, bool TRANSW>
 __global__ __launch_bounds__(256) void plain_gemm_kernel(PlanDev pd, const E* __restrict__ Z,
@@ -194,22 +194,54 @@ __global__ __launch_bounds__(256) void plain_gemm_kernel(PlanDev pd, const E* __
         }
         __syncthreads();
     }
+    // adapter term: for every adapter segment that crosses the tile, the task's ranks are further K steps of
+    // the same tile product, acc += P[rows, ranks] M_t[ranks, cols], with the rows outside the segment masked
+    // (the loops are uniform over the workgroup)
+    {
+        const int32_t row_end = min(row0 + 64, T);
+        for (int32_t sg = pd.rowblk_seg[row0 / kRowBlock]; sg < pd.nseg; ++sg) {
+            const int32_t seg_lo = pd.cseg_off[sg];
+            if (seg_lo >= row_end) break;
+            const int32_t t = pd.cseg_task[sg];
+            if (t < 0) continue;
+            const int32_t lo = max(seg_lo, row0), hi = min(pd.cseg_off[sg + 1], row_end);
+            const int32_t r = (pd.rank_off[t + 1] - pd.rank_off[t]) / nproj, pofs = proj * r;
+            const int32_t r0 = pd.rank_off[t] + pofs;
+            for (int32_t c0 = 0; c0 < r; c0 += 16) {
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int e = tid + 256 * u;
+                    {
+                        const int kk = e & 15, m = e >> 4;
+                        const int32_t row = row0 + m;
+                        Zs[kk][m] = (row >= lo && row < hi && c0 + kk < r) ? P[size_t(row) * pd.r_max + pofs + c0 + kk] : 0.f;
+                    }
+                    {
+                        const int nn = e & 63, kk = e >> 6;
+                        const int32_t n = col0 + nn;
+                        Ws[kk][nn] = (c0 + kk < r && n < N) ? Elem<E>::load(M, size_t(r0 + c0 + kk) * N + n) : 0.f;
+                    }
+                }
+                __syncthreads();
+#pragma unroll
+                for (int kk = 0; kk < 16; ++kk) {
+                    float a[4], b[4];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) a[i] = Zs[kk][ty * 4 + i];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) b[j] = Ws[kk][tx * 4 + j];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
+                }
+                __syncthreads();
+            }
+        }
+    }
     for (int i = 0; i < 4; ++i) {
         const int32_t row = row0 + ty * 4 + i;
         if (row >= T) continue;
-        const int32_t t = pd.cseg_task[segment_of_row(pd, row)];
-        if (t >= 0) {
-            const int32_t r = (pd.rank_off[t + 1] - pd.rank_off[t]) / nproj, pofs = proj * r;
-            const int32_t r0 = pd.rank_off[t] + pofs;
-            for (int32_t p = 0; p < r; ++p) {
-                const float pv = P[size_t(row) * pd.r_max + pofs + p];
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int32_t col = col0 + tx * 4 + j;
-                    if (col < N) acc[i][j] = fmaf(pv, Elem<E>::load(M, size_t(r0 + p) * N + col), acc[i][j]);
-                }
-            }
-        }
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int32_t col = col0 + tx * 4 + j;
