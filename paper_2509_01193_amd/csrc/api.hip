@@ -313,12 +313,17 @@ lobra_status lobra_mlora_bwd(const lobra_mlora_plan* plan, const void* x, const 
         if (p.R_tot > 0) {
             if (adapters) {
                 const size_t esz = dt == LOBRA_F32 ? 4 : 2;
-                for (int32_t j = 0; j < p.n_proj; ++j)
+                if (p.n_proj == 1) {       // dB and dA in one launch
                     LOBRA_LAUNCH(p, st, LOBRA_K_GRAD_STAGE1,
-                                 plain_grad_stage1(pd, dt, false, H, static_cast<const char*>(dy) + size_t(j) * pd.dg * esz,
-                                                   part_b, pd.dg, st, pd.d_out, p.n_proj, j));
-                LOBRA_LAUNCH(p, st, LOBRA_K_GRAD_STAGE1,
-                             plain_grad_stage1(pd, dt, false, G, x, part_a, pd.d_in, st));
+                                 plain_grad_stage1(pd, dt, false, H, dy, part_b, pd.d_out, st, 0, 1, 0, G, x, part_a, pd.d_in));
+                } else {
+                    for (int32_t j = 0; j < p.n_proj; ++j)
+                        LOBRA_LAUNCH(p, st, LOBRA_K_GRAD_STAGE1,
+                                     plain_grad_stage1(pd, dt, false, H, static_cast<const char*>(dy) + size_t(j) * pd.dg * esz,
+                                                       part_b, pd.dg, st, pd.d_out, p.n_proj, j));
+                    LOBRA_LAUNCH(p, st, LOBRA_K_GRAD_STAGE1,
+                                 plain_grad_stage1(pd, dt, false, G, x, part_a, pd.d_in, st));
+                }
             }
             const GradJob jb{H, dy, part_b, dB, pd.dg}, ja{G, x, part_a, dA, pd.d_in};
             LOBRA_LAUNCH(p, st, LOBRA_K_GRAD_STAGE2, reduce_partials(pd, jb, ja, accumulate, st));

@@ -37,7 +37,8 @@ hipError_t plain_gemm(const PlanDev& pd, int dtype, bool transW, const void* Z, 
 // P is fp32 [T][r_max], or (p_bf16) bf16 [T][r_pad].
 hipError_t plain_grad_stage1(const PlanDev& pd, int dtype, bool p_bf16, const void* P, const void* Z,
                              float* part, int32_t D, hipStream_t st, int32_t ldz = 0, int32_t nproj = 1,
-                             int32_t proj = 0);
+                             int32_t proj = 0, const void* P2 = nullptr, const void* Z2 = nullptr,
+                             float* part2 = nullptr, int32_t D2 = 0);
 // Stage 2 (also used by the MFMA path): out[R, :] (+)= sum of the partial sums of task(R), in
 // chunk order, so that the result does not depend on scheduling.
 // One launch for up to two gradients (jb.out == nullptr: only ja).

@@ -276,14 +276,25 @@ template <typename E, typename PE>
 __global__ __launch_bounds__(256) void plain_gradreduce_kernel(PlanDev pd, const PE* __restrict__ P,
                                                                int32_t pstride, const E* __restrict__ Z,
                                                                float* __restrict__ part, int32_t D, int32_t ldz,
-                                                               int32_t nproj, int32_t proj)
+                                                               int32_t nproj, int32_t proj, int32_t tiles_a,
+                                                               const PE* __restrict__ P2, const E* __restrict__ Z2,
+                                                               float* __restrict__ part2, int32_t D2)
 {
     // nproj > 1: projection `proj` of a fused call - Z is its column block (row pitch ldz), and of the
-    // task's ranks only the window [proj r, (proj + 1) r) is reduced (columns of P, rows of part)
+    // task's ranks only the window [proj r, (proj + 1) r) is reduced (columns of P, rows of part).
+    // One launch can serve two gradients (nproj = 1): column tiles from tiles_a on belong to (P2, Z2, part2, D2).
+    int32_t coltile = blockIdx.y;
+    if (coltile >= tiles_a) {
+        coltile -= tiles_a;
+        P = P2;
+        Z = Z2;
+        part = part2;
+        D = ldz = D2;
+    }
     const GradChunk c = pd.chunks[blockIdx.x];
     const int32_t r = (pd.rank_off[c.task + 1] - pd.rank_off[c.task]) / nproj;
     const int32_t pofs = proj * r;
-    const int32_t col = blockIdx.y * 256 + threadIdx.x;
+    const int32_t col = coltile * 256 + threadIdx.x;
     const bool live = col < D;
     for (int32_t p0 = 0; p0 < r; p0 += 16) {
         float acc[16] = {};
@@ -374,18 +385,25 @@ hipError_t reduce_partials(const PlanDev& pd, const GradJob& ja, const GradJob& 
 }
 
 hipError_t plain_grad_stage1(const PlanDev& pd, int dtype, bool p_bf16, const void* P, const void* Z,
-                             float* part, int32_t D, hipStream_t st, int32_t ldz, int32_t nproj, int32_t proj)
+                             float* part, int32_t D, hipStream_t st, int32_t ldz, int32_t nproj, int32_t proj,
+                             const void* P2, const void* Z2, float* part2, int32_t D2)
 {
+    // (P2, Z2, part2, D2): a second gradient served by the same launch (nproj = 1 only), or P2 = NULL
     if (pd.nchunks == 0) return hipSuccess;
     if (ldz == 0) ldz = D;
-    const dim3 grid(pd.nchunks, (D + 255) / 256);
+    if (P2 && nproj != 1) return hipErrorInvalidValue;
+    const int32_t tiles_a = (D + 255) / 256, tiles_b = P2 ? (D2 + 255) / 256 : 0;
+    const dim3 grid(pd.nchunks, tiles_a + tiles_b);
     if (grid.y > 65535u) return hipErrorInvalidValue;
     if (dtype == LOBRA_F32)
-        plain_gradreduce_kernel<float, float><<<grid, 256, 0, st>>>(pd, (const float*)P, pd.r_max, (const float*)Z, part, D, ldz, nproj, proj);
+        plain_gradreduce_kernel<float, float><<<grid, 256, 0, st>>>(pd, (const float*)P, pd.r_max, (const float*)Z, part, D, ldz, nproj, proj,
+                                                                     tiles_a, (const float*)P2, (const float*)Z2, part2, D2);
     else if (!p_bf16)
-        plain_gradreduce_kernel<uint16_t, float><<<grid, 256, 0, st>>>(pd, (const float*)P, pd.r_max, (const uint16_t*)Z, part, D, ldz, nproj, proj);
+        plain_gradreduce_kernel<uint16_t, float><<<grid, 256, 0, st>>>(pd, (const float*)P, pd.r_max, (const uint16_t*)Z, part, D, ldz, nproj, proj,
+                                                                        tiles_a, (const float*)P2, (const uint16_t*)Z2, part2, D2);
     else
-        plain_gradreduce_kernel<uint16_t, uint16_t><<<grid, 256, 0, st>>>(pd, (const uint16_t*)P, pd.r_pad, (const uint16_t*)Z, part, D, ldz, nproj, proj);
+        plain_gradreduce_kernel<uint16_t, uint16_t><<<grid, 256, 0, st>>>(pd, (const uint16_t*)P, pd.r_pad, (const uint16_t*)Z, part, D, ldz, nproj, proj,
+                                                                           tiles_a, (const uint16_t*)P2, (const uint16_t*)Z2, part2, D2);
     return hipGetLastError();
 }
 
