@@ -170,6 +170,20 @@ LOBRA_API lobra_status lobra_mlora_fwd(const lobra_mlora_plan *plan, const void 
                              const void *A, const void *B, const float *s, void *y,
                              void *h_save, void *ws, size_t ws_bytes, void *hip_stream);
 
+/* lobra_mlora_fwd for callers that cannot allocate device memory or have none to spare for scratch
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the forward
+ * pass with h_save = NULL whose scratch is a fixed array of LOBRA_STATIC_WS_BYTES inside the library's
+ * own device image instead of a caller buffer.  Arguments as for lobra_mlora_fwd.  Makes no allocation
+ * of any kind and does not synchronise.  LOBRA_ERR_WORKSPACE when the plan's fwd_ws_bytes exceed
+ * LOBRA_STATIC_WS_BYTES (nothing is launched).  Each GPU has ONE such array, which keeps the last
+ * call's contents: two calls of this function that overlap in time on the same GPU (different
+ * streams, or different threads) race on it and must be ordered by the caller; the saved
+ * activations are not available to bwd (pass h_saved = NULL there). */
+enum { LOBRA_STATIC_WS_BYTES = 16 * 1024 * 1024 };
+LOBRA_API lobra_status lobra_mlora_fwd_static_ws(const lobra_mlora_plan *plan, const void *x, const void *W,
+                                       const void *A, const void *B, const float *s, void *y,
+                                       void *hip_stream);
+
 /* Backward: dx, dA, dB as defined at the top (derivatives of the section 2.1 layer; W is
  * frozen, so no dW).
  *   dy      : device [T, d_out], element type desc.dtype

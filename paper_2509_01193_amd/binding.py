@@ -25,6 +25,7 @@ MAX_RANK = 128
 EXPORTS = [
     "lobra_mlora_validate", "lobra_mlora_plan_create", "lobra_mlora_plan_destroy",
     "lobra_mlora_plan_sizes", "lobra_mlora_plan_query", "lobra_mlora_fwd", "lobra_mlora_bwd",
+    "lobra_mlora_fwd_static_ws",
     "lobra_token_task_map", "lobra_mlora_adam_step", "lobra_dynamic_buckets", "lobra_mlora_plan_set_trace", "lobra_status_string", "lobra_version",
 ]
 
@@ -76,6 +77,8 @@ def lib():
         L.lobra_mlora_plan_query.argtypes = [vp, ctypes.c_int32, ctypes.POINTER(ctypes.c_int32), sz, szp]
         L.lobra_mlora_fwd.restype = ctypes.c_int
         L.lobra_mlora_fwd.argtypes = [vp] * 8 + [vp, sz, vp]
+        L.lobra_mlora_fwd_static_ws.restype = ctypes.c_int
+        L.lobra_mlora_fwd_static_ws.argtypes = [vp] * 7 + [vp]
         L.lobra_mlora_bwd.restype = ctypes.c_int
         L.lobra_mlora_bwd.argtypes = [vp] * 11 + [u32, vp, sz, vp]
         L.lobra_token_task_map.restype = ctypes.c_int
@@ -202,6 +205,18 @@ def lobra_mlora_fwd(plan: Plan, x, W, A, B, s, y, h_save=None, ws=None, stream=N
                                0 if ws is None else ws.numel() * ws.element_size(), _stream(stream))
     if check:
         _check(st, "lobra_mlora_fwd")
+    return st
+
+
+STATIC_WS_BYTES = 16 * 1024 * 1024
+
+
+def lobra_mlora_fwd_static_ws(plan: Plan, x, W, A, B, s, y, stream=None, check=True):
+    """lobra_mlora_fwd with the library's own static scratch array (no allocation anywhere)."""
+    st = lib().lobra_mlora_fwd_static_ws(plan.handle, _ptr(x), _ptr(W), _ptr(A), _ptr(B), _ptr(s), _ptr(y),
+                                         _stream(stream))
+    if check:
+        _check(st, "lobra_mlora_fwd_static_ws")
     return st
 
 

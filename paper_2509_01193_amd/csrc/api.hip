@@ -80,6 +80,20 @@ lobra_status runnable(const lobra_mlora_plan* plan)
             LOBRA_HIP(hipEventRecord(static_cast<hipEvent_t>(tp_.trace_events[2 * ti_ + 1]), stream)); \
     } while (0)
 
+// Scratch of lobra_mlora_fwd_static_ws: device memory that is part of the library's code object, so that
+// a call needs no allocation by anybody.  Every GPU the library runs on holds its own copy at its own
+// address; the name below is only a handle for hipGetSymbolAddress, never a pointer to pass to a kernel.
+static __device__ __align__(256) unsigned char scratch[LOBRA_STATIC_WS_BYTES];
+
+// Address of `scratch` on the current device (looked up once per plan, at plan creation).
+lobra_status static_scratch_address(void** out)
+{
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return LOBRA_ERR_HIP;
+    *out = p;
+    return LOBRA_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -109,6 +123,10 @@ lobra_status lobra_mlora_plan_create(const lobra_mlora_desc* desc, uint32_t plan
         }
         p->blob_bytes = blob.size() * sizeof(int32_t);
         if (hipGetDevice(&p->device) != hipSuccess) {
+            delete p;
+            return LOBRA_ERR_HIP;
+        }
+        if (static_scratch_address(&p->static_ws) != LOBRA_OK) {
             delete p;
             return LOBRA_ERR_HIP;
         }
@@ -263,6 +281,17 @@ lobra_status lobra_mlora_fwd(const lobra_mlora_plan* plan, const void* x, const 
                                pd.dg, pd.d_out, st, pd.d_out, p.n_proj, j));
     }
     return LOBRA_OK;
+}
+
+lobra_status lobra_mlora_fwd_static_ws(const lobra_mlora_plan* plan, const void* x, const void* W,
+                                       const void* A, const void* B, const float* s, void* y,
+                                       void* hip_stream)
+{
+    lobra_status rs = runnable(plan);
+    if (rs != LOBRA_OK) return rs;
+    if (plan->fwd_ws_bytes > size_t(LOBRA_STATIC_WS_BYTES)) return LOBRA_ERR_WORKSPACE;
+    // the kernels get the array's device address, looked up when the plan was created on this device
+    return lobra_mlora_fwd(plan, x, W, A, B, s, y, nullptr, plan->static_ws, size_t(LOBRA_STATIC_WS_BYTES), hip_stream);
 }
 
 lobra_status lobra_mlora_bwd(const lobra_mlora_plan* plan, const void* x, const void* W,

@@ -61,6 +61,7 @@ struct Plan {
     int device = -1;
     void* dev_blob = nullptr;
     size_t blob_bytes = 0;
+    void* static_ws = nullptr;          // this device's copy of the library's static scratch array
     // offsets (in int32 units) of the lists inside the blob
     size_t o_cseg_off = 0, o_cseg_task = 0, o_rowblk = 0, o_tb = 0, o_chunks = 0,
            o_task_chunk = 0, o_rank_off = 0, o_task_tb = 0, o_sb = 0, o_tb_order = 0, o_sb_order = 0;
