@@ -52,6 +52,13 @@ hipError_t reduce_partials(const PlanDev& pd, const GradJob& ja, const GradJob& 
 hipError_t gemm_mfma(const PlanDev& pd, bool transW, const void* Z, const void* W, const void* P,
                      const void* M, void* C, int32_t K, int32_t N, int32_t ldw, hipStream_t st,
                      int32_t ldc = 0, int32_t nproj = 1, int32_t proj = 0);
+// The persistent direct-to-LDS kernel behind gemm_mfma for K % 64 == 0 (gemm_persistent.hip); gm = tile rows
+// per sweep of the tile order.  Shapes the two kernels' 32-bit tile offsets cannot address are rejected by
+// gemm_mfma_shape_ok, which plan creation consults so that no call fails after its first launch.
+hipError_t gemm_persistent(const PlanDev& pd, bool transW, const void* Z, const void* W, const void* P,
+                           const void* M, void* C, int32_t K, int32_t N, int32_t ldw, int32_t ldc, int32_t nproj,
+                           int32_t proj, int32_t tiles_m, int32_t tiles_n, int32_t gm, hipStream_t st);
+bool gemm_mfma_shape_ok(int64_t T, int32_t K, int32_t N, int32_t ldw);
 // P = s_t Z M_t^T in bf16, written token-major [T][r_pad] and block-transposed [ntb][r_pad][32].
 // (ldz: row pitch of Z; nproj > 1: projection `proj` of a fused call - rank window, see the kernel)
 hipError_t shrink_mfma(const PlanDev& pd, const void* Z, const void* M, const float* s,
