@@ -32,8 +32,19 @@
  *
  * Every function returns a lobra_status; nothing throws.  All argument checks
  * run on the host before anything is launched, and on error nothing is
- * written.  No call synchronises the stream except lobra_mlora_plan_create
- * (one blocking upload of the plan) and lobra_mlora_plan_destroy.
+ * written.
+ *
+ * Two ways to call the layer:
+ *   one-shot   lobra_mlora_workspace_bytes, lobra_mlora_fwd, lobra_mlora_bwd, lobra_token_task_map take the
+ *              descriptor itself.  The library allocates no device memory and never synchronises: the
+ *              tables derived from the descriptor are placed at the start of the caller's workspace by an
+ *              asynchronous copy on the caller's stream.  Every call pays for building them on the host
+ *              (about 0.1 ms for 16384 tokens).
+ *   with plan  a packed batch goes through every LoRA linear of every layer with the same segment table,
+ *              so lobra_mlora_plan_init (device image in caller memory, asynchronous upload) or
+ *              lobra_mlora_plan_create (the one call that allocates device memory and blocks) builds the
+ *              tables once and lobra_mlora_plan_fwd / _bwd / ... reuse them; these calls do no host
+ *              work beyond the launches and can be captured in a HIP graph.
  */
 #ifndef LOBRA_MLORA_H
 #define LOBRA_MLORA_H
@@ -51,12 +62,12 @@ extern "C" {
 typedef enum {
     LOBRA_OK = 0,
     LOBRA_ERR_NULL = -1,      /* a required pointer is NULL */
-    LOBRA_ERR_SHAPE = -2,     /* T, d_in, d_out, n_tasks or S out of range */
+    LOBRA_ERR_SHAPE = -2,     /* T, d_in, d_out, n_tasks or S out of range (see lobra_mlora_desc) */
     LOBRA_ERR_DTYPE = -3,     /* dtype is neither LOBRA_F32 nor LOBRA_BF16 */
     LOBRA_ERR_SEGMENTS = -4,  /* seg_off[0] != 0, decreasing, or seg_off[S] != T */
     LOBRA_ERR_TASK_ID = -5,   /* a seg_task outside [-1, n_tasks) */
     LOBRA_ERR_RANK = -6,      /* rank_off[0] != 0 or a rank outside [1, LOBRA_MAX_RANK] */
-    LOBRA_ERR_WORKSPACE = -7, /* workspace NULL or smaller than lobra_mlora_plan_sizes says */
+    LOBRA_ERR_WORKSPACE = -7, /* workspace NULL or smaller than lobra_mlora_workspace_bytes / _plan_sizes say */
     LOBRA_ERR_ALIGN = -8,     /* a pointer not 16-byte aligned, or bf16 d_in/d_out not a multiple of 8 */
     LOBRA_ERR_HIP = -9,       /* a HIP runtime call failed (no device, launch error, ...) */
     LOBRA_ERR_PLAN = -10,     /* plan is NULL, host-only, or was built for another device */
@@ -65,7 +76,8 @@ typedef enum {
 
 typedef enum { LOBRA_F32 = 0, LOBRA_BF16 = 1 } lobra_dtype;
 
-enum { LOBRA_MAX_RANK = 128 };
+enum { LOBRA_MAX_RANK = 128,
+       LOBRA_MAX_WIDTH = 1 << 20 };  /* d_in, d_out: the kernels' launch grids and 32-bit tile offsets end here */
 
 /* flags of lobra_mlora_bwd */
 enum {
@@ -86,8 +98,9 @@ enum {
  * during lobra_mlora_validate / lobra_mlora_plan_create only (the plan keeps copies). */
 typedef struct {
     int32_t dtype;           /* lobra_dtype of x, W, A, B, y, dy, dx */
-    int32_t d_in, d_out;     /* >= 1; multiples of 8 for LOBRA_BF16 */
-    int64_t T;               /* packed tokens, 0 <= T < 2^31 */
+    int32_t d_in, d_out;     /* 1 .. LOBRA_MAX_WIDTH; multiples of 8 for LOBRA_BF16 */
+    int64_t T;               /* packed tokens, 0 <= T < 2^31 (fp32 and LOBRA_PLAN_PLAIN_KERNELS: T <= 4194240);
+                                ceil(T / 256) * ceil(max(d_in, d_out) / 256) < 2^31 */
     int32_t n_tasks;         /* >= 0; 0 = base product only */
     int32_t S;               /* segments, >= 0 (S = 0 requires T = 0) */
     const int32_t *rank_off; /* [n_tasks+1], rank_off[0] = 0, r_t = rank_off[t+1]-rank_off[t] */
@@ -111,7 +124,8 @@ typedef struct {
  * Requires d_out a multiple of 8 P (else LOBRA_ERR_ALIGN) and every stacked rank a multiple of 8 P
  * (else LOBRA_ERR_RANK); 1 <= P <= 16. */
 
-/* Opaque per-batch plan: the validated table plus the device-resident work lists (token
+/* Opaque per-batch plan (section 1 / Figure 1: the fused batch of task-tagged sequences, turned into what the
+ * kernels iterate over): the validated table plus the device-resident work lists (token
  * blocks, per-tile segment ranges, reduction chunks).  One packed batch passes through every
  * LoRA linear of every layer with the same table, so a plan is built once per batch and
  * shared by all those calls.  Immutable after creation; concurrent calls may share it. */
@@ -126,8 +140,18 @@ LOBRA_API lobra_status lobra_mlora_validate(const lobra_mlora_desc *desc);
 LOBRA_API lobra_status lobra_mlora_plan_create(const lobra_mlora_desc *desc, uint32_t plan_flags,
                                      lobra_mlora_plan **out);
 
-/* Frees the plan and its device buffer.  The caller makes sure no launched work still uses it.
- * NULL is accepted. */
+/* The same without any allocation of device memory and without blocking: the plan's device image
+ * (*bytes of lobra_mlora_plan_device_bytes for the same desc and flags) goes into device_mem, device memory of the
+ * caller (16-byte aligned, device_bytes long), by an asynchronous copy on hip_stream; work that uses the plan
+ * must be ordered after that copy (same stream, or an event).  device_mem belongs to the plan until
+ * lobra_mlora_plan_destroy, which does not free it.  LOBRA_ERR_WORKSPACE when device_bytes is too small,
+ * LOBRA_ERR_PLAN with LOBRA_PLAN_HOST_ONLY. */
+LOBRA_API lobra_status lobra_mlora_plan_device_bytes(const lobra_mlora_desc *desc, uint32_t plan_flags, size_t *bytes);
+LOBRA_API lobra_status lobra_mlora_plan_init(const lobra_mlora_desc *desc, uint32_t plan_flags, void *device_mem,
+                                   size_t device_bytes, void *hip_stream, lobra_mlora_plan **out);
+
+/* Frees the plan (and the device buffer of lobra_mlora_plan_create).  The caller makes sure that no launched
+ * work, and no upload of lobra_mlora_plan_init, still uses it.  NULL is accepted. */
 LOBRA_API lobra_status lobra_mlora_plan_destroy(lobra_mlora_plan *plan);
 
 /* Buffer sizes in bytes (each may be 0): h_save = the saved down-projected activations that
@@ -166,19 +190,19 @@ LOBRA_API lobra_status lobra_mlora_plan_query(const lobra_mlora_plan *plan, int3
  *                   h_save is NULL
  *   hip_stream    : hipStream_t (NULL = default stream); work is enqueued, not awaited
  * x, W, A, B, s are read only; y and h_save are overwritten. */
-LOBRA_API lobra_status lobra_mlora_fwd(const lobra_mlora_plan *plan, const void *x, const void *W,
-                             const void *A, const void *B, const float *s, void *y,
-                             void *h_save, void *ws, size_t ws_bytes, void *hip_stream);
+LOBRA_API lobra_status lobra_mlora_plan_fwd(const lobra_mlora_plan *plan, const void *x, const void *W,
+                                  const void *A, const void *B, const float *s, void *y,
+                                  void *h_save, void *ws, size_t ws_bytes, void *hip_stream);
 
-/* lobra_mlora_fwd for callers that cannot allocate device memory or have none to spare for scratch
+/* lobra_mlora_plan_fwd for callers that cannot allocate device memory or have none to spare for scratch
  * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the forward
  * pass with h_save = NULL whose scratch is a fixed array of LOBRA_STATIC_WS_BYTES inside the library's
- * own device image instead of a caller buffer.  Arguments as for lobra_mlora_fwd.  Makes no allocation
+ * own device image instead of a caller buffer.  Arguments as for lobra_mlora_plan_fwd.  Makes no allocation
  * of any kind and does not synchronise.  LOBRA_ERR_WORKSPACE when the plan's fwd_ws_bytes exceed
  * LOBRA_STATIC_WS_BYTES (nothing is launched).  Each GPU has ONE such array, which keeps the last
- * call's contents: two calls of this function that overlap in time on the same GPU (different
- * streams, or different threads) race on it and must be ordered by the caller; the saved
- * activations are not available to bwd (pass h_saved = NULL there). */
+ * call's contents: two calls of this function (or of lobra_token_task_map, which parks its tables there)
+ * that overlap in time on the same GPU (different streams, or different threads) race on it and must be
+ * ordered by the caller; the saved activations are not available to bwd (pass h_saved = NULL there). */
 enum { LOBRA_STATIC_WS_BYTES = 16 * 1024 * 1024 };
 LOBRA_API lobra_status lobra_mlora_fwd_static_ws(const lobra_mlora_plan *plan, const void *x, const void *W,
                                        const void *A, const void *B, const float *s, void *y,
@@ -193,16 +217,39 @@ LOBRA_API lobra_status lobra_mlora_fwd_static_ws(const lobra_mlora_plan *plan, c
  *             tokens become 0), or added to with LOBRA_FLAG_ACCUMULATE_GRADS
  *   ws      : device scratch of at least bwd_ws_bytes
  * The reductions run in a fixed order: results are bit-identical from run to run. */
-LOBRA_API lobra_status lobra_mlora_bwd(const lobra_mlora_plan *plan, const void *x, const void *W,
-                             const void *A, const void *B, const float *s, const void *dy,
-                             const void *h_saved, void *dx, float *dA, float *dB,
-                             uint32_t flags, void *ws, size_t ws_bytes, void *hip_stream);
+LOBRA_API lobra_status lobra_mlora_plan_bwd(const lobra_mlora_plan *plan, const void *x, const void *W,
+                                  const void *A, const void *B, const float *s, const void *dy,
+                                  const void *h_saved, void *dx, float *dA, float *dB,
+                                  uint32_t flags, void *ws, size_t ws_bytes, void *hip_stream);
 
-/* Index probe: writes the task of every token (device int32 [T], -1 = none) and the number
- * of tokens per task (device int64 [n_tasks]) with the same device-side table walk the
- * kernels use.  Either output may be NULL. */
-LOBRA_API lobra_status lobra_token_task_map(const lobra_mlora_plan *plan, int32_t *out_task,
-                                  int64_t *out_count, void *hip_stream);
+/* Index probe (section 1 / Figure 1: a fused batch is a sequence of task-tagged token runs): writes the task of
+ * every token (device int32 [T], -1 = none) and the number of tokens per task (device int64 [n_tasks]) with
+ * the same device-side table walk the kernels use.  Either output may be NULL. */
+LOBRA_API lobra_status lobra_mlora_plan_token_task_map(const lobra_mlora_plan *plan, int32_t *out_task,
+                                             int64_t *out_count, void *hip_stream);
+
+/* ---- one-shot forms: the same operations on the descriptor itself (section 1 / Figure 1: the fused batch is
+ * given as its task-tagged token runs; section 2.1: the layer).  Each call validates the descriptor, builds the
+ * tables on the host, copies them asynchronously (on hip_stream) to the start of ws and runs the kernels behind
+ * that copy.  No device memory is allocated or freed and nothing synchronises; the host image of the tables is
+ * released by a host callback on the stream (which is why these forms cannot be captured in a HIP graph: use a
+ * plan there).
+ *   lobra_mlora_workspace_bytes : bytes of ws that lobra_mlora_fwd (with h_save = NULL) and lobra_mlora_bwd
+ *                                 need for this descriptor; host only, no HIP call; either out pointer may be NULL
+ *   lobra_mlora_fwd / _bwd      : arguments as for the plan forms; ws (16-byte aligned, device) must hold
+ *                                 *fwd_bytes / *bwd_bytes (LOBRA_ERR_WORKSPACE otherwise, before any launch)
+ *   lobra_token_task_map        : has no workspace argument: its tables go into the library's static device
+ *                                 array (see lobra_mlora_fwd_static_ws for the sharing rule; LOBRA_ERR_WORKSPACE
+ *                                 beyond LOBRA_STATIC_WS_BYTES, about 30 million tokens) */
+LOBRA_API lobra_status lobra_mlora_workspace_bytes(const lobra_mlora_desc *desc, size_t *fwd_bytes, size_t *bwd_bytes);
+LOBRA_API lobra_status lobra_mlora_fwd(const lobra_mlora_desc *desc, const void *x, const void *W, const void *A,
+                             const void *B, const float *s, void *y, void *h_save, void *ws, size_t ws_bytes,
+                             void *hip_stream);
+LOBRA_API lobra_status lobra_mlora_bwd(const lobra_mlora_desc *desc, const void *x, const void *W, const void *A,
+                             const void *B, const float *s, const void *dy, const void *h_saved, void *dx,
+                             float *dA, float *dB, uint32_t flags, void *ws, size_t ws_bytes, void *hip_stream);
+LOBRA_API lobra_status lobra_token_task_map(const lobra_mlora_desc *desc, int32_t *out_task, int64_t *out_count,
+                                  void *hip_stream);
 
 /* Fused multi-adapter Adam step: the update that follows the backward pass, for the adapters of
  * all tasks in one launch (the paper trains every task with Adam and cites its decoupled

@@ -23,10 +23,11 @@ Q_BLOCK_ORDER, Q_RUN_ORDER = 6, 7
 MAX_RANK = 128
 
 EXPORTS = [
-    "lobra_mlora_validate", "lobra_mlora_plan_create", "lobra_mlora_plan_destroy",
-    "lobra_mlora_plan_sizes", "lobra_mlora_plan_query", "lobra_mlora_fwd", "lobra_mlora_bwd",
-    "lobra_mlora_fwd_static_ws",
-    "lobra_token_task_map", "lobra_mlora_adam_step", "lobra_dynamic_buckets", "lobra_mlora_plan_set_trace", "lobra_status_string", "lobra_version",
+    "lobra_mlora_validate", "lobra_mlora_workspace_bytes", "lobra_mlora_fwd", "lobra_mlora_bwd", "lobra_token_task_map",
+    "lobra_mlora_plan_create", "lobra_mlora_plan_device_bytes", "lobra_mlora_plan_init", "lobra_mlora_plan_destroy",
+    "lobra_mlora_plan_sizes", "lobra_mlora_plan_query", "lobra_mlora_plan_fwd", "lobra_mlora_plan_bwd",
+    "lobra_mlora_plan_token_task_map", "lobra_mlora_fwd_static_ws", "lobra_mlora_adam_step", "lobra_dynamic_buckets",
+    "lobra_mlora_plan_set_trace", "lobra_status_string", "lobra_version",
 ]
 
 
@@ -75,14 +76,24 @@ def lib():
         L.lobra_mlora_plan_sizes.argtypes = [vp, szp, szp, szp]
         L.lobra_mlora_plan_query.restype = ctypes.c_int
         L.lobra_mlora_plan_query.argtypes = [vp, ctypes.c_int32, ctypes.POINTER(ctypes.c_int32), sz, szp]
-        L.lobra_mlora_fwd.restype = ctypes.c_int
-        L.lobra_mlora_fwd.argtypes = [vp] * 8 + [vp, sz, vp]
+        for name in ("lobra_mlora_plan_fwd", "lobra_mlora_fwd"):      # (plan | desc, x, W, A, B, s, y, h_save, ws, bytes, stream)
+            getattr(L, name).restype = ctypes.c_int
+        L.lobra_mlora_plan_fwd.argtypes = [vp] * 8 + [vp, sz, vp]
+        L.lobra_mlora_fwd.argtypes = [ctypes.POINTER(Desc)] + [vp] * 7 + [vp, sz, vp]
         L.lobra_mlora_fwd_static_ws.restype = ctypes.c_int
         L.lobra_mlora_fwd_static_ws.argtypes = [vp] * 7 + [vp]
-        L.lobra_mlora_bwd.restype = ctypes.c_int
-        L.lobra_mlora_bwd.argtypes = [vp] * 11 + [u32, vp, sz, vp]
-        L.lobra_token_task_map.restype = ctypes.c_int
-        L.lobra_token_task_map.argtypes = [vp, vp, vp, vp]
+        L.lobra_mlora_plan_bwd.restype = L.lobra_mlora_bwd.restype = ctypes.c_int
+        L.lobra_mlora_plan_bwd.argtypes = [vp] * 11 + [u32, vp, sz, vp]
+        L.lobra_mlora_bwd.argtypes = [ctypes.POINTER(Desc)] + [vp] * 10 + [u32, vp, sz, vp]
+        L.lobra_mlora_plan_token_task_map.restype = L.lobra_token_task_map.restype = ctypes.c_int
+        L.lobra_mlora_plan_token_task_map.argtypes = [vp, vp, vp, vp]
+        L.lobra_token_task_map.argtypes = [ctypes.POINTER(Desc), vp, vp, vp]
+        L.lobra_mlora_workspace_bytes.restype = ctypes.c_int
+        L.lobra_mlora_workspace_bytes.argtypes = [ctypes.POINTER(Desc), szp, szp]
+        L.lobra_mlora_plan_device_bytes.restype = ctypes.c_int
+        L.lobra_mlora_plan_device_bytes.argtypes = [ctypes.POINTER(Desc), u32, szp]
+        L.lobra_mlora_plan_init.restype = ctypes.c_int
+        L.lobra_mlora_plan_init.argtypes = [ctypes.POINTER(Desc), u32, vp, sz, vp, ctypes.POINTER(vp)]
         L.lobra_mlora_adam_step.restype = ctypes.c_int
         L.lobra_mlora_adam_step.argtypes = [vp, ctypes.POINTER(AdamConfig)] + [vp] * 13 + [vp]
         L.lobra_status_string.restype = ctypes.c_char_p
@@ -158,11 +169,20 @@ def _stream(stream):
 class Plan:
     """Owns a ``lobra_mlora_plan``.  One plan per packed batch, shared by every layer's calls."""
 
-    def __init__(self, dtype, T, d_in, d_out, rank_off, seg_off, seg_task, flags=0, n_proj=1):
+    def __init__(self, dtype, T, d_in, d_out, rank_off, seg_off, seg_task, flags=0, n_proj=1, device_mem=None,
+                 stream=None):
+        """device_mem (a device uint8 tensor of at least plan_device_bytes(...)): lobra_mlora_plan_init places
+        the plan there with an asynchronous copy on `stream`; None: lobra_mlora_plan_create allocates."""
         self.desc, self._keep = make_desc(dtype, T, d_in, d_out, rank_off, seg_off, seg_task, n_proj)
         self.handle = ctypes.c_void_p()
-        _check(lib().lobra_mlora_plan_create(ctypes.byref(self.desc), int(flags),
-                                             ctypes.byref(self.handle)), "lobra_mlora_plan_create")
+        if device_mem is None:
+            _check(lib().lobra_mlora_plan_create(ctypes.byref(self.desc), int(flags),
+                                                 ctypes.byref(self.handle)), "lobra_mlora_plan_create")
+        else:
+            self._keep.append(device_mem)
+            _check(lib().lobra_mlora_plan_init(ctypes.byref(self.desc), int(flags), _ptr(device_mem),
+                                               device_mem.numel() * device_mem.element_size(), _stream(stream),
+                                               ctypes.byref(self.handle)), "lobra_mlora_plan_init")
         a, b, c = ctypes.c_size_t(), ctypes.c_size_t(), ctypes.c_size_t()
         _check(lib().lobra_mlora_plan_sizes(self.handle, ctypes.byref(a), ctypes.byref(b),
                                             ctypes.byref(c)), "lobra_mlora_plan_sizes")
@@ -198,13 +218,58 @@ class Plan:
             pass
 
 
-def lobra_mlora_fwd(plan: Plan, x, W, A, B, s, y, h_save=None, ws=None, stream=None, check=True):
+def plan_device_bytes(desc: Desc, flags=0) -> int:
+    n = ctypes.c_size_t()
+    _check(lib().lobra_mlora_plan_device_bytes(ctypes.byref(desc), int(flags), ctypes.byref(n)),
+           "lobra_mlora_plan_device_bytes")
+    return n.value
+
+
+def lobra_mlora_workspace_bytes(desc: Desc):
+    """(fwd bytes, bwd bytes) of workspace the one-shot calls need for this descriptor."""
+    a, b = ctypes.c_size_t(), ctypes.c_size_t()
+    _check(lib().lobra_mlora_workspace_bytes(ctypes.byref(desc), ctypes.byref(a), ctypes.byref(b)),
+           "lobra_mlora_workspace_bytes")
+    return a.value, b.value
+
+
+def _nbytes(t):
+    return 0 if t is None else t.numel() * t.element_size()
+
+
+def lobra_mlora_fwd(desc: Desc, x, W, A, B, s, y, h_save=None, ws=None, stream=None, check=True):
+    """One-shot forward on a descriptor (no plan object).  Returns the status."""
+    st = lib().lobra_mlora_fwd(ctypes.byref(desc), _ptr(x), _ptr(W), _ptr(A), _ptr(B), _ptr(s), _ptr(y),
+                               _ptr(h_save), _ptr(ws), _nbytes(ws), _stream(stream))
+    if check:
+        _check(st, "lobra_mlora_fwd")
+    return st
+
+
+def lobra_mlora_bwd(desc: Desc, x, W, A, B, s, dy, h_saved, dx, dA, dB, flags=0, ws=None, stream=None, check=True):
+    """One-shot backward on a descriptor.  Returns the status."""
+    st = lib().lobra_mlora_bwd(ctypes.byref(desc), _ptr(x), _ptr(W), _ptr(A), _ptr(B), _ptr(s), _ptr(dy),
+                               _ptr(h_saved), _ptr(dx), _ptr(dA), _ptr(dB), int(flags), _ptr(ws), _nbytes(ws),
+                               _stream(stream))
+    if check:
+        _check(st, "lobra_mlora_bwd")
+    return st
+
+
+def lobra_token_task_map(desc: Desc, out_task, out_count, stream=None, check=True):
+    st = lib().lobra_token_task_map(ctypes.byref(desc), _ptr(out_task), _ptr(out_count), _stream(stream))
+    if check:
+        _check(st, "lobra_token_task_map")
+    return st
+
+
+def lobra_mlora_plan_fwd(plan: Plan, x, W, A, B, s, y, h_save=None, ws=None, stream=None, check=True):
     """y = x W + s_t (A_t x) B_t.  Tensors are device tensors; returns the status."""
-    st = lib().lobra_mlora_fwd(plan.handle, _ptr(x), _ptr(W), _ptr(A), _ptr(B), _ptr(s), _ptr(y),
+    st = lib().lobra_mlora_plan_fwd(plan.handle, _ptr(x), _ptr(W), _ptr(A), _ptr(B), _ptr(s), _ptr(y),
                                _ptr(h_save), _ptr(ws),
                                0 if ws is None else ws.numel() * ws.element_size(), _stream(stream))
     if check:
-        _check(st, "lobra_mlora_fwd")
+        _check(st, "lobra_mlora_plan_fwd")
     return st
 
 
@@ -220,14 +285,14 @@ def lobra_mlora_fwd_static_ws(plan: Plan, x, W, A, B, s, y, stream=None, check=T
     return st
 
 
-def lobra_mlora_bwd(plan: Plan, x, W, A, B, s, dy, h_saved, dx, dA, dB, flags=0, ws=None,
-                    stream=None, check=True):
+def lobra_mlora_plan_bwd(plan: Plan, x, W, A, B, s, dy, h_saved, dx, dA, dB, flags=0, ws=None,
+                         stream=None, check=True):
     """dx, dA, dB of the layer.  Returns the status."""
-    st = lib().lobra_mlora_bwd(plan.handle, _ptr(x), _ptr(W), _ptr(A), _ptr(B), _ptr(s), _ptr(dy),
+    st = lib().lobra_mlora_plan_bwd(plan.handle, _ptr(x), _ptr(W), _ptr(A), _ptr(B), _ptr(s), _ptr(dy),
                                _ptr(h_saved), _ptr(dx), _ptr(dA), _ptr(dB), int(flags), _ptr(ws),
                                0 if ws is None else ws.numel() * ws.element_size(), _stream(stream))
     if check:
-        _check(st, "lobra_mlora_bwd")
+        _check(st, "lobra_mlora_plan_bwd")
     return st
 
 
@@ -258,9 +323,9 @@ def lobra_dynamic_buckets(seq_len, bounds, R):
     return out[: n.value].tolist(), int(pad.value)
 
 
-def lobra_token_task_map(plan: Plan, out_task, out_count, stream=None):
-    _check(lib().lobra_token_task_map(plan.handle, _ptr(out_task), _ptr(out_count), _stream(stream)),
-           "lobra_token_task_map")
+def lobra_mlora_plan_token_task_map(plan: Plan, out_task, out_count, stream=None):
+    _check(lib().lobra_mlora_plan_token_task_map(plan.handle, _ptr(out_task), _ptr(out_count), _stream(stream)),
+           "lobra_mlora_plan_token_task_map")
 
 
 # ---------------------------------------------------------------------------------------------
@@ -294,13 +359,13 @@ class DeviceProblem:
         self.ws = nb(max(self.plan.fwd_ws_bytes, self.plan.bwd_ws_bytes))
 
     def fwd(self, save_h=True):
-        lobra_mlora_fwd(self.plan, self.x, self.W, self.A, self.B, self.s, self.y,
-                        self.h_save if save_h else None, self.ws)
+        lobra_mlora_plan_fwd(self.plan, self.x, self.W, self.A, self.B, self.s, self.y,
+                             self.h_save if save_h else None, self.ws)
 
     def bwd(self, use_saved_h=True, flags=0):
-        lobra_mlora_bwd(self.plan, self.x, self.W, self.A, self.B, self.s, self.dy,
-                        self.h_save if use_saved_h else None, self.dx, self.dA, self.dB,
-                        flags, self.ws)
+        lobra_mlora_plan_bwd(self.plan, self.x, self.W, self.A, self.B, self.s, self.dy,
+                             self.h_save if use_saved_h else None, self.dx, self.dA, self.dB,
+                             flags, self.ws)
 
     def step(self):
         self.fwd(True)

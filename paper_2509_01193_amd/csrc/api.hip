@@ -80,6 +80,40 @@ lobra_status runnable(const lobra_mlora_plan* plan)
             LOBRA_HIP(hipEventRecord(static_cast<hipEvent_t>(tp_.trace_events[2 * ti_ + 1]), stream)); \
     } while (0)
 
+// Argument checks of a forward call on plan p (everything except the plan itself): host only.
+lobra_status fwd_check(const Plan& p, const void* x, const void* W, const void* A, const void* B, const float* s,
+                       const void* y, const void* h_save, const void* ws, size_t ws_bytes)
+{
+    const bool adapters = !p.tb.empty();
+    if (!x || !W || !y) return LOBRA_ERR_NULL;
+    if (adapters && (!A || !B || !s)) return LOBRA_ERR_NULL;
+    if (!aligned16(x) || !aligned16(W) || !aligned16(y) || !aligned16(A) || !aligned16(B) ||
+        !aligned16(h_save) || !aligned16(ws))
+        return LOBRA_ERR_ALIGN;
+    if (adapters && !h_save && (!ws || ws_bytes < p.fwd_ws_bytes)) return LOBRA_ERR_WORKSPACE;
+    return LOBRA_OK;
+}
+
+// The same for a backward call.
+lobra_status bwd_check(const Plan& p, const void* x, const void* W, const void* A, const void* B, const float* s,
+                       const void* dy, const void* h_saved, const void* dx, const float* dA, const float* dB,
+                       uint32_t flags, const void* ws, size_t ws_bytes)
+{
+    const bool adapters = !p.tb.empty();
+    const bool want_dx = !(flags & LOBRA_FLAG_NO_DX);
+    if (p.R_tot > 0 && (!dA || !dB)) return LOBRA_ERR_NULL;
+    if (p.desc.T > 0) {
+        if (!W || !dy) return LOBRA_ERR_NULL;
+        if (want_dx && !dx) return LOBRA_ERR_NULL;
+        if (adapters && (!x || !A || !B || !s)) return LOBRA_ERR_NULL;
+    }
+    if (!aligned16(x) || !aligned16(W) || !aligned16(A) || !aligned16(B) || !aligned16(dy) ||
+        !aligned16(h_saved) || !aligned16(dx) || !aligned16(dA) || !aligned16(dB) || !aligned16(ws))
+        return LOBRA_ERR_ALIGN;
+    if (p.bwd_ws_bytes > 0 && adapters && (!ws || ws_bytes < p.bwd_ws_bytes)) return LOBRA_ERR_WORKSPACE;
+    return LOBRA_OK;
+}
+
 // Scratch of lobra_mlora_fwd_static_ws: device memory that is part of the library's code object, so that
 // a call needs no allocation by anybody.  Every GPU the library runs on holds its own copy at its own
 // address; the name below is only a handle for hipGetSymbolAddress, never a pointer to pass to a kernel.
@@ -100,33 +134,39 @@ extern "C" {
 
 lobra_status lobra_mlora_validate(const lobra_mlora_desc* desc) { return validate(desc); }
 
-lobra_status lobra_mlora_plan_create(const lobra_mlora_desc* desc, uint32_t plan_flags,
-                                     lobra_mlora_plan** out)
+// Host side of a plan and its packed device image (kept in the plan: an asynchronous upload reads it later).
+static lobra_status make_host_plan(const lobra_mlora_desc* desc, uint32_t plan_flags, lobra_mlora_plan** out)
 {
-    if (!out) return LOBRA_ERR_NULL;
     lobra_status st = validate(desc);
     if (st != LOBRA_OK) return st;
     lobra_mlora_plan* p = new (std::nothrow) lobra_mlora_plan();
     if (!p) return LOBRA_ERR_NOMEM;
     st = build_host_plan(desc, plan_flags, p);
+    if (st == LOBRA_OK && !(plan_flags & LOBRA_PLAN_HOST_ONLY)) {
+        try {
+            p->host_blob = pack_blob(p);
+            p->blob_bytes = p->host_blob.size() * sizeof(int32_t);
+        } catch (const std::bad_alloc&) {
+            st = LOBRA_ERR_NOMEM;
+        }
+    }
     if (st != LOBRA_OK) {
         delete p;
         return st;
     }
+    *out = p;
+    return LOBRA_OK;
+}
+
+lobra_status lobra_mlora_plan_create(const lobra_mlora_desc* desc, uint32_t plan_flags,
+                                     lobra_mlora_plan** out)
+{
+    if (!out) return LOBRA_ERR_NULL;
+    lobra_mlora_plan* p = nullptr;
+    lobra_status st = make_host_plan(desc, plan_flags, &p);
+    if (st != LOBRA_OK) return st;
     if (!(plan_flags & LOBRA_PLAN_HOST_ONLY)) {
-        std::vector<int32_t> blob;
-        try {
-            blob = pack_blob(p);
-        } catch (const std::bad_alloc&) {
-            delete p;
-            return LOBRA_ERR_NOMEM;
-        }
-        p->blob_bytes = blob.size() * sizeof(int32_t);
-        if (hipGetDevice(&p->device) != hipSuccess) {
-            delete p;
-            return LOBRA_ERR_HIP;
-        }
-        if (static_scratch_address(&p->static_ws) != LOBRA_OK) {
+        if (hipGetDevice(&p->device) != hipSuccess || static_scratch_address(&p->static_ws) != LOBRA_OK) {
             delete p;
             return LOBRA_ERR_HIP;
         }
@@ -134,7 +174,8 @@ lobra_status lobra_mlora_plan_create(const lobra_mlora_desc* desc, uint32_t plan
             delete p;
             return LOBRA_ERR_NOMEM;
         }
-        if (hipMemcpy(p->dev_blob, blob.data(), p->blob_bytes, hipMemcpyHostToDevice) != hipSuccess) {
+        p->owns_blob = true;
+        if (hipMemcpy(p->dev_blob, p->host_blob.data(), p->blob_bytes, hipMemcpyHostToDevice) != hipSuccess) {
             (void)hipFree(p->dev_blob);
             delete p;
             return LOBRA_ERR_HIP;
@@ -144,11 +185,46 @@ lobra_status lobra_mlora_plan_create(const lobra_mlora_desc* desc, uint32_t plan
     return LOBRA_OK;
 }
 
+lobra_status lobra_mlora_plan_device_bytes(const lobra_mlora_desc* desc, uint32_t plan_flags, size_t* bytes)
+{
+    if (!bytes) return LOBRA_ERR_NULL;
+    lobra_mlora_plan* p = nullptr;
+    lobra_status st = make_host_plan(desc, plan_flags & ~uint32_t(LOBRA_PLAN_HOST_ONLY), &p);
+    if (st != LOBRA_OK) return st;
+    *bytes = p->blob_bytes;
+    delete p;
+    return LOBRA_OK;
+}
+
+lobra_status lobra_mlora_plan_init(const lobra_mlora_desc* desc, uint32_t plan_flags, void* device_mem,
+                                   size_t device_bytes, void* hip_stream, lobra_mlora_plan** out)
+{
+    if (!out) return LOBRA_ERR_NULL;
+    if (plan_flags & LOBRA_PLAN_HOST_ONLY) return LOBRA_ERR_PLAN;
+    lobra_mlora_plan* p = nullptr;
+    lobra_status st = make_host_plan(desc, plan_flags, &p);
+    if (st != LOBRA_OK) return st;
+    if (!device_mem || device_bytes < p->blob_bytes) st = LOBRA_ERR_WORKSPACE;
+    else if (!aligned16(device_mem)) st = LOBRA_ERR_ALIGN;
+    else if (hipGetDevice(&p->device) != hipSuccess || static_scratch_address(&p->static_ws) != LOBRA_OK) st = LOBRA_ERR_HIP;
+    // the source of the copy is the plan's own host image, which lives as long as the plan
+    else if (hipMemcpyAsync(device_mem, p->host_blob.data(), p->blob_bytes, hipMemcpyHostToDevice,
+                            static_cast<hipStream_t>(hip_stream)) != hipSuccess) st = LOBRA_ERR_HIP;
+    if (st != LOBRA_OK) {
+        delete p;
+        return st;
+    }
+    p->dev_blob = device_mem;
+    p->owns_blob = false;
+    *out = p;
+    return LOBRA_OK;
+}
+
 lobra_status lobra_mlora_plan_destroy(lobra_mlora_plan* plan)
 {
     if (!plan) return LOBRA_OK;
     lobra_status st = LOBRA_OK;
-    if (plan->dev_blob && hipFree(plan->dev_blob) != hipSuccess) st = LOBRA_ERR_HIP;
+    if (plan->dev_blob && plan->owns_blob && hipFree(plan->dev_blob) != hipSuccess) st = LOBRA_ERR_HIP;
     delete plan;
     return st;
 }
@@ -217,7 +293,7 @@ lobra_status lobra_mlora_plan_query(const lobra_mlora_plan* plan, int32_t what, 
     return LOBRA_OK;
 }
 
-lobra_status lobra_mlora_fwd(const lobra_mlora_plan* plan, const void* x, const void* W,
+lobra_status lobra_mlora_plan_fwd(const lobra_mlora_plan* plan, const void* x, const void* W,
                              const void* A, const void* B, const float* s, void* y,
                              void* h_save, void* ws, size_t ws_bytes, void* hip_stream)
 {
@@ -225,17 +301,10 @@ lobra_status lobra_mlora_fwd(const lobra_mlora_plan* plan, const void* x, const 
     if (rs != LOBRA_OK) return rs;
     const Plan& p = *plan;
     if (p.desc.T == 0) return LOBRA_OK;
+    rs = fwd_check(p, x, W, A, B, s, y, h_save, ws, ws_bytes);
+    if (rs != LOBRA_OK) return rs;
     const bool adapters = !p.tb.empty();
-    if (!x || !W || !y) return LOBRA_ERR_NULL;
-    if (adapters && (!A || !B || !s)) return LOBRA_ERR_NULL;
-    if (!aligned16(x) || !aligned16(W) || !aligned16(y) || !aligned16(A) || !aligned16(B) ||
-        !aligned16(h_save) || !aligned16(ws))
-        return LOBRA_ERR_ALIGN;
-    void* hbuf = h_save;
-    if (adapters && !hbuf) {
-        if (!ws || ws_bytes < p.fwd_ws_bytes) return LOBRA_ERR_WORKSPACE;
-        hbuf = ws;
-    }
+    void* hbuf = h_save ? h_save : ws;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const PlanDev pd = device_view(p);
     const int dt = p.desc.dtype;
@@ -291,10 +360,10 @@ lobra_status lobra_mlora_fwd_static_ws(const lobra_mlora_plan* plan, const void*
     if (rs != LOBRA_OK) return rs;
     if (plan->fwd_ws_bytes > size_t(LOBRA_STATIC_WS_BYTES)) return LOBRA_ERR_WORKSPACE;
     // the kernels get the array's device address, looked up when the plan was created on this device
-    return lobra_mlora_fwd(plan, x, W, A, B, s, y, nullptr, plan->static_ws, size_t(LOBRA_STATIC_WS_BYTES), hip_stream);
+    return lobra_mlora_plan_fwd(plan, x, W, A, B, s, y, nullptr, plan->static_ws, size_t(LOBRA_STATIC_WS_BYTES), hip_stream);
 }
 
-lobra_status lobra_mlora_bwd(const lobra_mlora_plan* plan, const void* x, const void* W,
+lobra_status lobra_mlora_plan_bwd(const lobra_mlora_plan* plan, const void* x, const void* W,
                              const void* A, const void* B, const float* s, const void* dy,
                              const void* h_saved, void* dx, float* dA, float* dB,
                              uint32_t flags, void* ws, size_t ws_bytes, void* hip_stream)
@@ -302,19 +371,11 @@ lobra_status lobra_mlora_bwd(const lobra_mlora_plan* plan, const void* x, const 
     lobra_status rs = runnable(plan);
     if (rs != LOBRA_OK) return rs;
     const Plan& p = *plan;
+    rs = bwd_check(p, x, W, A, B, s, dy, h_saved, dx, dA, dB, flags, ws, ws_bytes);
+    if (rs != LOBRA_OK) return rs;
     const bool adapters = !p.tb.empty();
     const bool want_dx = !(flags & LOBRA_FLAG_NO_DX);
     const bool accumulate = (flags & LOBRA_FLAG_ACCUMULATE_GRADS) != 0;
-    if (p.R_tot > 0 && (!dA || !dB)) return LOBRA_ERR_NULL;
-    if (p.desc.T > 0) {
-        if (!W || !dy) return LOBRA_ERR_NULL;
-        if (want_dx && !dx) return LOBRA_ERR_NULL;
-        if (adapters && (!x || !A || !B || !s)) return LOBRA_ERR_NULL;
-    }
-    if (!aligned16(x) || !aligned16(W) || !aligned16(A) || !aligned16(B) || !aligned16(dy) ||
-        !aligned16(h_saved) || !aligned16(dx) || !aligned16(dA) || !aligned16(dB) || !aligned16(ws))
-        return LOBRA_ERR_ALIGN;
-    if (p.bwd_ws_bytes > 0 && adapters && (!ws || ws_bytes < p.bwd_ws_bytes)) return LOBRA_ERR_WORKSPACE;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const PlanDev pd = device_view(p);
     const int dt = p.desc.dtype;
@@ -413,7 +474,7 @@ lobra_status lobra_mlora_bwd(const lobra_mlora_plan* plan, const void* x, const 
     return LOBRA_OK;
 }
 
-lobra_status lobra_token_task_map(const lobra_mlora_plan* plan, int32_t* out_task,
+lobra_status lobra_mlora_plan_token_task_map(const lobra_mlora_plan* plan, int32_t* out_task,
                                   int64_t* out_count, void* hip_stream)
 {
     lobra_status rs = runnable(plan);
@@ -422,6 +483,114 @@ lobra_status lobra_token_task_map(const lobra_mlora_plan* plan, int32_t* out_tas
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     LOBRA_LAUNCH(*plan, st, LOBRA_K_TOKEN_TASK, token_task_map(pd, out_task, out_count, st));
     return LOBRA_OK;
+}
+
+// ---- descriptor-taking one-shot forms: the plan of the call is built on the host, its device image is placed
+//      at the start of the caller's workspace by an asynchronous copy on the caller's stream, and the
+//      plan-taking entry point does the rest with what remains of the workspace.
+namespace {
+
+inline size_t align256(size_t v) { return (v + 255) / 256 * 256; }
+
+// Frees a one-shot plan (and with it the host image its upload reads) once the stream has passed the upload.
+void free_oneshot_plan(void* p) { delete static_cast<lobra_mlora_plan*>(p); }
+
+lobra_status release_after(hipStream_t st, lobra_mlora_plan* p)
+{
+    if (hipLaunchHostFunc(st, free_oneshot_plan, p) == hipSuccess) return LOBRA_OK;
+    // no host callback on this stream: wait for the upload instead (slow path, never taken on a plain stream)
+    const hipError_t e = hipStreamSynchronize(st);
+    delete p;
+    return e == hipSuccess ? LOBRA_OK : LOBRA_ERR_HIP;
+}
+
+// Places the device image of one-shot plan `p` at dev (device memory of at least align256(p->blob_bytes) bytes).
+lobra_status upload_oneshot(lobra_mlora_plan* p, void* dev, hipStream_t st)
+{
+    if (hipGetDevice(&p->device) != hipSuccess) return LOBRA_ERR_HIP;
+    if (hipMemcpyAsync(dev, p->host_blob.data(), p->blob_bytes, hipMemcpyHostToDevice, st) != hipSuccess)
+        return LOBRA_ERR_HIP;
+    p->dev_blob = dev;
+    p->owns_blob = false;
+    return LOBRA_OK;
+}
+
+}  // namespace
+
+lobra_status lobra_mlora_workspace_bytes(const lobra_mlora_desc* desc, size_t* fwd_bytes, size_t* bwd_bytes)
+{
+    lobra_mlora_plan* p = nullptr;
+    lobra_status st = make_host_plan(desc, 0, &p);
+    if (st != LOBRA_OK) return st;
+    const size_t img = align256(p->blob_bytes);
+    if (fwd_bytes) *fwd_bytes = img + p->fwd_ws_bytes;
+    if (bwd_bytes) *bwd_bytes = img + p->bwd_ws_bytes;
+    delete p;
+    return LOBRA_OK;
+}
+
+lobra_status lobra_mlora_fwd(const lobra_mlora_desc* desc, const void* x, const void* W, const void* A,
+                             const void* B, const float* s, void* y, void* h_save, void* ws, size_t ws_bytes,
+                             void* hip_stream)
+{
+    lobra_mlora_plan* p = nullptr;
+    lobra_status st = make_host_plan(desc, 0, &p);
+    if (st != LOBRA_OK) return st;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const size_t img = align256(p->blob_bytes);
+    char* rest = static_cast<char*>(ws) + img;
+    if (p->desc.T == 0) st = LOBRA_OK;
+    else if (!ws || ws_bytes < img + (h_save ? 0 : p->fwd_ws_bytes)) st = LOBRA_ERR_WORKSPACE;
+    else if (!aligned16(ws)) st = LOBRA_ERR_ALIGN;
+    else if ((st = fwd_check(*p, x, W, A, B, s, y, h_save, rest, ws_bytes - img)) == LOBRA_OK &&
+             (st = upload_oneshot(p, ws, stream)) == LOBRA_OK) {
+        st = lobra_mlora_plan_fwd(p, x, W, A, B, s, y, h_save, rest, ws_bytes - img, hip_stream);
+        const lobra_status rel = release_after(stream, p);
+        return st != LOBRA_OK ? st : rel;
+    }
+    delete p;
+    return st;
+}
+
+lobra_status lobra_mlora_bwd(const lobra_mlora_desc* desc, const void* x, const void* W, const void* A,
+                             const void* B, const float* s, const void* dy, const void* h_saved, void* dx,
+                             float* dA, float* dB, uint32_t flags, void* ws, size_t ws_bytes, void* hip_stream)
+{
+    lobra_mlora_plan* p = nullptr;
+    lobra_status st = make_host_plan(desc, 0, &p);
+    if (st != LOBRA_OK) return st;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const size_t img = align256(p->blob_bytes);
+    char* rest = static_cast<char*>(ws) + img;
+    if (!ws || ws_bytes < img + p->bwd_ws_bytes) st = LOBRA_ERR_WORKSPACE;
+    else if (!aligned16(ws)) st = LOBRA_ERR_ALIGN;
+    else if ((st = bwd_check(*p, x, W, A, B, s, dy, h_saved, dx, dA, dB, flags, rest, ws_bytes - img)) == LOBRA_OK &&
+             (st = upload_oneshot(p, ws, stream)) == LOBRA_OK) {
+        st = lobra_mlora_plan_bwd(p, x, W, A, B, s, dy, h_saved, dx, dA, dB, flags, rest, ws_bytes - img, hip_stream);
+        const lobra_status rel = release_after(stream, p);
+        return st != LOBRA_OK ? st : rel;
+    }
+    delete p;
+    return st;
+}
+
+lobra_status lobra_token_task_map(const lobra_mlora_desc* desc, int32_t* out_task, int64_t* out_count,
+                                  void* hip_stream)
+{
+    lobra_mlora_plan* p = nullptr;
+    lobra_status st = make_host_plan(desc, 0, &p);
+    if (st != LOBRA_OK) return st;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    void* dev = nullptr;
+    // the call has no workspace argument: the tables go into the library's static device array
+    if (p->blob_bytes > size_t(LOBRA_STATIC_WS_BYTES)) st = LOBRA_ERR_WORKSPACE;
+    else if ((st = static_scratch_address(&dev)) == LOBRA_OK && (st = upload_oneshot(p, dev, stream)) == LOBRA_OK) {
+        st = lobra_mlora_plan_token_task_map(p, out_task, out_count, hip_stream);
+        const lobra_status rel = release_after(stream, p);
+        return st != LOBRA_OK ? st : rel;
+    }
+    delete p;
+    return st;
 }
 
 lobra_status lobra_mlora_adam_step(const lobra_mlora_plan* plan, const lobra_adam_config* cfg,

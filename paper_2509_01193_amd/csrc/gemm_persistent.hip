@@ -398,8 +398,8 @@ void gemm_persistent_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const ui
                     constexpr int q = decltype(q_c)::value;
                     o[q] = (__bf16)acc_read<acc_reg(mb, 2 * p) + q>();
                 });
-#if LOBRA_GP_STORE == 0      // timing variant: only a token store, so that the result is not dead code
-                if (mb == 0 && p == 0)
+#if LOBRA_GP_STORE == 0 || LOBRA_GP_STORE == 3     // timing variants: only a token store (3: on half of the XCDs), so that the result is not dead code
+                if ((mb == 0 && p == 0) || (LOBRA_GP_STORE == 3 && (blockIdx.x & 7) < 4))
                     __builtin_nontemporal_store(o, reinterpret_cast<bf16x8*>(cp + size_t(16 * mb) * ldc + 32 * p));
                 else asm volatile("" : : "v"(o));
 #elif LOBRA_GP_STORE == 2

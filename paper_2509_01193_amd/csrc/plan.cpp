@@ -17,6 +17,14 @@ lobra_status validate(const lobra_mlora_desc* d)
     if (d->dtype != LOBRA_F32 && d->dtype != LOBRA_BF16) return LOBRA_ERR_DTYPE;
     if (d->T < 0 || d->T >= (int64_t(1) << 31)) return LOBRA_ERR_SHAPE;
     if (d->d_in < 1 || d->d_out < 1 || d->n_tasks < 0 || d->S < 0) return LOBRA_ERR_SHAPE;
+    // what the kernels' launch grids and 32-bit offsets inside a tile can address (checked here so that
+    // no call fails after its first launch): widths, and the number of 256 x 256 output tiles
+    if (d->d_in > LOBRA_MAX_WIDTH || d->d_out > LOBRA_MAX_WIDTH) return LOBRA_ERR_SHAPE;
+    {
+        const int64_t tiles_m = (d->T + 255) / 256, tiles_n = (int64_t(d->d_in > d->d_out ? d->d_in : d->d_out) + 255) / 256;
+        if (tiles_m * tiles_n > 0x7fffffff) return LOBRA_ERR_SHAPE;
+    }
+    if (d->dtype == LOBRA_F32 && d->T > kPlainMaxTokens) return LOBRA_ERR_SHAPE;
     if (d->S == 0 && d->T != 0) return LOBRA_ERR_SEGMENTS;
     if (d->dtype == LOBRA_BF16 && (d->d_in % 8 != 0 || d->d_out % 8 != 0)) return LOBRA_ERR_ALIGN;
     if (d->n_proj < 0 || d->n_proj > 16) return LOBRA_ERR_SHAPE;
@@ -49,6 +57,7 @@ lobra_status build_host_plan(const lobra_mlora_desc* d, uint32_t flags, Plan* p)
         p->desc = *d;
         p->flags = flags;
         p->mfma = kMfmaKernels && d->dtype == LOBRA_BF16 && !(flags & LOBRA_PLAN_PLAIN_KERNELS);
+        if (!p->mfma && d->T > kPlainMaxTokens) return LOBRA_ERR_SHAPE;   // the plain kernels' grid
         p->n_proj = d->n_proj > 1 ? d->n_proj : 1;
         p->dg = d->d_out / p->n_proj;
 

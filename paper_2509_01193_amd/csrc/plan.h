@@ -12,6 +12,7 @@ namespace lobra {
 constexpr int kTokenBlock = 32;   // tokens per token block (one MFMA K step of the reductions)
 constexpr int kRowBlock = 32;     // granularity of the row -> segment lookup table
 constexpr bool kMfmaKernels = true;   // bf16 storage runs on the MFMA kernels
+constexpr int64_t kPlainMaxTokens = 65535 * 64;   // the plain kernels put 64-token tiles on grid.y
 
 struct TokenBlock { int32_t row0, nrows, task, rank_row0; };
 struct GradChunk  { int32_t tb_begin, tb_end, task, part_row0; };
@@ -60,6 +61,8 @@ struct Plan {
     // device copy (absent for host-only plans)
     int device = -1;
     void* dev_blob = nullptr;
+    bool owns_blob = false;             // dev_blob came from hipMalloc (plan_create), not from the caller (plan_init)
+    std::vector<int32_t> host_blob;     // what dev_blob holds
     size_t blob_bytes = 0;
     void* static_ws = nullptr;          // this device's copy of the library's static scratch array
     // offsets (in int32 units) of the lists inside the blob

@@ -71,7 +71,7 @@ def check_index_probe(p):
     dp_plan = bd.Plan.for_problem(p)
     out_task = torch.full((max(p.T, 1),), -7, dtype=torch.int32, device="cuda:0")
     out_cnt = torch.full((max(p.n_tasks, 1),), -7, dtype=torch.int64, device="cuda:0")
-    bd.lobra_token_task_map(dp_plan, out_task, out_cnt)
+    bd.lobra_mlora_plan_token_task_map(dp_plan, out_task, out_cnt)
     torch.cuda.synchronize()
     ref = oracle.token_task(p.T, p.seg_off, p.seg_task, p.n_tasks)
     assert np.array_equal(out_task.cpu().numpy()[: p.T], ref)
@@ -242,15 +242,15 @@ def test_empty_batch_and_argument_errors():
     assert not dp.dA.any().item()                 # no tokens: gradients are zero
     p = wl.make_config(1)
     dp = bd.DeviceProblem(p)
-    st = bd.lobra_mlora_fwd(dp.plan, None, dp.W, dp.A, dp.B, dp.s, dp.y, check=False)
+    st = bd.lobra_mlora_plan_fwd(dp.plan, None, dp.W, dp.A, dp.B, dp.s, dp.y, check=False)
     assert st == -1
-    st = bd.lobra_mlora_fwd(dp.plan, dp.x, dp.W, dp.A, dp.B, dp.s, dp.y, None, None, check=False)
+    st = bd.lobra_mlora_plan_fwd(dp.plan, dp.x, dp.W, dp.A, dp.B, dp.s, dp.y, None, None, check=False)
     assert st == -7                               # needs scratch when h_save is not given
-    st = bd.lobra_mlora_bwd(dp.plan, dp.x, dp.W, dp.A, dp.B, dp.s, dp.dy, None, dp.dx, dp.dA, dp.dB,
+    st = bd.lobra_mlora_plan_bwd(dp.plan, dp.x, dp.W, dp.A, dp.B, dp.s, dp.dy, None, dp.dx, dp.dA, dp.dB,
                             0, dp.ws[:64], check=False)
     assert st == -7
     off = dp.x.view(-1)[1:1 + dp.x.numel() - 4]
-    st = bd.lib().lobra_mlora_fwd(dp.plan.handle, off.data_ptr(), dp.W.data_ptr(), dp.A.data_ptr(),
+    st = bd.lib().lobra_mlora_plan_fwd(dp.plan.handle, off.data_ptr(), dp.W.data_ptr(), dp.A.data_ptr(),
                                   dp.B.data_ptr(), dp.s.data_ptr(), dp.y.data_ptr(), None,
                                   dp.ws.data_ptr(), dp.ws.numel(), None)
     assert st == -8
@@ -393,6 +393,101 @@ def test_fwd_bwd_under_hip_graph_capture():
         torch.cuda.synchronize()
         for a, b, name in zip(got, (dp.y, dp.dx, dp.dA, dp.dB), ("y", "dx", "dA", "dB")):
             assert torch.equal(a, b), (rep, name)
+
+
+@pytest.mark.parametrize("which", ["cfg1-f32", "cfg2-bf16-narrow", "adversarial-bf16"])
+def test_one_shot_descriptor_forms_against_the_oracle(which):
+    """lobra_mlora_workspace_bytes / lobra_mlora_fwd / lobra_mlora_bwd / lobra_token_task_map on the descriptor
+    itself: no plan object, the tables travel in the caller's workspace.  Compared with the oracle element by
+    element; the workspace sits between sentinel margins that must survive."""
+    import torch
+    if which == "cfg1-f32":
+        p = wl.make_config(1)
+    elif which == "cfg2-bf16-narrow":
+        p = wl.make_config(2, "shuffled", d_in=384, d_out=256)       # the persistent GEMM and the MFMA rank-r kernels
+    else:
+        seg_off, seg_task = adversarial_tables()["residues"]          # empty and one-token segments, no-adapter spans
+        p = wl.make_custom("one-shot-residues", "bf16", 136, 72, [8, 16, 5, 64], seg_off, seg_task, 21)
+    dp = bd.DeviceProblem(p)                      # only for the uploaded tensors and output buffers
+    d, keep = bd.make_desc(p.dtype, p.T, p.d_in, p.d_out, p.rank_off, p.seg_off, p.seg_task)
+    fwd_b, bwd_b = bd.lobra_mlora_workspace_bytes(d)
+    margin = 4096
+    buf = torch.full((max(fwd_b, bwd_b) + 2 * margin,), 0x5A, dtype=torch.uint8, device="cuda")
+    ws_f, ws_b = buf[margin:margin + fwd_b], buf[margin:margin + bwd_b]
+    for t in (dp.y, dp.dx):
+        t.fill_(7.0)
+    # forward without h_save, backward recomputing the projections
+    bd.lobra_mlora_fwd(d, dp.x, dp.W, dp.A, dp.B, dp.s, dp.y, None, ws_f)
+    bd.lobra_mlora_bwd(d, dp.x, dp.W, dp.A, dp.B, dp.s, dp.dy, None, dp.dx, dp.dA, dp.dB, 0, ws_b)
+    torch.cuda.synchronize()
+    assert bool((buf[:margin] == 0x5A).all()) and bool((buf[margin + max(fwd_b, bwd_b):] == 0x5A).all())
+    o = make_oracle(p)
+    dA, dB = o.grads()
+    tol = TOL[p.dtype]
+    errs = {"y": relerr(dp.host(dp.y), o.y()), "dx": relerr(dp.host(dp.dx), o.dx()),
+            "dA": relerr(dp.host(dp.dA), dA), "dB": relerr(dp.host(dp.dB), dB)}
+    print("one-shot", p.name, {k: "%.2e" % v for k, v in errs.items()}, flush=True)
+    assert all(v <= tol for v in errs.values()), errs
+    # with h_save handed from fwd to bwd: the same results as the plan forms, bit for bit
+    y1, dx1, dA1, dB1 = (t.clone() for t in (dp.y, dp.dx, dp.dA, dp.dB))
+    bd.lobra_mlora_fwd(d, dp.x, dp.W, dp.A, dp.B, dp.s, dp.y, dp.h_save, ws_f)
+    bd.lobra_mlora_bwd(d, dp.x, dp.W, dp.A, dp.B, dp.s, dp.dy, dp.h_save, dp.dx, dp.dA, dp.dB, 0, ws_b)
+    torch.cuda.synchronize()
+    y2, dx2, dA2, dB2 = (t.clone() for t in (dp.y, dp.dx, dp.dA, dp.dB))
+    dp.step()
+    torch.cuda.synchronize()
+    for a, b, c, name in ((y1, y2, dp.y, "y"), (dx1, dx2, dp.dx, "dx"), (dA1, dA2, dp.dA, "dA"), (dB1, dB2, dp.dB, "dB")):
+        assert torch.equal(b, c), name
+        assert torch.equal(a, c), name            # recomputed projections are the same numbers
+    # index probe on the descriptor (its tables go into the library's static device array)
+    out_task = torch.full((p.T,), -7, dtype=torch.int32, device="cuda")
+    out_cnt = torch.full((p.n_tasks,), -7, dtype=torch.int64, device="cuda")
+    bd.lobra_token_task_map(d, out_task, out_cnt)
+    torch.cuda.synchronize()
+    ref = oracle.token_task(p.T, p.seg_off, p.seg_task, p.n_tasks)
+    assert np.array_equal(out_task.cpu().numpy(), ref)
+    assert np.array_equal(out_cnt.cpu().numpy(), np.bincount(ref[ref >= 0], minlength=p.n_tasks))
+
+
+def test_plan_in_caller_memory_and_under_graph_capture():
+    """lobra_mlora_plan_init: the plan's device image lives in a buffer of the caller's (no hipMalloc, no blocking
+    copy); its calls give the results of a lobra_mlora_plan_create plan bit for bit, also as replays of a HIP graph."""
+    import torch
+    p = wl.make_config(3, "shuffled", d_in=256, d_out=384)
+    ref = bd.DeviceProblem(p)
+    ref.step()
+    torch.cuda.synchronize()
+    d, keep = bd.make_desc(p.dtype, p.T, p.d_in, p.d_out, p.rank_off, p.seg_off, p.seg_task)
+    n = bd.plan_device_bytes(d)
+    margin = 1024
+    mem = torch.full((n + 2 * margin,), 0xA5, dtype=torch.uint8, device="cuda")
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        plan = bd.Plan(p.dtype, p.T, p.d_in, p.d_out, p.rank_off, p.seg_off, p.seg_task, device_mem=mem[margin:margin + n],
+                       stream=side)
+        assert (plan.h_save_bytes, plan.fwd_ws_bytes, plan.bwd_ws_bytes) == (ref.plan.h_save_bytes, ref.plan.fwd_ws_bytes,
+                                                                              ref.plan.bwd_ws_bytes)
+        dp = bd.DeviceProblem.__new__(bd.DeviceProblem)
+        dp.__dict__.update(ref.__dict__)
+        dp.plan = plan
+        dp.y, dp.dx, dp.dA, dp.dB = (torch.full_like(t, 3.0) for t in (ref.y, ref.dx, ref.dA, ref.dB))
+        dp.step()                                 # on the stream of the upload, hence behind it
+    torch.cuda.synchronize()
+    assert bool((mem[:margin] == 0xA5).all()) and bool((mem[margin + n:] == 0xA5).all())
+    for a, b, name in ((dp.y, ref.y, "y"), (dp.dx, ref.dx, "dx"), (dp.dA, ref.dA, "dA"), (dp.dB, ref.dB, "dB")):
+        assert torch.equal(a, b), name
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            dp.step()
+    for rep in range(2):
+        for t in (dp.y, dp.dx, dp.dA, dp.dB):
+            t.fill_(-1.0)
+        g.replay()
+        torch.cuda.synchronize()
+        for a, b, name in ((dp.y, ref.y, "y"), (dp.dx, ref.dx, "dx"), (dp.dA, ref.dA, "dA"), (dp.dB, ref.dB, "dB")):
+            assert torch.equal(a, b), (rep, name)
+    plan.close()
 
 
 def test_shared_input_projection_fusion_through_the_same_entry_point():

@@ -70,10 +70,92 @@ def test_validate_null_tables_and_empty_batch():
 def test_host_only_plan_cannot_run():
     p = wl.make_config(1, fill=False)
     plan = bd.Plan.for_problem(p, bd.PLAN_HOST_ONLY)
-    st = bd.lib().lobra_mlora_fwd(plan.handle, None, None, None, None, None, None, None, None, 0, None)
+    st = bd.lib().lobra_mlora_plan_fwd(plan.handle, None, None, None, None, None, None, None, None, 0, None)
     assert st == -10
-    assert bd.lib().lobra_mlora_fwd(None, None, None, None, None, None, None, None, None, 0, None) == -10
+    assert bd.lib().lobra_mlora_plan_fwd(None, None, None, None, None, None, None, None, None, 0, None) == -10
     assert bd.lib().lobra_mlora_plan_destroy(None) == 0
+
+
+def test_shape_limits_are_reported_before_any_launch():
+    """Launch grids and 32-bit tile offsets bound the shapes; the bounds are argument errors of validate /
+    plan_create / the one-shot calls, not launch failures in the middle of a call."""
+    big = (1 << 20) + 8
+    for kw in (dict(dtype="bf16", d_in=big, d_out=16), dict(dtype="bf16", d_in=16, d_out=big),
+               dict(dtype="f32", d_in=big)):
+        d, keep = _desc(**kw)
+        assert bd.validate(d) == -2, kw
+    # number of 256 x 256 output tiles
+    T = (1 << 31) - 256
+    d, keep = bd.make_desc("bf16", T, 1 << 20, 8, None, [0, T], [-1])
+    assert bd.validate(d) == -2
+    d, keep = bd.make_desc("bf16", T, 1024, 8, None, [0, T], [-1])
+    assert bd.validate(d) == 0
+    # the plain kernels put 64-token tiles on grid.y: fp32 storage, and bf16 under LOBRA_PLAN_PLAIN_KERNELS
+    T = 65535 * 64 + 1
+    d, keep = bd.make_desc("f32", T, 8, 8, None, [0, T], [-1])
+    assert bd.validate(d) == -2
+    d, keep = bd.make_desc("bf16", T, 8, 8, None, [0, T], [-1])
+    assert bd.validate(d) == 0
+    h = ctypes.c_void_p()
+    assert bd.lib().lobra_mlora_plan_create(ctypes.byref(d), bd.PLAN_HOST_ONLY | bd.PLAN_PLAIN_KERNELS, ctypes.byref(h)) == -2
+    assert bd.lib().lobra_mlora_plan_create(ctypes.byref(d), bd.PLAN_HOST_ONLY, ctypes.byref(h)) == 0
+    assert bd.lib().lobra_mlora_plan_destroy(h) == 0
+
+
+def test_workspace_bytes_and_one_shot_argument_errors():
+    """lobra_mlora_workspace_bytes is host only; the one-shot calls report descriptor and workspace errors
+    before they touch the device (so all of this runs without a GPU)."""
+    p = wl.make_config(1, fill=False)
+    d, keep = bd.make_desc(p.dtype, p.T, p.d_in, p.d_out, p.rank_off, p.seg_off, p.seg_task)
+    fwd, bwd = bd.lobra_mlora_workspace_bytes(d)
+    plan = bd.Plan.for_problem(p, bd.PLAN_HOST_ONLY)
+    img = bd.plan_device_bytes(d)
+    assert img > 0 and img % 4 == 0
+    img256 = (img + 255) // 256 * 256
+    assert fwd == img256 + plan.fwd_ws_bytes and bwd == img256 + plan.bwd_ws_bytes
+    L = bd.lib()
+    a = ctypes.c_size_t()
+    assert L.lobra_mlora_workspace_bytes(None, ctypes.byref(a), None) == -1
+    assert L.lobra_mlora_workspace_bytes(ctypes.byref(d), None, None) == 0
+    assert L.lobra_mlora_plan_device_bytes(ctypes.byref(d), 0, None) == -1
+    bad, keep2 = _desc(seg_off=[0, 4, 9])
+    assert L.lobra_mlora_workspace_bytes(ctypes.byref(bad), ctypes.byref(a), None) == -4
+    one = ctypes.c_void_p(0x1000)                       # a non-NULL, aligned pointer that is never dereferenced
+    # descriptor errors come first
+    assert L.lobra_mlora_fwd(ctypes.byref(bad), one, one, one, one, one, one, None, one, 1 << 30, None) == -4
+    assert L.lobra_mlora_bwd(ctypes.byref(bad), one, one, one, one, one, one, None, one, one, one, 0, one, 1 << 30, None) == -4
+    assert L.lobra_token_task_map(ctypes.byref(bad), one, one, None) == -4
+    assert L.lobra_mlora_fwd(None, one, one, one, one, one, one, None, one, 1 << 30, None) == -1
+    # then the workspace: missing, too small (one byte short), misaligned
+    assert L.lobra_mlora_fwd(ctypes.byref(d), one, one, one, one, one, one, None, None, 0, None) == -7
+    assert L.lobra_mlora_fwd(ctypes.byref(d), one, one, one, one, one, one, None, one, fwd - 1, None) == -7
+    assert L.lobra_mlora_bwd(ctypes.byref(d), one, one, one, one, one, one, None, one, one, one, 0, one, bwd - 1, None) == -7
+    assert L.lobra_mlora_fwd(ctypes.byref(d), one, one, one, one, one, one, None, ctypes.c_void_p(0x1004), fwd, None) == -8
+    # then the tensors: a missing one, a misaligned one
+    assert L.lobra_mlora_fwd(ctypes.byref(d), None, one, one, one, one, one, None, one, fwd, None) == -1
+    assert L.lobra_mlora_fwd(ctypes.byref(d), ctypes.c_void_p(0x1008), one, one, one, one, one, None, one, fwd, None) == -8
+    assert L.lobra_mlora_bwd(ctypes.byref(d), one, one, one, one, one, None, None, one, one, one, 0, one, bwd, None) == -1
+    # an empty batch is a no-op that needs nothing
+    e, keep3 = bd.make_desc("f32", 0, 8, 8, None, None, None)
+    assert L.lobra_mlora_fwd(ctypes.byref(e), None, None, None, None, None, None, None, None, 0, None) == 0
+
+
+def test_plan_init_argument_errors():
+    """The errors of lobra_mlora_plan_init that precede its first HIP call."""
+    p = wl.make_config(1, fill=False)
+    d, keep = bd.make_desc(p.dtype, p.T, p.d_in, p.d_out, p.rank_off, p.seg_off, p.seg_task)
+    L = bd.lib()
+    h = ctypes.c_void_p()
+    n = bd.plan_device_bytes(d)
+    one = ctypes.c_void_p(0x1000)
+    assert L.lobra_mlora_plan_init(ctypes.byref(d), 0, one, n, None, None) == -1
+    assert L.lobra_mlora_plan_init(ctypes.byref(d), bd.PLAN_HOST_ONLY, one, n, None, ctypes.byref(h)) == -10
+    assert L.lobra_mlora_plan_init(ctypes.byref(d), 0, None, n, None, ctypes.byref(h)) == -7
+    assert L.lobra_mlora_plan_init(ctypes.byref(d), 0, one, n - 1, None, ctypes.byref(h)) == -7
+    assert L.lobra_mlora_plan_init(ctypes.byref(d), 0, ctypes.c_void_p(0x1004), n, None, ctypes.byref(h)) == -8
+    bad, keep2 = _desc(rank_off=[0, 0, 5])
+    assert L.lobra_mlora_plan_init(ctypes.byref(bad), 0, one, 1 << 20, None, ctypes.byref(h)) == -6
+    assert not h.value
 
 
 def brute_force_lists(p):

@@ -1,5 +1,5 @@
 """lobra_mlora_fwd_static_ws (the forward pass whose scratch is the library's static device array)
-against lobra_mlora_fwd with a caller workspace, through the C ABI: same kernels, so y must be bit
+against lobra_mlora_plan_fwd with a caller workspace, through the C ABI: same kernels, so y must be bit
 for bit the same, and within the layer's tolerance of the fp64 oracle.  Two calls in a row on the
 same GPU, the second on a smaller batch (the array keeps the first call's contents).
 """
@@ -20,7 +20,7 @@ def _run_both(p):
     dp = bd.DeviceProblem(p)
     assert 0 < dp.plan.fwd_ws_bytes <= bd.STATIC_WS_BYTES
     dp.y.fill_(7.0)
-    bd.lobra_mlora_fwd(dp.plan, dp.x, dp.W, dp.A, dp.B, dp.s, dp.y, None, dp.ws)
+    bd.lobra_mlora_plan_fwd(dp.plan, dp.x, dp.W, dp.A, dp.B, dp.s, dp.y, None, dp.ws)
     torch.cuda.synchronize()
     y_ref = dp.y.clone()
     dp.y.fill_(-3.0)
