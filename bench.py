@@ -21,9 +21,55 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_FP32_TFLOPS = 157.3      # MI355X fp32 vector
 PEAK_HBM_GBS = 8000.0
-# measured on this chip with random bf16 operands and nothing but back-to-back 16x16x32 MFMAs (the shape
-# the GEMM uses; 32x32x16 blocks: 1790): what the matrix cores sustain under the power limit (context for `frac`)
-MFMA_ONLY_SUSTAINED_TFLOPS = 2050.0
+COLD_SETS = 3                 # independent (x, dy, y, dx) sets the cold figures rotate over
+
+
+def measure_ceilings(torch, read_bytes):
+    """What this chip sustains, measured here and now with the bench-only kernels of liblobra_ceilings.so: a loop
+    of nothing but the GEMM's MFMA (random bf16 operands), and a streaming read / copy - of a buffer as large as
+    one activation tensor, read again and again (it stays in the 256 MB infinity cache, like the inputs of the
+    warm steps), and of a 1 GiB buffer (which does not)."""
+    import ctypes
+    path = os.path.join(ROOT, "paper_2509_01193_amd", "liblobra_ceilings.so")
+    if not os.path.exists(path):
+        raise FileNotFoundError(path + " is missing: build it with `python -m paper_2509_01193_amd.build`")
+    L = ctypes.CDLL(path)
+    vp = ctypes.c_void_p
+    L.lobra_ceiling_mfma.argtypes = [vp, vp, ctypes.c_int, ctypes.c_int, vp]
+    L.lobra_ceiling_read.argtypes = [vp, ctypes.c_size_t, vp, ctypes.c_int, vp]
+    L.lobra_ceiling_copy.argtypes = [vp, vp, ctypes.c_size_t, ctypes.c_int, vp]
+    dev = torch.device("cuda:0")
+    st = vp(torch.cuda.current_stream().cuda_stream)
+    ncu = torch.cuda.get_device_properties(0).multi_processor_count
+
+    def t_of(fn, reps=5, warm=2):
+        for _ in range(warm):
+            assert fn() == 0
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            assert fn() == 0
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps * 1e-3
+
+    ops = (torch.randn(64 * 64 * 8, device=dev) * 0.5).to(torch.bfloat16)       # 64 KiB of operands
+    out = torch.empty(ncu * 256, dtype=torch.float32, device=dev)
+    iters = 4000
+    sec = t_of(lambda: L.lobra_ceiling_mfma(vp(ops.data_ptr()), vp(out.data_ptr()), ncu, iters, st))
+    res = {"mfma_only_measured_tflops": ncu * 4 * iters * 64 * 2.0 * 16 * 16 * 32 / sec / 1e12}
+    sink = torch.zeros(4, dtype=torch.int32, device=dev)
+    wgs = ncu * 8
+    n = max(read_bytes // 16 * 16, 1 << 20)
+    a = torch.randint(0, 255, (n,), dtype=torch.uint8, device=dev)
+    b = torch.empty_like(a)
+    big = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_(0, 255)
+    res["stream_read_warm_measured_gbs"] = n / t_of(lambda: L.lobra_ceiling_read(vp(a.data_ptr()), n, vp(sink.data_ptr()), wgs, st), 10, 3) / 1e9
+    res["stream_read_cold_measured_gbs"] = (1 << 30) / t_of(lambda: L.lobra_ceiling_read(vp(big.data_ptr()), 1 << 30, vp(sink.data_ptr()), wgs, st), 4, 1) / 1e9
+    res["stream_copy_measured_gbs"] = 2.0 * n / t_of(lambda: L.lobra_ceiling_copy(vp(a.data_ptr()), vp(b.data_ptr()), n, wgs, st), 10, 3) / 1e9
+    res["stream_buffer_bytes"] = n
+    return res
 
 
 def cpu_baseline(p, budget_rows):
@@ -222,6 +268,8 @@ def main():
         print(json.dumps({"pmc_probe": True, "copy_bytes_each_way": dp.x.numel() * dp.x.element_size()}))
         return
 
+    ceilings = measure_ceilings(torch, p.T * p.d_in * (2 if p.dtype == "bf16" else 4))
+
     def timed(fn, steps, warmup):
         for _ in range(warmup):
             fn()
@@ -237,43 +285,77 @@ def main():
         return wall, e0.elapsed_time(e1) / steps
 
     ms_wall_eager, ms_ev_eager = timed(dp.step, a.steps, a.warmup)
+    # A training loop captures far more than one layer's step in a HIP graph (a whole stack of LoRA linears), so
+    # the cost of starting a replay is spread over many kernels.  Here a graph holds `spg` steps (the largest
+    # divisor of --steps up to 10) and is replayed steps / spg times: exactly --steps steps are timed.
+    spg = max(g for g in range(1, 11) if a.steps % g == 0)
+
+    def step_graph(q, n):
+        q.step()
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(g, stream=side):
+                for _ in range(n):
+                    q.step()
+        torch.cuda.synchronize()
+        return g
     if a.no_graph:
         ms_wall, ms_ev = ms_wall_eager, ms_ev_eager
     else:
-        # one step (fwd + bwd, all kernels) captured once and replayed: the launch path of a training
-        # loop that does not want to pay host launch latency between dependent kernels
-        graph, side = torch.cuda.CUDAGraph(), torch.cuda.Stream()
-        with torch.cuda.stream(side):
-            with torch.cuda.graph(graph, stream=side):
-                dp.step()
-        torch.cuda.synchronize()
-        ms_wall, ms_ev = timed(graph.replay, a.steps, a.warmup)
+        side = torch.cuda.Stream()
+        wall, ev = timed(step_graph(dp, spg).replay, a.steps // spg, -(-a.warmup // spg))
+        ms_wall, ms_ev = wall / spg, ev / spg
 
     # the same library with no adapters: base GEMM time, for the LoRA overhead figure
     base = dp.base_only()
     if a.no_graph:
-        ms_base_wall, ms_base = timed(base.step, max(a.steps // 2, 1), min(a.warmup, 3))
+        ms_base_wall, ms_base = timed(base.step, a.steps, min(a.warmup, 3))
     else:
-        base.step()
-        torch.cuda.synchronize()
-        bgraph = torch.cuda.CUDAGraph()
-        with torch.cuda.stream(side):
-            with torch.cuda.graph(bgraph, stream=side):
-                base.step()
-        torch.cuda.synchronize()
-        ms_base_wall, ms_base = timed(bgraph.replay, max(a.steps // 2, 1), min(a.warmup, 3))
+        ms_base_wall, ms_base = (t / spg for t in timed(step_graph(base, spg).replay, a.steps // spg, -(-min(a.warmup, 3) // spg)))
 
     # per-kernel durations from HIP events on the launch stream, over `steps` more passes
     tr = bd.LaunchTrace(dp.plan, 32)
-    per = {}
-    for _ in range(a.steps):
-        tr.attach()
-        dp.step()
-        torch.cuda.synchronize()
-        for name, ms in tr.durations():
-            per.setdefault(name, []).append(ms)
+
+    def traced(problems):
+        per = {}
+        for i in range(a.steps):
+            tr.attach()
+            problems[i % len(problems)].step()
+            torch.cuda.synchronize()
+            for name, ms in tr.durations():
+                per.setdefault(name, []).append(ms)
+        return {k: {"launches_per_step": len(v) // a.steps, "avg_ms": float(np.mean(v))} for k, v in per.items()}
+    kern = traced([dp])
+
+    # the same with inputs that no cache holds: the step rotates over COLD_SETS independent sets of x, dy, y, dx
+    # (in a model every layer's activations are new; at workload 2 one set is 0.5 GB, twice the infinity cache)
+    sets = [dp] + [dp.clone_io() for _ in range(COLD_SETS - 1)]
+    bases = [q.base_only() for q in sets]
+    kern_cold = traced(sets)
     tr.close()
-    kern = {k: {"launches_per_step": len(v) // a.steps, "avg_ms": float(np.mean(v))} for k, v in per.items()}
+    if a.no_graph:
+        def rot(qs):
+            def f():
+                for q in qs:
+                    q.step()
+            return f
+        ms_cold = timed(rot(sets), max(a.steps // COLD_SETS, 1), min(a.warmup, 2))[1] / COLD_SETS
+        ms_base_cold = timed(rot(bases), max(a.steps // COLD_SETS, 1), min(a.warmup, 2))[1] / COLD_SETS
+    else:
+        def rot_graph(qs):
+            for q in qs:
+                q.step()
+            torch.cuda.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.stream(side):
+                with torch.cuda.graph(g, stream=side):
+                    for q in qs:
+                        q.step()
+            torch.cuda.synchronize()
+            return g
+        ms_cold = timed(rot_graph(sets).replay, max(a.steps // COLD_SETS, 1), min(a.warmup, 2))[1] / COLD_SETS
+        ms_base_cold = timed(rot_graph(bases).replay, max(a.steps // COLD_SETS, 1), min(a.warmup, 2))[1] / COLD_SETS
 
     # outside the step: the optimiser update that follows it, and the cost of building a batch plan
     extras = {}
@@ -298,13 +380,16 @@ def main():
     # dominant kernel: the fused GEMM (two launches per step: y and dx)
     gemm_flops = 0.5 * (4.0 * p.T * p.d_in * p.d_out + 2.0 * tok_rank * (p.d_in + p.d_out))
     gemm_ms = kern.get("gemm", {}).get("avg_ms", float("nan"))
+    gemm_ms_cold = kern_cold.get("gemm", {}).get("avg_ms", float("nan"))
     peak = PEAK_BF16_TFLOPS if p.dtype == "bf16" else PEAK_FP32_TFLOPS
     achieved = gemm_flops / (gemm_ms * 1e-3) / 1e12
     roofline = {"bound": "mfma" if p.dtype == "bf16" else "alu", "kernel": "gemm (base product + fused up projection)",
                 "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
                 "traffic": read_traffic("cfg%d" % a.config), "avg_launch_ms": gemm_ms,
                 "flops_per_launch": gemm_flops,
-                "mfma_only_sustained_tflops": MFMA_ONLY_SUSTAINED_TFLOPS if p.dtype == "bf16" else None}
+                "frac_cold": gemm_flops / (gemm_ms_cold * 1e-3) / 1e12 / peak, "avg_launch_ms_cold": gemm_ms_cold,
+                # a loop of nothing but this kernel's MFMA, measured in this process before the timed region
+                "mfma_only_measured_tflops": ceilings["mfma_only_measured_tflops"] if p.dtype == "bf16" else None}
     esz = 2 if p.dtype == "bf16" else 4
     skinny = {}
     # each of the two rank-r stages reads x once and dy once per step (algorithmic bytes); `traffic` is
@@ -313,8 +398,15 @@ def main():
         if name in kern and kern[name]["launches_per_step"] > 0:
             per_launch = float(esz) * p.T * (p.d_in + p.d_out) / kern[name]["launches_per_step"]
             gbs = per_launch / (kern[name]["avg_ms"] * 1e-3) / 1e9
+            gbs_cold = per_launch / (kern_cold[name]["avg_ms"] * 1e-3) / 1e9
             skinny[name] = {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                             "frac": gbs / PEAK_HBM_GBS, "avg_launch_ms": kern[name]["avg_ms"],
+                            "achieved_cold": gbs_cold, "frac_cold": gbs_cold / PEAK_HBM_GBS,
+                            "avg_launch_ms_cold": kern_cold[name]["avg_ms"],
+                            # a plain streaming read measured in this process: of a buffer this size that stays
+                            # in the infinity cache, and of 1 GiB that does not
+                            "stream_read_measured_gbs": ceilings["stream_read_warm_measured_gbs"],
+                            "stream_read_cold_measured_gbs": ceilings["stream_read_cold_measured_gbs"],
                             "bytes_per_launch": per_launch,
                             "traffic": read_traffic("cfg%d" % a.config, "TRAFFIC_%s_BYTES_PER_LAUNCH" % name.upper())}
     out = {
@@ -322,7 +414,8 @@ def main():
         "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms_wall,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": p.dtype, "data": "synthetic",
-        "launch": "eager" if a.no_graph else "hip_graph_replay", "ms_per_step_eager": ms_wall_eager,
+        "launch": "eager" if a.no_graph else "hip_graph_replay", "steps_per_graph": 1 if a.no_graph else spg,
+        "ms_per_step_eager": ms_wall_eager,
         "config": {"workload": p.name, "T": p.T, "d_in": p.d_in, "d_out": p.d_out,
                    "n_tasks": p.n_tasks, "ranks": sorted(set(int(r) for r in p.ranks)),
                    "segments": p.S, "order": a.order, **layout_info},
@@ -330,6 +423,10 @@ def main():
         "pct_of_peak": 100.0 * flops / (ms_wall * 1e-3) / 1e12 / peak,
         "ms_per_step_events": ms_ev, "ms_base_only": ms_base,
         "lora_overhead_pct": 100.0 * (ms_ev - ms_base) / ms_base,
+        "ms_per_step_cold": ms_cold, "ms_base_only_cold": ms_base_cold,
+        "lora_overhead_pct_cold": 100.0 * (ms_cold - ms_base_cold) / ms_base_cold,
+        "tokens_per_s_cold": real_tokens / (ms_cold * 1e-3), "cold_sets": COLD_SETS,
+        "ceilings": ceilings, "kernels_cold": kern_cold,
         "kernels": kern, "skinny_hbm": skinny, "extras": extras, "roofline": roofline,
         "setup_s": time.perf_counter() - t0,
     }

@@ -100,7 +100,9 @@ typedef struct {
     int32_t dtype;           /* lobra_dtype of x, W, A, B, y, dy, dx */
     int32_t d_in, d_out;     /* 1 .. LOBRA_MAX_WIDTH; multiples of 8 for LOBRA_BF16 */
     int64_t T;               /* packed tokens, 0 <= T < 2^31 (fp32 and LOBRA_PLAN_PLAIN_KERNELS: T <= 4194240);
-                                ceil(T / 256) * ceil(max(d_in, d_out) / 256) < 2^31 */
+                                ceil(T / 256) * ceil(max(d_in, d_out) / 256) < 2^31, and with adapters
+                                ceil(T / 2048) * (d_in + d_out) / 64 < 2^31 roughly (exactly: reduction chunks x
+                                64-column tiles; plan creation and the one-shot calls report LOBRA_ERR_SHAPE) */
     int32_t n_tasks;         /* >= 0; 0 = base product only */
     int32_t S;               /* segments, >= 0 (S = 0 requires T = 0) */
     const int32_t *rank_off; /* [n_tasks+1], rank_off[0] = 0, r_t = rank_off[t+1]-rank_off[t] */

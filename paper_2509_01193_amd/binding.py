@@ -371,6 +371,17 @@ class DeviceProblem:
         self.fwd(True)
         self.bwd(True)
 
+    def clone_io(self):
+        """The same layer and batch (plan, W, A, B, s, scratch shared) on its own copies of x and dy and its own
+        outputs: benchmarks rotate over several of these so that no call finds its inputs in a cache."""
+        torch = self.torch
+        o = DeviceProblem.__new__(DeviceProblem)
+        o.__dict__.update(self.__dict__)
+        o.x, o.dy = self.x.clone(), self.dy.clone()
+        o.y, o.dx = torch.empty_like(self.y), torch.empty_like(self.dx)
+        o.dA, o.dB = torch.zeros_like(self.dA), torch.zeros_like(self.dB)
+        return o
+
     def base_only(self):
         """The same x, W, dy, y, dx under a plan without adapters: the base products alone."""
         torch, p = self.torch, self.p

@@ -14,6 +14,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblobra_mlora.so")
+CSRC_BENCH = os.path.join(HERE, "csrc_bench")                 # bench-only kernels (measured ceilings): their own library
+LIB_CEILINGS = os.path.join(HERE, "liblobra_ceilings.so")
 OBJ = os.path.join(HERE, "_build")
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
@@ -70,5 +72,20 @@ def build(force: bool = True, verbose: bool = False, defines=(), out: str = LIB,
     return out
 
 
+def build_ceilings(verbose: bool = False, out: str = LIB_CEILINGS) -> str:
+    """The bench-only library of csrc_bench/ (never linked into, or loaded by, the product library)."""
+    srcs = sorted(os.path.join(CSRC_BENCH, f) for f in os.listdir(CSRC_BENCH) if f.endswith(".hip"))
+    tmp = out + ".tmp%d" % os.getpid()
+    cmd = [HIPCC] + FLAGS + ["-shared", "-x", "hip"] + srcs + ["-o", tmp]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("hipcc failed for %s:\n%s\n%s" % (srcs, r.stdout, r.stderr))
+    os.replace(tmp, out)
+    return out
+
+
 if __name__ == "__main__":
     print(build(force="--incremental" not in sys.argv, verbose=True))
+    print(build_ceilings(verbose=True))

@@ -138,9 +138,12 @@ lobra_status build_host_plan(const lobra_mlora_desc* d, uint32_t flags, Plan* p)
             for (int32_t t = 0; t < n; ++t)
                 for (int32_t b = p->task_tb_off[t]; b < p->task_tb_off[t + 1]; b += g)
                     p->sb_off.push_back(std::min(b + g, p->task_tb_off[t + 1]));
-            // 3c. launch order by descending rank.  A workgroup's cost grows with its task's rank (the
-            //     adapter rows it reads next to its 32 token rows), and the lists above are in task
-            //     order, so with mixed ranks whichever task comes last would make up the launch's tail.
+            // 3c. launch order of the projection's workgroups by descending rank.  A workgroup's cost grows with
+            //     its task's rank (the adapter rows it reads next to its 32 token rows), and the lists above are
+            //     in task order, so with mixed ranks whichever task comes last would make up the launch's tail.
+            //     (Inside a rank the stored, task-grouped order stays: ordering the blocks by their position in
+            //     the batch as well measured 2 us slower on the shuffled workload 2, although the kernels deal
+            //     their work items to the XCDs in contiguous ranges.)
             auto by_rank = [&](size_t count, auto task_of, std::vector<int32_t>& order) {
                 order.resize(count);
                 for (size_t i = 0; i < count; ++i) order[i] = int32_t(i);
@@ -176,6 +179,10 @@ lobra_status build_host_plan(const lobra_mlora_desc* d, uint32_t flags, Plan* p)
             }
             p->task_chunk_off[t + 1] = int32_t(p->chunks.size());
         }
+
+        // (the reduction kernels put chunks x column tiles of at least 64 columns on grid.x)
+        if (int64_t(p->chunks.size()) * ((int64_t(d->d_in) + 63) / 64 + (int64_t(d->d_out) + 63) / 64) > 0x7fffffff)
+            return LOBRA_ERR_SHAPE;
 
         // 5. buffer sizes
         BufferLayout& L = p->p_layout;

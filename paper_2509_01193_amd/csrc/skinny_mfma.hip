@@ -8,6 +8,13 @@
 // each task of the fused batch has its own pair.)
 #include "kernels.h"
 
+#ifndef LOBRA_SHRINK_PROBE
+#define LOBRA_SHRINK_PROBE 0    // timing variants: 1 adapter rows always from the first slab, 2 (almost) no stores
+#endif
+#ifndef LOBRA_SKINNY_XCD
+#define LOBRA_SKINNY_XCD 1      // work items dealt to the XCDs in contiguous ranges (see xcd_contiguous)
+#endif
+
 namespace lobra {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -56,14 +63,17 @@ __global__ __launch_bounds__(64 * NWV) void shrink_mfma_kernel(PlanDev pd, const
     // that projection's column block of dy (row pitch ldz), M its rows of the compact up factors,
     // and the task's rank rows it reads and writes are the window [proj r, (proj + 1) r).
     __shared__ float red[NWV][2][NRB][64][4];   // [wave][token half][rank block][lane][4]
-    const int32_t bi = pd.tb_order ? pd.tb_order[blockIdx.x] : int32_t(blockIdx.x);
+    const int32_t wi = LOBRA_SKINNY_XCD ? xcd_contiguous(blockIdx.x, gridDim.x) : int32_t(blockIdx.x);
+    const int32_t bi = pd.tb_order ? pd.tb_order[wi] : wi;
     const TokenBlock b = pd.tb[bi];
     const int32_t r = (pd.rank_off[b.task + 1] - b.rank_row0) / nproj;
     const int32_t pofs = proj * r;               // first rank of the window inside the task's rows
     const int32_t rank_row0 = b.rank_row0 + pofs;
     const int32_t plim = proj == nproj - 1 ? pd.r_pad - pofs : r;   // ranks (and zero padding) stored by this launch
     const int32_t nrb_t = (r + 15) >> 4;        // rank blocks this task needs (uniform)
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    // (the wave number as a scalar: the loops below then branch on scalars, and the compiler can count the
+    //  loads in flight instead of draining them at every join of divergent paths)
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int j = lane & 15, kg = lane >> 4;
     const u32x4 zero4 = {0u, 0u, 0u, 0u};
 
@@ -94,7 +104,7 @@ __global__ __launch_bounds__(64 * NWV) void shrink_mfma_kernel(PlanDev pd, const
 #pragma unroll
                 for (int rb = 0; rb < NRB; ++rb)
                     if (NRB == 1 || rb < nrb_t)
-                        sl.mv[rb][q] = *reinterpret_cast<const u32x4*>(mrow[rb] + k + 32 * q);
+                        sl.mv[rb][q] = *reinterpret_cast<const u32x4*>(mrow[rb] + (LOBRA_SHRINK_PROBE == 1 ? 8 * kg : k) + 32 * q);
 #pragma unroll
                 for (int h = 0; h < 2; ++h)
                     sl.zv[h][q] = *reinterpret_cast<const u32x4*>(zrow[h] + k + 32 * q);
@@ -124,19 +134,57 @@ __global__ __launch_bounds__(64 * NWV) void shrink_mfma_kernel(PlanDev pd, const
                         acc[h][rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
                             as_bf16x8(sl.mv[rb][q]), as_bf16x8(sl.zv[h][q]), acc[h][rb], 0, 0, 0);
     };
-    // DEPTH slabs in flight per wave: the loads of slab i + DEPTH - 1 are issued before the MFMAs
-    // of slab i (DEPTH = 1: load, then multiply).
     const int32_t nsl = (D + 127) >> 7;
-    Slab buf[DEPTH];
+    if (DEPTH == 3 && (D & 127) == 0) {
+        // Whole slabs only: this wave's slabs are wave, wave + NWV, ...; three of them are in flight (the loads
+        // of slab t + 2 are issued before the MFMAs of slab t), three slabs per trip so that the register sets
+        // rotate without copies, and not a branch in the trip.
+        const int32_t n_my = (nsl - wave + NWV - 1) / NWV;
+        auto slab_of = [&](int32_t t) { return (wave + NWV * t) << 7; };
+        auto load_full = [&](Slab& sl, int32_t slab) {
+            const int32_t k = slab + 8 * kg;
 #pragma unroll
-    for (int d = 0; d < DEPTH - 1; ++d)
-        if (wave + NWV * d < nsl) load(buf[d], (wave + NWV * d) << 7);
-    for (int32_t i = wave; i < nsl; i += NWV * DEPTH) {
+            for (int q = 0; q < 4; ++q) {
 #pragma unroll
-        for (int d = 0; d < DEPTH; ++d) {
-            const int32_t nx = i + NWV * (d + DEPTH - 1);
-            if (nx < nsl) load(buf[(d + DEPTH - 1) % DEPTH], nx << 7);
-            if (i + NWV * d < nsl) mac(buf[d]);
+                for (int rb = 0; rb < NRB; ++rb)
+                    if (NRB == 1 || rb < nrb_t) sl.mv[rb][q] = *reinterpret_cast<const u32x4*>(mrow[rb] + k + 32 * q);
+#pragma unroll
+                for (int h = 0; h < 2; ++h) sl.zv[h][q] = *reinterpret_cast<const u32x4*>(zrow[h] + k + 32 * q);
+            }
+        };
+        Slab b0, b1, b2;
+        if (n_my > 0) load_full(b0, slab_of(0));
+        if (n_my > 1) load_full(b1, slab_of(1));
+        int32_t t = 0;
+        for (; t + 5 <= n_my; t += 3) {
+            load_full(b2, slab_of(t + 2));
+            mac(b0);
+            load_full(b0, slab_of(t + 3));
+            mac(b1);
+            load_full(b1, slab_of(t + 4));
+            mac(b2);
+        }
+        // two to four slabs are left; b0 and b1 hold the first two of them
+        if (t + 2 < n_my) load_full(b2, slab_of(t + 2));
+        if (t < n_my) mac(b0);
+        if (t + 3 < n_my) load_full(b0, slab_of(t + 3));
+        if (t + 1 < n_my) mac(b1);
+        if (t + 2 < n_my) mac(b2);
+        if (t + 3 < n_my) mac(b0);
+    } else {
+        // DEPTH slabs in flight per wave: the loads of slab i + DEPTH - 1 are issued before the MFMAs
+        // of slab i (DEPTH = 1: load, then multiply).
+        Slab buf[DEPTH];
+#pragma unroll
+        for (int d = 0; d < DEPTH - 1; ++d)
+            if (wave + NWV * d < nsl) load(buf[d], (wave + NWV * d) << 7);
+        for (int32_t i = wave; i < nsl; i += NWV * DEPTH) {
+#pragma unroll
+            for (int d = 0; d < DEPTH; ++d) {
+                const int32_t nx = i + NWV * (d + DEPTH - 1);
+                if (nx < nsl) load(buf[(d + DEPTH - 1) % DEPTH], nx << 7);
+                if (i + NWV * d < nsl) mac(buf[d]);
+            }
         }
     }
     // cross-wave sum through LDS, then lane (token j, rank group kg) of wave 0/1 stores half h
@@ -165,7 +213,7 @@ __global__ __launch_bounds__(64 * NWV) void shrink_mfma_kernel(PlanDev pd, const
                 o[v] = (__bf16)((p < r && tok < b.nrows) ? st * sum : 0.f);
             }
             const int32_t p0 = 16 * rb + 4 * kg;
-            if (p0 < plim) {
+            if (p0 < plim && !(LOBRA_SHRINK_PROBE == 2 && o[0] != (__bf16)123.f)) {
                 if (tok < b.nrows)
                     *reinterpret_cast<bf16x4*>(P_tok + size_t(b.row0 + tok) * pd.r_pad + pofs + p0) = o;
                 // block-transposed copy [block][rank][32 tokens]; tokens beyond the block hold 0
@@ -200,7 +248,8 @@ __global__ __launch_bounds__(256) void shrink_lds_kernel(PlanDev pd, const uint1
     constexpr int CH = ROWS * 16;                        // 16-byte chunks per staged slab
     constexpr int MLD = (CH + 255) / 256;                // chunks per thread
     __shared__ __attribute__((aligned(16))) unsigned char ms[2][ROWS * 256];
-    const int32_t run = pd.sb_order ? pd.sb_order[blockIdx.x] : int32_t(blockIdx.x);
+    const int32_t wi = LOBRA_SKINNY_XCD ? xcd_contiguous(blockIdx.x, gridDim.x) : int32_t(blockIdx.x);
+    const int32_t run = pd.sb_order ? pd.sb_order[wi] : wi;
     const int32_t tb0 = pd.sb_off[run];
     const int32_t cnt = pd.sb_off[run + 1] - tb0;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -355,28 +404,32 @@ hipError_t shrink_mfma(const PlanDev& pd, const void* Z, const void* M, const fl
 // The four waves' sums are combined through LDS in two steps (fixed order: ((w0+w2)+(w1+w3))).
 // -------------------------------------------------------------------------------------------------
 template <int NRB, int CW, bool STREAM>
-__global__ __launch_bounds__(256) void grad_mfma_kernel(PlanDev pd, GradJob ja, GradJob jb, int32_t tiles_a)
+__global__ __launch_bounds__(256) void grad_mfma_kernel(PlanDev pd, GradJob ja, GradJob jb, int32_t tiles_a, int32_t tiles_all)
 {
     typedef uint32_t zvec __attribute__((ext_vector_type(CW / 2)));
     typedef float ovec __attribute__((ext_vector_type(4)));
+    // The grid is one-dimensional in (chunk, column tile), column tile fastest, and dealt to the XCDs in
+    // contiguous ranges: an XCD then works on whole rows of a few chunks at a time (see xcd_contiguous).
+    const int32_t wi = LOBRA_SKINNY_XCD ? xcd_contiguous(blockIdx.x, gridDim.x) : int32_t(blockIdx.x);
+    const int32_t tile_y = wi % tiles_all, chunk_x = wi / tiles_all;
     // one launch serves both gradients: column tiles [0, tiles_a) belong to job a, the rest to job b
-    const bool first = int32_t(blockIdx.y) < tiles_a;
+    const bool first = tile_y < tiles_a;
     const uint16_t* __restrict__ P_blk = static_cast<const uint16_t*>(first ? ja.P : jb.P);
     const uint16_t* __restrict__ Z = static_cast<const uint16_t*>(first ? ja.Z : jb.Z);
     float* __restrict__ part = first ? ja.part : jb.part;
     const int32_t D = first ? ja.D : jb.D;
     const int32_t ldz = (first ? ja.ldz : jb.ldz) ? (first ? ja.ldz : jb.ldz) : D;   // row pitch of Z (elements)
     const int32_t nproj = first ? ja.nproj : jb.nproj;    // > 1: only the rank window of one projection
-    const int32_t coltile = first ? int32_t(blockIdx.y) : int32_t(blockIdx.y) - tiles_a;
+    const int32_t coltile = first ? tile_y : tile_y - tiles_a;
     const int32_t proj_in = first ? ja.proj : jb.proj;
     const int32_t proj = proj_in >= 0 ? proj_in : coltile * (16 * CW) / pd.dg;   // projection of this column tile
     const int32_t pcol0 = proj_in >= 0 ? 0 : proj * pd.dg;                      // its first column
     const int32_t ldp = (first ? ja.ldp : jb.ldp) ? (first ? ja.ldp : jb.ldp) : D;   // row pitch of part
     __shared__ float red[2][NRB][CW][64][4];
-    const GradChunk ch = pd.chunks[blockIdx.x];
+    const GradChunk ch = pd.chunks[chunk_x];
     const int32_t r = (pd.rank_off[ch.task + 1] - pd.rank_off[ch.task]) / nproj;
     const int32_t pofs = proj * r;                        // first rank of the window inside the task's rows
-    const int32_t rb0 = blockIdx.z * NRB;                 // first rank block of this pass
+    const int32_t rb0 = blockIdx.y * NRB;                 // first rank block of this pass
     if (16 * rb0 >= r) return;                            // uniform: nothing to do for this task
     const int32_t nrb_t = min(NRB, (r - 16 * rb0 + 15) >> 4);   // rank blocks needed (uniform)
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -484,28 +537,32 @@ __global__ __launch_bounds__(256) void grad_mfma_kernel(PlanDev pd, GradJob ja, 
 // Operand layouts as in grad_mfma_kernel with CW = 4.
 // -------------------------------------------------------------------------------------------------
 template <int NRB>
-__global__ __launch_bounds__(256) void grad_lds_kernel(PlanDev pd, GradJob ja, GradJob jb, int32_t tiles_a)
+__global__ __launch_bounds__(256) void grad_lds_kernel(PlanDev pd, GradJob ja, GradJob jb, int32_t tiles_a, int32_t tiles_all)
 {
     constexpr int CW = 4, TW = 4 * 16 * CW;     // rank blocks per pass, columns per lane, tile width
     typedef uint32_t zvec __attribute__((ext_vector_type(CW / 2)));
     typedef float ovec __attribute__((ext_vector_type(4)));
     __shared__ __attribute__((aligned(16))) unsigned char ps[2][16 * NRB * 64];
-    const bool first = int32_t(blockIdx.y) < tiles_a;
+    // The grid is one-dimensional in (chunk, column tile), column tile fastest, and dealt to the XCDs in
+    // contiguous ranges: an XCD then works on whole rows of a few chunks at a time (see xcd_contiguous).
+    const int32_t wi = LOBRA_SKINNY_XCD ? xcd_contiguous(blockIdx.x, gridDim.x) : int32_t(blockIdx.x);
+    const int32_t tile_y = wi % tiles_all, chunk_x = wi / tiles_all;
+    const bool first = tile_y < tiles_a;
     const uint16_t* __restrict__ P_blk = static_cast<const uint16_t*>(first ? ja.P : jb.P);
     const uint16_t* __restrict__ Z = static_cast<const uint16_t*>(first ? ja.Z : jb.Z);
     float* __restrict__ part = first ? ja.part : jb.part;
     const int32_t D = first ? ja.D : jb.D;
     const int32_t ldz = (first ? ja.ldz : jb.ldz) ? (first ? ja.ldz : jb.ldz) : D;
     const int32_t nproj = first ? ja.nproj : jb.nproj;
-    const int32_t coltile = first ? int32_t(blockIdx.y) : int32_t(blockIdx.y) - tiles_a;
+    const int32_t coltile = first ? tile_y : tile_y - tiles_a;
     const int32_t proj_in = first ? ja.proj : jb.proj;
     const int32_t proj = proj_in >= 0 ? proj_in : coltile * TW / pd.dg;   // pd.dg is a multiple of TW then
     const int32_t pcol0 = proj_in >= 0 ? 0 : proj * pd.dg;
     const int32_t ldp = (first ? ja.ldp : jb.ldp) ? (first ? ja.ldp : jb.ldp) : D;
-    const GradChunk ch = pd.chunks[blockIdx.x];
+    const GradChunk ch = pd.chunks[chunk_x];
     const int32_t r = (pd.rank_off[ch.task + 1] - pd.rank_off[ch.task]) / nproj;
     const int32_t pofs = proj * r;
-    const int32_t rb0 = blockIdx.z * NRB;
+    const int32_t rb0 = blockIdx.y * NRB;
     if (16 * rb0 >= r) return;                            // uniform
     const int32_t nrb_t = min(NRB, (r - 16 * rb0 + 15) >> 4);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -597,23 +654,21 @@ hipError_t grad_mfma(const PlanDev& pd, const GradJob& ja, const GradJob& jb, hi
     if (NRB >= 2 &&
         (ja.proj >= 0 || pd.dg % 256 == 0) && (!jb.P || jb.proj >= 0 || pd.dg % 256 == 0)) {
         const int32_t ta = (ja.D + 255) / 256, tb = jb.P ? (jb.D + 255) / 256 : 0;
-        const dim3 grid(pd.nchunks, ta + tb, (nrb + 3) / 4);
-        if (grid.y > 65535u) return hipErrorInvalidValue;
-        if (NRB == 2) grad_lds_kernel<2><<<dim3(pd.nchunks, ta + tb, 1), 256, 0, st>>>(pd, ja, jb, ta);
-        else grad_lds_kernel<4><<<grid, 256, 0, st>>>(pd, ja, jb, ta);
+        const dim3 grid(uint32_t(pd.nchunks) * uint32_t(ta + tb), (nrb + 3) / 4);     // (plan creation bounds the product)
+        if (NRB == 2) grad_lds_kernel<2><<<dim3(grid.x, 1), 256, 0, st>>>(pd, ja, jb, ta, ta + tb);
+        else grad_lds_kernel<4><<<grid, 256, 0, st>>>(pd, ja, jb, ta, ta + tb);
         return hipGetLastError();
     }
     const int cw = NRB == 4 ? 4 : 8;
     const int32_t tw = 16 * cw;
     const int32_t tiles_a = (ja.D + tw - 1) / tw, tiles_b = jb.P ? (jb.D + tw - 1) / tw : 0;
-    const dim3 grid(pd.nchunks, tiles_a + tiles_b, (nrb + NRB - 1) / NRB);
-    if (grid.y > 65535u) return hipErrorInvalidValue;
+    const dim3 grid(uint32_t(pd.nchunks) * uint32_t(tiles_a + tiles_b), (nrb + NRB - 1) / NRB);
     // token rows that cannot stay in the 256 MB infinity cache anyway are streamed past the caches
     const bool stream = int64_t(pd.T) * (int64_t(ja.D) + (jb.P ? jb.D : 0)) * 2 > (int64_t(512) << 20);
 #define LOBRA_GRAD(NRB_, CW_)                                                                  \
     do {                                                                                       \
-        if (stream) grad_mfma_kernel<NRB_, CW_, true><<<grid, 256, 0, st>>>(pd, ja, jb, tiles_a);  \
-        else grad_mfma_kernel<NRB_, CW_, false><<<grid, 256, 0, st>>>(pd, ja, jb, tiles_a);        \
+        if (stream) grad_mfma_kernel<NRB_, CW_, true><<<grid, 256, 0, st>>>(pd, ja, jb, tiles_a, tiles_a + tiles_b);  \
+        else grad_mfma_kernel<NRB_, CW_, false><<<grid, 256, 0, st>>>(pd, ja, jb, tiles_a, tiles_a + tiles_b);        \
     } while (0)
     if (NRB == 1) LOBRA_GRAD(1, 8);
     else if (NRB == 2) LOBRA_GRAD(2, 8);
