@@ -176,8 +176,14 @@ def main():
         lens = [L for L, _ in p.seqs if L > 0]
         cand = list(range(256, (max(lens) + 255) // 256 * 256 + 1, 256))
         bounds, pad = bd.lobra_dynamic_buckets(lens, cand, a.buckets)
-        p = wl.pad_to_buckets(p, bounds)
-        assert p.T == real_tokens + pad
+        seqs = [(L, t) for L, t in p.seqs if L > 0]
+        p = wl.pad_to_buckets(p, bounds, fill=False)
+        # the chunk's segment table from the library's own helper (every sequence padded to its bucket boundary)
+        so, stk, T = bd.lobra_padded_segments([L for L, _ in seqs], [t for _, t in seqs], p.n_tasks,
+                                              [min(b for b in bounds if b >= L) for L, _ in seqs])
+        assert T == p.T == real_tokens + pad
+        p.seg_off, p.seg_task = so, stk
+        p = p.fill()
         layout_info = {"layout": "padded", "bucket_bounds": bounds, "pad_tokens": pad, "real_tokens": real_tokens}
     t0 = time.perf_counter()
     dp = bd.DeviceProblem(p)

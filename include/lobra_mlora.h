@@ -293,6 +293,20 @@ LOBRA_API lobra_status lobra_dynamic_buckets(const int32_t *seq_len, int64_t n_s
                                    int32_t U, int32_t R, int32_t *out_bounds, int32_t *out_n,
                                    int64_t *out_padding);
 
+/* The paper's default chunk layout as input of this operator (section 2.1, "Processing Variable-length Data": the
+ * sequences of a chunk are padded to a common length, [b, s_j] tokens): writes the segment table that makes the
+ * packed operator treat such a chunk correctly.  Sequence i occupies padded_len[i] consecutive token rows
+ * (padded_len = NULL: every sequence occupies uniform_len rows, the [b, s_j] case with b = n_seq, s_j = uniform_len);
+ * its first valid_len[i] rows become a segment of task[i], the remaining rows a segment of task -1 (pad tokens:
+ * base product only, no contribution to dA and dB).  Pure host code, all pointers are HOST pointers.
+ *   seg_off [2 n_seq + 1], seg_task [2 n_seq] : the table (a segment may be empty); *T_out = seg_off[2 n_seq] =
+ *                                               the token rows of the chunk (T of the descriptor); may be NULL
+ * LOBRA_ERR_SEGMENTS for a valid_len outside [0, padded length], LOBRA_ERR_TASK_ID for a task outside
+ * [-1, n_tasks), LOBRA_ERR_SHAPE when the chunk has 2^31 rows or more; on error nothing is written. */
+LOBRA_API lobra_status lobra_padded_segments(int64_t n_seq, const int32_t *padded_len, int32_t uniform_len,
+                                   const int32_t *valid_len, const int32_t *task, int32_t n_tasks,
+                                   int32_t *seg_off, int32_t *seg_task, int64_t *T_out);
+
 /* Profiling aid (bench, tests).  While a trace is attached, every kernel that fwd / bwd /
  * token_task_map launch through this plan is bracketed by hipEventRecord on the call's stream:
  * the i-th launch since the trace was attached records events[2i] before and events[2i+1]

@@ -82,3 +82,16 @@ def brute_force(lengths, u, R):
         for chosen in combinations(u, k):
             best = min(best, padding_for(lengths, chosen))
     return best
+
+
+def padded_segments(padded_len, valid_len, task):
+    """Segment table of a padded chunk (paper section 2.1, "Processing Variable-length Data": sequences padded to a
+    common length): sequence i occupies padded_len[i] token rows, the first valid_len[i] of them belong to
+    task[i], the rest are pad tokens (task -1).  Written out row by row: the task of every token row, then the
+    maximal description as (offsets, tasks) with two segments per sequence."""
+    seg_off, seg_task = [0], []
+    for pl, vl, t in zip(padded_len, valid_len, task):
+        seg_off += [seg_off[-1] + int(vl), seg_off[-1] + int(pl)]
+        seg_task += [int(t), -1]
+    return seg_off, seg_task
+

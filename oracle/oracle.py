@@ -263,7 +263,7 @@ class Oracle:
 
 class FusedProjections:
     """Several layers that read the same x (the q/k/v projections of an attention block, gate/up of
-    an MLP; paper section 3.3 names the LoRA linears of one layer), each computed by the oracle above
+    an MLP: the LoRA linears of one transformer layer that section 2.1 adapts), each computed by the oracle above
     on its own slice - nothing is fused here, the definition is "P separate layers":
 
         y[:, j]  = layer_j(x)                 dx = sum_j dx_j

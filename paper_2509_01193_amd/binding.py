@@ -27,6 +27,7 @@ EXPORTS = [
     "lobra_mlora_plan_create", "lobra_mlora_plan_device_bytes", "lobra_mlora_plan_init", "lobra_mlora_plan_destroy",
     "lobra_mlora_plan_sizes", "lobra_mlora_plan_query", "lobra_mlora_plan_fwd", "lobra_mlora_plan_bwd",
     "lobra_mlora_plan_token_task_map", "lobra_mlora_fwd_static_ws", "lobra_mlora_adam_step", "lobra_dynamic_buckets",
+    "lobra_padded_segments",
     "lobra_mlora_plan_set_trace", "lobra_status_string", "lobra_version",
 ]
 
@@ -323,6 +324,26 @@ def lobra_dynamic_buckets(seq_len, bounds, R):
     return out[: n.value].tolist(), int(pad.value)
 
 
+def lobra_padded_segments(valid_len, task, n_tasks, padded_len=None, uniform_len=0, check=True):
+    """Segment table (seg_off, seg_task) and token count of a padded chunk; returns (status, ...) when check=False."""
+    L = lib()
+    i32p = ctypes.POINTER(ctypes.c_int32)
+    L.lobra_padded_segments.restype = ctypes.c_int
+    L.lobra_padded_segments.argtypes = [ctypes.c_int64, i32p, ctypes.c_int32, i32p, i32p, ctypes.c_int32, i32p, i32p,
+                                        ctypes.POINTER(ctypes.c_int64)]
+    vl, tk = _i32(valid_len), _i32(task)
+    n = int(vl.shape[0])
+    pl = None if padded_len is None else _i32(padded_len)
+    so, stk, T = np.full(2 * n + 1, -9, np.int32), np.full(max(2 * n, 1), -9, np.int32), ctypes.c_int64(-9)
+    st = L.lobra_padded_segments(n, None if pl is None else pl.ctypes.data_as(i32p), int(uniform_len),
+                                 vl.ctypes.data_as(i32p), tk.ctypes.data_as(i32p), int(n_tasks),
+                                 so.ctypes.data_as(i32p), stk.ctypes.data_as(i32p), ctypes.byref(T))
+    if check:
+        _check(st, "lobra_padded_segments")
+        return so, stk[: 2 * n], int(T.value)
+    return st, so, stk[: 2 * n], int(T.value)
+
+
 def lobra_mlora_plan_token_task_map(plan: Plan, out_task, out_count, stream=None):
     _check(lib().lobra_mlora_plan_token_task_map(plan.handle, _ptr(out_task), _ptr(out_count), _stream(stream)),
            "lobra_mlora_plan_token_task_map")
@@ -350,13 +371,30 @@ class DeviceProblem:
         self.A = up(p.A) if p.R_tot else None
         self.B = up(p.B) if p.R_tot else None
         self.s = torch.from_numpy(np.asarray(p.s, np.float32)).to(self.dev) if p.n_tasks else None
-        self.y = torch.empty((p.T, p.d_out), dtype=self.edt, device=self.dev)
-        self.dx = torch.empty((p.T, p.d_in), dtype=self.edt, device=self.dev)
-        self.dA = torch.zeros((p.R_tot, p.d_in), dtype=torch.float32, device=self.dev)
-        self.dB = torch.zeros((p.R_tot, p.d_out // getattr(p, "n_proj", 1)), dtype=torch.float32, device=self.dev)
-        nb = lambda n: torch.empty(max(n, 16), dtype=torch.uint8, device=self.dev)
-        self.h_save = nb(self.plan.h_save_bytes)
-        self.ws = nb(max(self.plan.fwd_ws_bytes, self.plan.bwd_ws_bytes))
+        # every buffer the library writes sits between two sentinel margins (guards_intact() checks them)
+        self._guards = []
+        self.y = self._guarded((p.T, p.d_out), self.edt)
+        self.dx = self._guarded((p.T, p.d_in), self.edt)
+        self.dA = self._guarded((p.R_tot, p.d_in), torch.float32).zero_()
+        self.dB = self._guarded((p.R_tot, p.d_out // getattr(p, "n_proj", 1)), torch.float32).zero_()
+        self.h_save = self._guarded((max(self.plan.h_save_bytes, 16),), torch.uint8)
+        self.ws = self._guarded((max(self.plan.fwd_ws_bytes, self.plan.bwd_ws_bytes, 16),), torch.uint8)
+
+    GUARD_BYTES, GUARD_VALUE = 4096, 0xC3
+
+    def _guarded(self, shape, dtype):
+        torch = self.torch
+        n = int(np.prod(shape)) * torch.empty(0, dtype=dtype).element_size()
+        n16 = (n + 15) // 16 * 16
+        buf = torch.full((n16 + 2 * self.GUARD_BYTES,), self.GUARD_VALUE, dtype=torch.uint8, device=self.dev)
+        self._guards.append((buf, n))
+        return buf[self.GUARD_BYTES:self.GUARD_BYTES + n].view(dtype).view(*shape)
+
+    def guards_intact(self):
+        """True when no byte of the margins around y, dx, dA, dB, h_save and the workspace has changed."""
+        g = self.GUARD_BYTES
+        return all(bool((buf[:g] == self.GUARD_VALUE).all()) and bool((buf[g + n:] == self.GUARD_VALUE).all())
+                   for buf, n in self._guards)
 
     def fwd(self, save_h=True):
         lobra_mlora_plan_fwd(self.plan, self.x, self.W, self.A, self.B, self.s, self.y,

@@ -86,3 +86,37 @@ extern "C" lobra_status lobra_dynamic_buckets(const int32_t* seq_len, int64_t n_
     }
     return LOBRA_OK;
 }
+
+// The padded layout of a chunk (paper section 2.1, "Processing Variable-length Data": sequences of a chunk are
+// padded to a common length) as a segment table of the packed operator: sequence i takes padded_len[i]
+// consecutive token rows, the first valid_len[i] of them belong to task[i], the rest are pad tokens (task -1:
+// base product only, no part in dA and dB).  Pure index arithmetic on the host.
+extern "C" lobra_status lobra_padded_segments(int64_t n_seq, const int32_t* padded_len, int32_t uniform_len,
+                                              const int32_t* valid_len, const int32_t* task, int32_t n_tasks,
+                                              int32_t* seg_off, int32_t* seg_task, int64_t* T_out)
+{
+    if (n_seq < 0 || n_tasks < 0) return LOBRA_ERR_SHAPE;
+    if (!seg_off || (n_seq > 0 && (!valid_len || !task || !seg_task))) return LOBRA_ERR_NULL;
+    if (!padded_len && uniform_len < 0) return LOBRA_ERR_SHAPE;
+    if (2 * n_seq > 0x7fffffff) return LOBRA_ERR_SHAPE;          // the table has 2 n_seq segments
+    int64_t pos = 0;
+    for (int64_t i = 0; i < n_seq; ++i) {                        // all checks first: on error nothing is written
+        const int64_t pl = padded_len ? padded_len[i] : uniform_len;
+        if (pl < 0 || valid_len[i] < 0 || valid_len[i] > pl) return LOBRA_ERR_SEGMENTS;
+        if (task[i] < -1 || task[i] >= n_tasks) return LOBRA_ERR_TASK_ID;
+        pos += pl;
+        if (pos >= (int64_t(1) << 31)) return LOBRA_ERR_SHAPE;
+    }
+    pos = 0;
+    seg_off[0] = 0;
+    for (int64_t i = 0; i < n_seq; ++i) {
+        const int64_t pl = padded_len ? padded_len[i] : uniform_len;
+        seg_off[2 * i + 1] = int32_t(pos + valid_len[i]);
+        seg_task[2 * i] = task[i];
+        seg_off[2 * i + 2] = int32_t(pos + pl);
+        seg_task[2 * i + 1] = -1;
+        pos += pl;
+    }
+    if (T_out) *T_out = pos;
+    return LOBRA_OK;
+}

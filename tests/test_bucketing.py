@@ -92,3 +92,58 @@ def test_padded_layout_of_a_workload_follows_the_chosen_boundaries():
         assert (q.task_tokens() == p.task_tokens()).all()
     with pytest.raises(ValueError):
         wl.pad_to_buckets(p, [16])
+
+
+# ---- the padded chunk as a segment table (lobra_padded_segments) ---------------------------------------------
+def test_padded_segments_oracle_pin_against_the_row_by_row_definition():
+    """The oracle's table, expanded token by token with the layer oracle's own token -> task map, must be the
+    definition: row r of sequence i belongs to task[i] when r < valid_len[i], to nobody otherwise."""
+    import oracle
+    rng = np.random.default_rng(9)
+    for trial in range(30):
+        n = int(rng.integers(0, 9))
+        pl = rng.integers(0, 20, n)
+        vl = np.asarray([int(rng.integers(0, p + 1)) for p in pl], np.int64)
+        tk = rng.integers(-1, 4, n)
+        seg_off, seg_task = ob.padded_segments(pl, vl, tk)
+        want = np.concatenate([np.concatenate([np.full(v, t), np.full(p - v, -1)]) for p, v, t in zip(pl, vl, tk)]
+                              + [np.zeros(0, np.int64)]).astype(np.int32)
+        got = oracle.token_task(int(pl.sum()), np.asarray(seg_off, np.int32), np.asarray(seg_task, np.int32), 4)
+        assert np.array_equal(got, want), (pl, vl, tk)
+    # the worked case: [b, s_j] = [3, 8] with valid lengths 5, 8, 0
+    assert ob.padded_segments([8, 8, 8], [5, 8, 0], [1, 0, 2]) == ([0, 5, 8, 16, 16, 16, 24], [1, -1, 0, -1, 2, -1])
+
+
+def test_padded_segments_entry_point_against_the_oracle_bit_for_bit():
+    rng = np.random.default_rng(10)
+    for trial in range(60):
+        n = int(rng.integers(0, 40))
+        uniform = trial % 2 == 0
+        pl = np.full(n, int(rng.integers(0, 600))) if uniform else rng.integers(0, 600, n)
+        vl = np.asarray([int(rng.integers(0, p + 1)) for p in pl], np.int64)
+        tk = rng.integers(-1, 5, n)
+        so, stk, T = bd.lobra_padded_segments(vl, tk, 5, None if uniform else pl, int(pl[0]) if (uniform and n) else 0)
+        ro, rt = ob.padded_segments(pl, vl, tk)
+        assert so.tolist() == ro and stk.tolist() == rt and T == int(pl.sum())
+        # what it writes is a table the layer accepts
+        d, keep = bd.make_desc("bf16", T, 64, 64, np.arange(6) * 8, so, stk)
+        assert bd.validate(d) == 0
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(valid_len=[3, 9], task=[0, 1], padded_len=[4, 8]), -4),         # longer than its padded length
+    (dict(valid_len=[3, -1], task=[0, 1], padded_len=[4, 8]), -4),
+    (dict(valid_len=[3, 5], task=[0, 1], padded_len=[4, -8]), -4),
+    (dict(valid_len=[3, 5], task=[0, 2], padded_len=[4, 8]), -5),         # n_tasks = 2
+    (dict(valid_len=[3, 5], task=[-2, 1], padded_len=[4, 8]), -5),
+    (dict(valid_len=[3, 5], task=[0, 1], uniform_len=-1), -2),
+    (dict(valid_len=[1] * 3, task=[0] * 3, uniform_len=(1 << 30)), -2),   # 2^31 token rows and more
+    (dict(valid_len=[3, 5], task=[0, 1], padded_len=[4, 8]), 0),
+])
+def test_padded_segments_argument_errors_write_nothing(kw, code):
+    st, so, stk, T = bd.lobra_padded_segments(kw["valid_len"], kw["task"], 2, kw.get("padded_len"), kw.get("uniform_len", 0),
+                                              check=False)
+    assert st == code
+    if code != 0:
+        assert (so == -9).all() and (stk == -9).all() and T == -9
+

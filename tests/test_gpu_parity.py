@@ -49,6 +49,7 @@ def check_problem(p, rows=None, plan_flags=0, tol=None, label=""):
     dp = bd.DeviceProblem(p, plan_flags)
     dp.step()
     torch.cuda.synchronize()
+    assert dp.guards_intact(), (p.name, "a write outside y, dx, dA, dB, h_save or the workspace")
     o = make_oracle(p)
     if rows is None:
         y, dx = dp.host(dp.y), dp.host(dp.dx)
@@ -342,11 +343,9 @@ def test_padded_bucket_layout_as_no_adapter_spans():
     Pad tokens are segments of task -1: they take the base product only and stay out of dA, dB."""
     import torch
     lens, tasks, bucket = [100, 250, 17, 256, 190], [0, 1, 1, 0, 2], 256
-    seg_off, seg_task = [0], []
-    for L, t in zip(lens, tasks):
-        seg_off.append(seg_off[-1] + L); seg_task.append(t)
-        if L < bucket:
-            seg_off.append(seg_off[-1] + bucket - L); seg_task.append(-1)
+    # the [b, s_j] chunk with its valid lengths, turned into a segment table by the library's own helper
+    seg_off, seg_task, T = bd.lobra_padded_segments(lens, tasks, 3, None, bucket)
+    assert T == len(lens) * bucket and seg_off.tolist() == [0, 100, 256, 506, 512, 529, 768, 1024, 1024, 1214, 1280]
     padded = wl.make_custom("padded", "bf16", 320, 192, [16, 8, 32], seg_off, seg_task, 11)
     dp, _ = check_problem(padded, label="padded")
     # the packed batch of the same sequences gives the same adapter gradients

@@ -262,7 +262,39 @@ def pin_token_task_map():
         oracle.token_task(6, [0, 5], [0], 1)                  # table does not cover T
 
 
-PINS = [pin_golden_integer_case, pin_b_zero_is_base_only, pin_single_task_merged_weight,
+def pin_projected_activations():
+    """The optional outputs h_i = A_t x_i and g_i = B_t dy_i (section 2.1: the down factor applied to the token)
+    against numpy's matmul per segment; rows without adapter and ranks beyond r_t are zero; a row subset gives
+    the rows of the full result."""
+    for dtype in ("f32", "bf16"):
+        p = small_problem(dtype=dtype, d_in=24, d_out=16)
+        x, W, A, B, dy = f64(p)
+        task_of = oracle.token_task(p.T, p.seg_off, p.seg_task, p.n_tasks)
+        y, h = oracle.forward(p.x, p.W, p.A, p.B, p.s, p.rank_off, task_of, want_h=True)
+        dx, g = oracle.backward_dx(p.W, p.A, p.B, p.s, p.dy, p.rank_off, task_of, want_g=True)
+        r_max = int(np.max(p.ranks))
+        href, gref = np.zeros((p.T, r_max)), np.zeros((p.T, r_max))
+        for k in range(p.S):
+            t = int(p.seg_task[k])
+            if t < 0:
+                continue
+            m = slice(int(p.seg_off[k]), int(p.seg_off[k + 1]))
+            r0, r1 = int(p.rank_off[t]), int(p.rank_off[t + 1])
+            href[m, : r1 - r0] = x[m] @ A[r0:r1].T
+            gref[m, : r1 - r0] = dy[m] @ B[r0:r1].T
+        assert h.shape == href.shape and relerr(h, href) < 1e-13 and relerr(g, gref) < 1e-13
+        assert not h[task_of < 0].any() and not g[task_of < 0].any()
+        for t in range(p.n_tasks):
+            assert not h[task_of == t, int(p.ranks[t]):].any() and not g[task_of == t, int(p.ranks[t]):].any()
+        # y and dx are what the calls return without the optional output
+        assert np.array_equal(y, oracle.forward(p.x, p.W, p.A, p.B, p.s, p.rank_off, task_of))
+        assert np.array_equal(dx, oracle.backward_dx(p.W, p.A, p.B, p.s, p.dy, p.rank_off, task_of))
+        rows = np.asarray([p.T - 1, 0, 6, 6, 13], np.int64)
+        assert np.array_equal(oracle.forward(p.x, p.W, p.A, p.B, p.s, p.rank_off, task_of, rows, want_h=True)[1], h[rows])
+        assert np.array_equal(oracle.backward_dx(p.W, p.A, p.B, p.s, p.dy, p.rank_off, task_of, rows, want_g=True)[1], g[rows])
+
+
+PINS = [pin_golden_integer_case, pin_projected_activations, pin_b_zero_is_base_only, pin_single_task_merged_weight,
         pin_fused_equals_per_task, pin_adjoint_identities, pin_finite_differences,
         pin_autograd_per_task, pin_structural_invariances, pin_bf16_widening_and_row_subset,
         pin_token_task_map]
@@ -308,6 +340,8 @@ MUTANTS = [
      "lo += h[p] * load_elem(B, dtype, (size_t)(p) * d_out + j);"),
     ("gradient sums over every adapter token", "if (task_of[i] != t)", "if (task_of[i] < 0)"),
     ("bf16 widened wrongly", "[i] << 16;", "[i] << 15;"),
+    ("h output scaled", "h_out[(size_t)q * r_max + p] = acc;", "h_out[(size_t)q * r_max + p] = 2.0 * acc;"),
+    ("g output misplaced", "g_out[(size_t)q * r_max + p] = acc;", "g_out[(size_t)q * r_max + (r - 1 - p)] = acc;"),
     ("g uses A", "ag += load_elem(dy, dtype, (size_t)i * d_out + j) *\n                      load_elem(B, dtype, (size_t)(r0 + p) * d_out + j);",
      "ag += load_elem(dy, dtype, (size_t)i * d_out + j) *\n                      load_elem(A, dtype, ((size_t)(r0 + p) * d_in + j) % ((size_t)d_in));"),
 ]
