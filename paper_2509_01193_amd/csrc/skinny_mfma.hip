@@ -8,9 +8,6 @@
 // each task of the fused batch has its own pair.)
 #include "kernels.h"
 
-#ifndef LOBRA_SHRINK_PROBE
-#define LOBRA_SHRINK_PROBE 0    // timing variants: 1 adapter rows always from the first slab, 2 (almost) no stores
-#endif
 #ifndef LOBRA_SKINNY_XCD
 #define LOBRA_SKINNY_XCD 1      // work items dealt to the XCDs in contiguous ranges (see xcd_contiguous)
 #endif
@@ -63,17 +60,16 @@ __global__ __launch_bounds__(64 * NWV) void shrink_mfma_kernel(PlanDev pd, const
     // that projection's column block of dy (row pitch ldz), M its rows of the compact up factors,
     // and the task's rank rows it reads and writes are the window [proj r, (proj + 1) r).
     __shared__ float red[NWV][2][NRB][64][4];   // [wave][token half][rank block][lane][4]
-    const int32_t wi = LOBRA_SKINNY_XCD ? xcd_contiguous(blockIdx.x, gridDim.x) : int32_t(blockIdx.x);
-    const int32_t bi = pd.tb_order ? pd.tb_order[wi] : wi;
+    // (a launch order by rank is dealt round-robin: contiguous ranges of it would give one XCD all the expensive blocks)
+    const int32_t bi = pd.tb_order ? pd.tb_order[blockIdx.x]
+                                   : (LOBRA_SKINNY_XCD ? xcd_contiguous(blockIdx.x, gridDim.x) : int32_t(blockIdx.x));
     const TokenBlock b = pd.tb[bi];
     const int32_t r = (pd.rank_off[b.task + 1] - b.rank_row0) / nproj;
     const int32_t pofs = proj * r;               // first rank of the window inside the task's rows
     const int32_t rank_row0 = b.rank_row0 + pofs;
     const int32_t plim = proj == nproj - 1 ? pd.r_pad - pofs : r;   // ranks (and zero padding) stored by this launch
     const int32_t nrb_t = (r + 15) >> 4;        // rank blocks this task needs (uniform)
-    // (the wave number as a scalar: the loops below then branch on scalars, and the compiler can count the
-    //  loads in flight instead of draining them at every join of divergent paths)
-    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int j = lane & 15, kg = lane >> 4;
     const u32x4 zero4 = {0u, 0u, 0u, 0u};
 
@@ -104,7 +100,7 @@ __global__ __launch_bounds__(64 * NWV) void shrink_mfma_kernel(PlanDev pd, const
 #pragma unroll
                 for (int rb = 0; rb < NRB; ++rb)
                     if (NRB == 1 || rb < nrb_t)
-                        sl.mv[rb][q] = *reinterpret_cast<const u32x4*>(mrow[rb] + (LOBRA_SHRINK_PROBE == 1 ? 8 * kg : k) + 32 * q);
+                        sl.mv[rb][q] = *reinterpret_cast<const u32x4*>(mrow[rb] + k + 32 * q);
 #pragma unroll
                 for (int h = 0; h < 2; ++h)
                     sl.zv[h][q] = *reinterpret_cast<const u32x4*>(zrow[h] + k + 32 * q);
@@ -135,56 +131,18 @@ __global__ __launch_bounds__(64 * NWV) void shrink_mfma_kernel(PlanDev pd, const
                             as_bf16x8(sl.mv[rb][q]), as_bf16x8(sl.zv[h][q]), acc[h][rb], 0, 0, 0);
     };
     const int32_t nsl = (D + 127) >> 7;
-    if (DEPTH == 3 && (D & 127) == 0) {
-        // Whole slabs only: this wave's slabs are wave, wave + NWV, ...; three of them are in flight (the loads
-        // of slab t + 2 are issued before the MFMAs of slab t), three slabs per trip so that the register sets
-        // rotate without copies, and not a branch in the trip.
-        const int32_t n_my = (nsl - wave + NWV - 1) / NWV;
-        auto slab_of = [&](int32_t t) { return (wave + NWV * t) << 7; };
-        auto load_full = [&](Slab& sl, int32_t slab) {
-            const int32_t k = slab + 8 * kg;
+    // DEPTH slabs in flight per wave: the loads of slab i + DEPTH - 1 are issued before the MFMAs
+    // of slab i (DEPTH = 1: load, then multiply).
+    Slab buf[DEPTH];
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
+    for (int d = 0; d < DEPTH - 1; ++d)
+        if (wave + NWV * d < nsl) load(buf[d], (wave + NWV * d) << 7);
+    for (int32_t i = wave; i < nsl; i += NWV * DEPTH) {
 #pragma unroll
-                for (int rb = 0; rb < NRB; ++rb)
-                    if (NRB == 1 || rb < nrb_t) sl.mv[rb][q] = *reinterpret_cast<const u32x4*>(mrow[rb] + k + 32 * q);
-#pragma unroll
-                for (int h = 0; h < 2; ++h) sl.zv[h][q] = *reinterpret_cast<const u32x4*>(zrow[h] + k + 32 * q);
-            }
-        };
-        Slab b0, b1, b2;
-        if (n_my > 0) load_full(b0, slab_of(0));
-        if (n_my > 1) load_full(b1, slab_of(1));
-        int32_t t = 0;
-        for (; t + 5 <= n_my; t += 3) {
-            load_full(b2, slab_of(t + 2));
-            mac(b0);
-            load_full(b0, slab_of(t + 3));
-            mac(b1);
-            load_full(b1, slab_of(t + 4));
-            mac(b2);
-        }
-        // two to four slabs are left; b0 and b1 hold the first two of them
-        if (t + 2 < n_my) load_full(b2, slab_of(t + 2));
-        if (t < n_my) mac(b0);
-        if (t + 3 < n_my) load_full(b0, slab_of(t + 3));
-        if (t + 1 < n_my) mac(b1);
-        if (t + 2 < n_my) mac(b2);
-        if (t + 3 < n_my) mac(b0);
-    } else {
-        // DEPTH slabs in flight per wave: the loads of slab i + DEPTH - 1 are issued before the MFMAs
-        // of slab i (DEPTH = 1: load, then multiply).
-        Slab buf[DEPTH];
-#pragma unroll
-        for (int d = 0; d < DEPTH - 1; ++d)
-            if (wave + NWV * d < nsl) load(buf[d], (wave + NWV * d) << 7);
-        for (int32_t i = wave; i < nsl; i += NWV * DEPTH) {
-#pragma unroll
-            for (int d = 0; d < DEPTH; ++d) {
-                const int32_t nx = i + NWV * (d + DEPTH - 1);
-                if (nx < nsl) load(buf[(d + DEPTH - 1) % DEPTH], nx << 7);
-                if (i + NWV * d < nsl) mac(buf[d]);
-            }
+        for (int d = 0; d < DEPTH; ++d) {
+            const int32_t nx = i + NWV * (d + DEPTH - 1);
+            if (nx < nsl) load(buf[(d + DEPTH - 1) % DEPTH], nx << 7);
+            if (i + NWV * d < nsl) mac(buf[d]);
         }
     }
     // cross-wave sum through LDS, then lane (token j, rank group kg) of wave 0/1 stores half h
@@ -213,7 +171,7 @@ __global__ __launch_bounds__(64 * NWV) void shrink_mfma_kernel(PlanDev pd, const
                 o[v] = (__bf16)((p < r && tok < b.nrows) ? st * sum : 0.f);
             }
             const int32_t p0 = 16 * rb + 4 * kg;
-            if (p0 < plim && !(LOBRA_SHRINK_PROBE == 2 && o[0] != (__bf16)123.f)) {
+            if (p0 < plim) {
                 if (tok < b.nrows)
                     *reinterpret_cast<bf16x4*>(P_tok + size_t(b.row0 + tok) * pd.r_pad + pofs + p0) = o;
                 // block-transposed copy [block][rank][32 tokens]; tokens beyond the block hold 0
@@ -248,8 +206,8 @@ __global__ __launch_bounds__(256) void shrink_lds_kernel(PlanDev pd, const uint1
     constexpr int CH = ROWS * 16;                        // 16-byte chunks per staged slab
     constexpr int MLD = (CH + 255) / 256;                // chunks per thread
     __shared__ __attribute__((aligned(16))) unsigned char ms[2][ROWS * 256];
-    const int32_t wi = LOBRA_SKINNY_XCD ? xcd_contiguous(blockIdx.x, gridDim.x) : int32_t(blockIdx.x);
-    const int32_t run = pd.sb_order ? pd.sb_order[wi] : wi;
+    const int32_t run = pd.sb_order ? pd.sb_order[blockIdx.x]
+                                    : (LOBRA_SKINNY_XCD ? xcd_contiguous(blockIdx.x, gridDim.x) : int32_t(blockIdx.x));
     const int32_t tb0 = pd.sb_off[run];
     const int32_t cnt = pd.sb_off[run + 1] - tb0;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
