@@ -45,11 +45,15 @@
 #include "gemm_common.h"
 #include "kernels.h"
 
+#ifndef LOBRA_GP_TPW
+#define LOBRA_GP_TPW 4       // output tiles per workgroup
+#endif
 #ifndef LOBRA_GP_STORES_IN_FLIGHT
 #define LOBRA_GP_STORES_IN_FLIGHT 32   // stores of an epilogue (MB x NB / 2 per wave); 0: wait for them at the next barrier
 #endif
 #ifndef LOBRA_GP_STORE
-#define LOBRA_GP_STORE 1     // 1: non-temporal stores (the product); 0 / 2: timing variants (hardly any stores / plain stores)
+#define LOBRA_GP_STORE 1     // 1: non-temporal stores of whole lines through LDS (the product); 4: 64-byte pieces straight from the
+                             // accumulators; 0 / 2: timing variants (hardly any stores / plain stores)
 #endif
 
 namespace lobra {
@@ -86,8 +90,10 @@ __global__ __launch_bounds__(64 * NW)
 void gemm_persistent_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const uint16_t* __restrict__ W,
                             const uint16_t* __restrict__ P, const uint16_t* __restrict__ M,
                             uint16_t* __restrict__ C, int32_t K, int32_t N, int32_t ldw, int32_t ldc,
-                            int32_t nproj, int32_t proj, int32_t tiles_m, int32_t tiles_n, int32_t GM)
+                            int32_t nproj, int32_t proj, int32_t tiles_m, int32_t tiles_n, int32_t GM, int32_t cpx,
+                            int32_t TPW)
 {
+    // cpx: workgroups an XCD runs at one time (one per compute unit); TPW: output tiles per workgroup.
     // ldc: row pitch of C.  nproj > 1: this launch is projection `proj` of a fused shared-input
     // call: of every task's rank rows (in M) and rank columns (in P) only the window
     // [proj r, (proj + 1) r) takes part, r = the task's stacked rank / nproj.  proj < 0: the launch
@@ -103,18 +109,23 @@ void gemm_persistent_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const ui
     const int32_t KT = K / BK;                       // the launcher guarantees K % (2 BK) == 0: an even number of K tiles
 
     // ---- this workgroup's output tiles.  Consecutive workgroup ids go to different XCDs (each with its own
-    //      L2), so every XCD gets a contiguous range of the tile order and its workgroups walk it side by
-    //      side; inside the order, GM tile-rows share one sweep over the tile-columns.
+    //      L2), so every XCD gets a contiguous range of the tile order; inside the order, GM tile-rows share one
+    //      sweep over the tile-columns.  The cpx workgroups that an XCD runs at one time walk its range side by
+    //      side - at any moment they work on cpx neighbouring tiles and share their panels through the L2 - but
+    //      only for TPW tiles each: then the next cpx workgroups are dispatched.  (A workgroup that kept its
+    //      place for the whole launch would drift: one that falls behind misses the panels its neighbours have
+    //      fetched, which slows it further; at 112 tiles per compute unit that cost 5 % and 44 % more L2 misses.)
     const int32_t ntiles = tiles_m * tiles_n;
-    const int32_t nwg = gridDim.x, wg = blockIdx.x;
+    const int32_t wg = blockIdx.x;
     const int32_t xcd = wg & 7, xidx = wg >> 3;
     const int32_t xper = ntiles >> 3, xrem = ntiles & 7;
     const int32_t xstart = xcd * xper + min(xcd, xrem), xcount = xper + (xcd < xrem ? 1 : 0);
-    const int32_t xwgs = (nwg - xcd + 7) >> 3;       // workgroups of this launch on this XCD
-    const int32_t my_tiles = xidx < xcount ? (xcount - xidx + xwgs - 1) / xwgs : 0;
+    const int32_t xwgs = cpx;                        // stride between a workgroup's tiles
+    const int32_t xfirst = (xidx / cpx) * (cpx * TPW) + xidx % cpx;      // its first tile within the XCD's range
+    const int32_t my_tiles = xfirst < xcount ? min(TPW, (xcount - xfirst + cpx - 1) / cpx) : 0;
     if (my_tiles == 0) return;                       // uniform over the workgroup
     auto tile_origin = [&](int32_t n, int32_t& row0, int32_t& col0) {   // my n-th tile
-        const int32_t id = xstart + xidx + n * xwgs;
+        const int32_t id = xstart + xfirst + n * xwgs;
         const int32_t group = id / (GM * tiles_n);
         const int32_t first_m = group * GM;
         const int32_t gsz = min(tiles_m - first_m, GM);
@@ -341,7 +352,7 @@ void gemm_persistent_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const ui
                     load_p(k0);
                     // the slice is rows * 32 chunks of 16 bytes; the first MCH * 256 of them are fetched before
                     // the barrier that frees the region and written after it
-                    constexpr int MCH = 4, NT = 64 * NW;
+                    constexpr int MCH = 2, NT = 64 * NW;
                     u32x4 mreg[MCH];
                     auto fetch_m = [&](int32_t base) {
 #pragma unroll
@@ -384,9 +395,11 @@ void gemm_persistent_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const ui
             }
             asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
         }
-        // ---- fp32 -> bf16 (one rounding, to nearest even) and 16-byte stores straight from the accumulators:
-        //      blocks 2 p and 2 p + 1 hold this lane's columns 32 p + 8 kg .. + 7.  Non-temporal, so that y / dx
-        //      do not evict x / dy from the caches before the rank-r passes read them.
+        // ---- fp32 -> bf16 (one rounding, to nearest even) and the stores.  Blocks 2 p and 2 p + 1 hold this lane's
+        //      columns 32 p + 8 kg .. + 7 of token row j.  Non-temporal, so that y / dx do not evict x / dy from the
+        //      caches before the rank-r passes read them.
+#if LOBRA_GP_STORE == 4
+        //      Straight from the accumulators: 16 bytes per lane, 64 contiguous bytes per row and instruction.
         const int32_t orow = wrow0 + j, ocol = col0 + wn * TN + 8 * kg;
         uint16_t* cp = C + size_t(orow) * ldc + ocol;
         static_for<0, MB>([&](auto mb_c) {
@@ -398,17 +411,47 @@ void gemm_persistent_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const ui
                     constexpr int q = decltype(q_c)::value;
                     o[q] = (__bf16)acc_read<acc_reg(mb, 2 * p) + q>();
                 });
-#if LOBRA_GP_STORE == 0 || LOBRA_GP_STORE == 3     // timing variants: only a token store (3: on half of the XCDs), so that the result is not dead code
-                if ((mb == 0 && p == 0) || (LOBRA_GP_STORE == 3 && (blockIdx.x & 7) < 4))
-                    __builtin_nontemporal_store(o, reinterpret_cast<bf16x8*>(cp + size_t(16 * mb) * ldc + 32 * p));
+                __builtin_nontemporal_store(o, reinterpret_cast<bf16x8*>(cp + size_t(16 * mb) * ldc + 32 * p));
+            });
+        });
+#else
+        //      Through the wave's quarter of the adapter-slice region (8 KiB, free now), a 64 x 64 block at a time,
+        //      so that every store instruction writes whole 128-byte lines (8 rows of them): written 64 bytes at a
+        //      time the result costs 40 % more write requests between L2 and memory.  Rows of a block are 128 bytes
+        //      apart in LDS, 16-byte chunk c of row r stored at c ^ ((r >> 1) & 7); a wave's LDS operations are
+        //      carried out in order, so the reads of a block need no wait for its writes.
+        if (P) __syncthreads();                      // other waves may still read the adapter slice
+        unsigned char* cs = lds + MSLICE_OFF + wave * 8192;
+        static_for<0, 4>([&](auto b_c) {
+            constexpr int hm = decltype(b_c)::value / 2, hn = decltype(b_c)::value % 2;
+            static_for<0, 4>([&](auto m_c) {
+                constexpr int mb = 4 * hm + decltype(m_c)::value;
+                static_for<0, 2>([&](auto p_c) {
+                    constexpr int p = 2 * hn + decltype(p_c)::value;
+                    bf16x8 o;
+                    static_for<0, 8>([&](auto q_c) {     // accumulators (mb, 2 p) and (mb, 2 p + 1) are neighbours
+                        constexpr int q = decltype(q_c)::value;
+                        o[q] = (__bf16)acc_read<acc_reg(mb, 2 * p) + q>();
+                    });
+                    const int r = 16 * (mb % 4) + j, c = 4 * (p % 2) + kg;
+                    *reinterpret_cast<bf16x8*>(cs + r * 128 + ((c ^ swz_row(r)) << 4)) = o;
+                });
+            });
+            static_for<0, 8>([&](auto i_c) {
+                const int r = 8 * decltype(i_c)::value + (lane >> 3), pos = lane & 7;
+                const bf16x8 o = *reinterpret_cast<const bf16x8*>(cs + r * 128 + (pos << 4));
+                uint16_t* dst = C + size_t(wrow0 + 64 * hm + r) * ldc + (col0 + wn * TN + 64 * hn + 8 * (pos ^ swz_row(r)));
+#if LOBRA_GP_STORE == 0     // timing variant: only a token store, so that the result is not dead code
+                if (decltype(b_c)::value == 0 && decltype(i_c)::value == 0) __builtin_nontemporal_store(o, reinterpret_cast<bf16x8*>(dst));
                 else asm volatile("" : : "v"(o));
 #elif LOBRA_GP_STORE == 2
-                *reinterpret_cast<bf16x8*>(cp + size_t(16 * mb) * ldc + 32 * p) = o;
+                *reinterpret_cast<bf16x8*>(dst) = o;
 #else
-                __builtin_nontemporal_store(o, reinterpret_cast<bf16x8*>(cp + size_t(16 * mb) * ldc + 32 * p));
+                __builtin_nontemporal_store(o, reinterpret_cast<bf16x8*>(dst));
 #endif
             });
         });
+#endif
         // (the accumulators are not cleared here: the first K step of the next tile starts from zero)
     };
 
@@ -507,14 +550,14 @@ hipError_t launch_persistent(const PlanDev& pd, const void* Z, const void* W, co
         cus[dev].store(ncu, std::memory_order_release);
     }
     const int64_t ntiles = int64_t(tiles_m) * tiles_n;
-#ifdef LOBRA_GP_GRID_TILES      // timing variant: one workgroup per output tile
-    const uint32_t grid = uint32_t(ntiles);
-#else
-    const uint32_t grid = uint32_t(ntiles < ncu ? ntiles : ncu);
-#endif
-    gemm_persistent_kernel<W_KN><<<dim3(grid), 64 * NW, LDS_BYTES, st>>>(
+    const int32_t cpx = ncu >= 8 ? ncu / 8 : 1;
+    const int32_t tpw = LOBRA_GP_TPW;
+    const int64_t xmax = (ntiles + 7) / 8;                                    // tiles of the fullest XCD
+    const int64_t rounds = (xmax + int64_t(cpx) * tpw - 1) / (int64_t(cpx) * tpw);
+    const int64_t wgs = ntiles <= 8 * int64_t(cpx) ? ntiles : 8 * rounds * cpx;   // few tiles: one workgroup each
+    gemm_persistent_kernel<W_KN><<<dim3(uint32_t(wgs)), 64 * NW, LDS_BYTES, st>>>(
         pd, (const uint16_t*)Z, (const uint16_t*)W, (const uint16_t*)P, (const uint16_t*)M, (uint16_t*)C,
-        K, N, ldw, ldc, nproj, proj, tiles_m, tiles_n, gm);
+        K, N, ldw, ldc, nproj, proj, tiles_m, tiles_n, gm, cpx, tpw);
     return hipGetLastError();
 }
 }  // namespace
