@@ -61,7 +61,7 @@ def measure_ceilings(torch, read_bytes):
     res = {"mfma_only_measured_tflops": ncu * 4 * iters * 64 * 2.0 * 16 * 16 * 32 / sec / 1e12}
     sink = torch.zeros(4, dtype=torch.int32, device=dev)
     wgs = ncu * 8
-    n = max(read_bytes // 16 * 16, 1 << 20)
+    n = max(read_bytes // 16 * 16, 64 << 20)
     a = torch.randint(0, 255, (n,), dtype=torch.uint8, device=dev)
     b = torch.empty_like(a)
     big = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_(0, 255)
