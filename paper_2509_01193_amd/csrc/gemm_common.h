@@ -26,6 +26,13 @@ __device__ __forceinline__ int swz_row(int row) { return (row >> 1) & 7; }
 // of a wave sit 8 rows apart: bits 0-1 of k pick the 64-byte quarter, bit 3 the 32-byte half of it.
 __device__ __forceinline__ int kn_swz(int k) { return ((k & 3) << 2) | (((k >> 3) & 1) << 1); }
 
+// The same for the persistent kernel's dealing of columns to MFMA blocks (block_col in gemm_persistent.hip): there
+// the four 8-byte pieces a k row contributes to one transpose read lie in four different 16-byte chunks, in the low
+// or the high half of each by the parity of lane group and block; bits 0-1 of k pick the 64-byte quarter as
+// above, bit 3 the neighbouring chunk - whose piece lies in the other half - so that the k rows 8 apart, which the
+// two lane groups of a 32-lane pass read, never meet in a bank.
+__device__ __forceinline__ int kn_swz2(int k) { return ((k & 3) << 2) | ((k >> 3) & 1); }
+
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v)
 {
     union { u32x4 u; bf16x8 b; } c;

@@ -35,7 +35,7 @@
 // LDS: stage 0, stage 1 (64 KiB each: Z tile then W tile), adapter slice (32 KiB).
 //   Z tile, and the W tile when K is fastest (backward): [256 rows][64 k], 16-byte chunk c of a row
 //       stored at c ^ ((row >> 1) & 7): the 16 rows of one ds_read_b128 pass hit 16 bank groups.
-//   W tile when N is fastest (forward), adapter slice: [k][256 n], chunk c of k-row k stored at c ^ kn_swz(k);
+//   W tile when N is fastest (forward), adapter slice: [k][256 n], chunk c of k-row k stored at c ^ kn_swz2(k);
 //       the MFMA operand (8 consecutive k of one column) is gathered with two ds_read_b64_tr_b16.
 //   A wave-wide direct-to-LDS copy lands in lane order, so the swizzle - and, backward, the dealing of the
 //       columns to the MFMA blocks - is applied to the global address each lane fetches from.
@@ -78,8 +78,13 @@ static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
 
 // Column of the wave tile that MFMA block nb produces in its result row i (= row i of its "A" operand).
 // Lane (j, kg) of a block holds result rows 4 kg .. 4 kg + 3, so with this dealing the blocks 2 p and
-// 2 p + 1 together give it the 8 consecutive columns 32 p + 8 kg .. + 7 of token row j.
-__device__ __forceinline__ int block_col(int nb, int i) { return 32 * (nb >> 1) + 8 * (i >> 2) + 4 * (nb & 1) + (i & 3); }
+// 2 p + 1 together give it the 8 consecutive columns 32 p + 8 kg .. + 7 of token row j: the low four from block
+// 2 p and the high four from block 2 p + 1 when kg is even, the other way round when kg is odd (the alternation
+// is what lets the forward kernel's transpose reads use both halves of every 16-byte chunk, see kn_swz2).
+__device__ __forceinline__ int block_col(int nb, int i)
+{
+    return 32 * (nb >> 1) + 8 * (i >> 2) + 4 * ((nb ^ (i >> 2)) & 1) + (i & 3);
+}
 
 constexpr int acc_reg(int mb, int nb) { return 4 * (NB * mb + nb); }   // first AGPR of accumulator (mb, nb)
 
@@ -157,7 +162,7 @@ void gemm_persistent_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const ui
         zvo[c] = (uint32_t(row) * uint32_t(K) + 8u * ch) * 2u;
         if (W_KN) {
             const int krow = 2 * blk + (lane >> 5);
-            const int chn = (lane & 31) ^ kn_swz(krow);
+            const int chn = (lane & 31) ^ kn_swz2(krow);
             wvo[c] = (uint32_t(krow) * uint32_t(ldw) + 8u * chn) * 2u;
         } else {
             // LDS row `row` of the W tile feeds result row (row & 15) of block (row & 127) >> 4 of wave
@@ -208,11 +213,11 @@ void gemm_persistent_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const ui
     };
     // "A" operand of block nb out of a [k][256 n] tile at `base`: k rows krow0 + 8 kg + (j >> 2) + {0, 4}, the
     // 4-column group (j & 3) of the block - with block_col's dealing that is columns 32 (nb / 2) + 8 (j & 3)
-    // + 4 (nb % 2) .. + 3 of the wave tile
+    // + 4 ((nb + j) % 2) .. + 3 of the wave tile
     auto read_kn = [&](const unsigned char* base, int krow0, int nb) __attribute__((always_inline)) {
         const int krow = krow0 + 8 * kg + (j >> 2);
-        const int n = wn * TN + 32 * (nb >> 1) + 8 * (j & 3) + 4 * (nb & 1);
-        const int ch = (n >> 3) ^ kn_swz(krow);
+        const int n = wn * TN + 32 * (nb >> 1) + 8 * (j & 3) + 4 * ((nb ^ j) & 1);
+        const int ch = (n >> 3) ^ kn_swz2(krow);
         return tr_pair(base + krow * 512 + ch * 16 + (n & 7) * 2, 512);
     };
     auto read_w = [&](const unsigned char* wa, int stage, int ks, int nb, bf16x8 (&wf)[NB]) __attribute__((always_inline)) {
@@ -366,7 +371,7 @@ void gemm_persistent_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const ui
 #pragma unroll
                         for (int q = 0; q < MCH; ++q) {
                             const int32_t ch = base + tid + q * NT, kr = ch >> 5, c = ch & 31;
-                            if (ch < rows * 32) *reinterpret_cast<u32x4*>(ml + kr * 512 + ((c ^ kn_swz(kr)) << 4)) = mreg[q];
+                            if (ch < rows * 32) *reinterpret_cast<u32x4*>(ml + kr * 512 + ((c ^ kn_swz2(kr)) << 4)) = mreg[q];
                         }
                     };
                     fetch_m(0);
@@ -395,6 +400,14 @@ void gemm_persistent_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const ui
             }
             asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
         }
+        // (block_col: a lane with odd kg holds its high four columns in block 2 p and its low four in block 2 p + 1)
+        auto pair_order = [&](bf16x8 o) {
+            union { bf16x8 b; uint64_t h[2]; } u, v;
+            u.b = o;
+            v.h[0] = (kg & 1) ? u.h[1] : u.h[0];
+            v.h[1] = (kg & 1) ? u.h[0] : u.h[1];
+            return v.b;
+        };
         // ---- fp32 -> bf16 (one rounding, to nearest even) and the stores.  Blocks 2 p and 2 p + 1 hold this lane's
         //      columns 32 p + 8 kg .. + 7 of token row j.  Non-temporal, so that y / dx do not evict x / dy from the
         //      caches before the rank-r passes read them.
@@ -411,6 +424,7 @@ void gemm_persistent_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const ui
                     constexpr int q = decltype(q_c)::value;
                     o[q] = (__bf16)acc_read<acc_reg(mb, 2 * p) + q>();
                 });
+                o = pair_order(o);
                 __builtin_nontemporal_store(o, reinterpret_cast<bf16x8*>(cp + size_t(16 * mb) * ldc + 32 * p));
             });
         });
@@ -433,6 +447,7 @@ void gemm_persistent_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const ui
                         constexpr int q = decltype(q_c)::value;
                         o[q] = (__bf16)acc_read<acc_reg(mb, 2 * p) + q>();
                     });
+                    o = pair_order(o);
                     const int r = 16 * (mb % 4) + j, c = 4 * (p % 2) + kg;
                     *reinterpret_cast<bf16x8*>(cs + r * 128 + ((c ^ swz_row(r)) << 4)) = o;
                 });
