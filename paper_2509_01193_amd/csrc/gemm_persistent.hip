@@ -5,34 +5,29 @@
 // (paper section 2.1: X W + X (down)(up); section 1: one shared base product for the fused batch,
 // a per-task adapter product on top of it).
 //
-// One workgroup per compute unit walks a run of 256 x 256 output tiles.  Everything a tile has to pay
-// besides its MFMAs overlaps with MFMAs of a neighbouring tile:
+// One workgroup per compute unit walks a few 256 x 256 output tiles (LOBRA_GP_TPW of them; then the next round of
+// workgroups is dispatched, which re-aligns the compute units of an XCD that share panels through its L2):
 //   * the K tiles of ALL of a workgroup's output tiles form one stream through the two LDS stages: while the
 //     last K tiles of an output tile are multiplied, the first K tiles of the next one are already being
-//     copied, and the operand fragments of its first K step are in registers when the epilogue begins;
+//     copied, so no stage fill is exposed except the very first;
 //   * the epilogue keeps its hands off the two stages: the adapter slice of the fused up projection is staged
-//     in a third LDS region, and the result goes from the accumulators straight to global memory (the
-//     columns of a wave tile are dealt to the MFMA blocks so that a lane holds 8 consecutive columns: 16-byte
-//     stores, 64 contiguous bytes per row and instruction); the stores drain under the next tile's MFMAs.
-// Launching one workgroup per output tile instead costs about 15 us per tile (workgroup start, two exposed
-// stage fills, the epilogue's LDS round trip and store drain) next to 80 us of MFMAs at K = 4096.
+//     in a third LDS region, and the result is rounded, passed through the same region (a 64 x 64 block per wave
+//     at a time) and stored in whole 128-byte lines; the stores drain under the next tile's first MFMAs.
+// One workgroup per output tile instead costs about 15 us per tile (workgroup start, two exposed stage fills,
+// the epilogue and its store drain) next to 80 us of MFMAs at K = 4096; of that the stream hides what is not the
+// stores and the epilogue's own instructions.
 //
 // Tile: 256 x 256 x 64, four waves of 128 x 128 (one per SIMD), blocks of v_mfma_f32_16x16x32_bf16 with the
-// 64 accumulators of a wave in its 256 AGPRs (a loop of nothing but these MFMAs sustains 2.05 PFLOP/s on this
-// chip, one of 32x32x16 blocks 1.79).  The MFMA "A" operand is fed from W and the "B" operand from Z, so a
-// lane ends up with four consecutive output columns of one token row per block.
+// 64 accumulators of a wave in its 256 AGPRs, which the kernel names itself (gemm_common.h).  The MFMA "A"
+// operand is fed from W and the "B" operand from Z, so a lane ends up with four output columns of one token row
+// per block; block_col deals the columns of a wave tile to the blocks so that two blocks give a lane 8
+// consecutive columns.
 // K tiles go global -> LDS with global_load_lds_dwordx4 (no registers, no ds_write); every row segment a copy
 // fetches is one 128-byte line.  With one wave per SIMD nothing hides a wave's own latencies, so the loop is
 // software-pipelined by hand and its order is pinned (the MFMAs are volatile asm statements, sched_barrier
-// between the slots): a K step of 32 is 16 sections of four MFMAs with one other piece of work behind each
-// MFMA: the two instructions of a copy, a fragment read.  The fragments of K step s + 1 are read during
-// step s (the token-side fragment of a row block straight back into its register once the block is done, the
-// other operand into a second register set); the barrier of a K tile stands in front of its last K step,
-// whose fragments are already in registers, so MFMAs and not LDS latency follow the barrier; the stage it
-// frees is refilled by the 16 copies of the K tile after next, one per section of that K step (issued back to
-// back they block their wave for as long as the texture unit takes to accept them).
+// between the slots); see kstep for the schedule of a K step.
 //
-// LDS: stage 0, stage 1 (64 KiB each: Z tile then W tile), adapter slice (32 KiB).
+// LDS: stage 0, stage 1 (64 KiB each: Z tile then W tile), adapter slice / result staging (32 KiB).
 //   Z tile, and the W tile when K is fastest (backward): [256 rows][64 k], 16-byte chunk c of a row
 //       stored at c ^ ((row >> 1) & 7): the 16 rows of one ds_read_b128 pass hit 16 bank groups.
 //   W tile when N is fastest (forward), adapter slice: [k][256 n], chunk c of k-row k stored at c ^ kn_swz2(k);
