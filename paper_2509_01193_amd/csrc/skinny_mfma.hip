@@ -8,6 +8,9 @@
 // each task of the fused batch has its own pair.)
 #include "kernels.h"
 
+#ifndef LOBRA_GRAD_ORDER
+#define LOBRA_GRAD_ORDER 2      // reduction kernels: 2 column tile fastest, 0 chunk fastest, 1 column tile fastest and XCD-contiguous
+#endif
 #ifndef LOBRA_SKINNY_XCD
 #define LOBRA_SKINNY_XCD 1      // work items dealt to the XCDs in contiguous ranges (see xcd_contiguous)
 #endif
@@ -366,10 +369,18 @@ __global__ __launch_bounds__(256) void grad_mfma_kernel(PlanDev pd, GradJob ja, 
 {
     typedef uint32_t zvec __attribute__((ext_vector_type(CW / 2)));
     typedef float ovec __attribute__((ext_vector_type(4)));
-    // The grid is one-dimensional in (chunk, column tile), column tile fastest, and dealt to the XCDs in
-    // contiguous ranges: an XCD then works on whole rows of a few chunks at a time (see xcd_contiguous).
-    const int32_t wi = LOBRA_SKINNY_XCD ? xcd_contiguous(blockIdx.x, gridDim.x) : int32_t(blockIdx.x);
+    // The grid is one-dimensional in (chunk, column tile), column tile fastest, workgroup ids as dispatched
+    // (round-robin over the XCDs): the workgroups in flight at one time then cover whole rows of a few chunks.
+    // Measured against chunk fastest (the order of a two-dimensional grid) and against contiguous ranges per
+    // XCD: 287 / 352 / 484 us at workload 5, 881 / 908 / 972 us at workload 4, 178 / 187 / 182 us at workload 3,
+    // 50 / 51 / 50 us at workload 2 (58 for chunk fastest on a task-sorted batch).
+#if LOBRA_GRAD_ORDER == 0        // chunk fastest, workgroup ids as dispatched
+    const int32_t nch = int32_t(gridDim.x) / tiles_all;
+    const int32_t tile_y = int32_t(blockIdx.x) / nch, chunk_x = int32_t(blockIdx.x) % nch;
+#else
+    const int32_t wi = LOBRA_GRAD_ORDER == 1 ? xcd_contiguous(blockIdx.x, gridDim.x) : int32_t(blockIdx.x);
     const int32_t tile_y = wi % tiles_all, chunk_x = wi / tiles_all;
+#endif
     // one launch serves both gradients: column tiles [0, tiles_a) belong to job a, the rest to job b
     const bool first = tile_y < tiles_a;
     const uint16_t* __restrict__ P_blk = static_cast<const uint16_t*>(first ? ja.P : jb.P);
@@ -501,10 +512,14 @@ __global__ __launch_bounds__(256) void grad_lds_kernel(PlanDev pd, GradJob ja, G
     typedef uint32_t zvec __attribute__((ext_vector_type(CW / 2)));
     typedef float ovec __attribute__((ext_vector_type(4)));
     __shared__ __attribute__((aligned(16))) unsigned char ps[2][16 * NRB * 64];
-    // The grid is one-dimensional in (chunk, column tile), column tile fastest, and dealt to the XCDs in
-    // contiguous ranges: an XCD then works on whole rows of a few chunks at a time (see xcd_contiguous).
-    const int32_t wi = LOBRA_SKINNY_XCD ? xcd_contiguous(blockIdx.x, gridDim.x) : int32_t(blockIdx.x);
+    // (work order as in grad_mfma_kernel)
+#if LOBRA_GRAD_ORDER == 0        // chunk fastest, workgroup ids as dispatched
+    const int32_t nch = int32_t(gridDim.x) / tiles_all;
+    const int32_t tile_y = int32_t(blockIdx.x) / nch, chunk_x = int32_t(blockIdx.x) % nch;
+#else
+    const int32_t wi = LOBRA_GRAD_ORDER == 1 ? xcd_contiguous(blockIdx.x, gridDim.x) : int32_t(blockIdx.x);
     const int32_t tile_y = wi % tiles_all, chunk_x = wi / tiles_all;
+#endif
     const bool first = tile_y < tiles_a;
     const uint16_t* __restrict__ P_blk = static_cast<const uint16_t*>(first ? ja.P : jb.P);
     const uint16_t* __restrict__ Z = static_cast<const uint16_t*>(first ? ja.Z : jb.Z);
