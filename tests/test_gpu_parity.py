@@ -128,7 +128,7 @@ def test_long_batch_at_medium_and_large_rank_takes_the_lds_staged_kernels(rank):
 
 
 @pytest.mark.parametrize("dims", [(8, 8), (16, 24), (64, 64), (72, 8), (8, 1032), (1024, 64), (2048, 256),
-                                  (128, 192), (192, 320), (320, 128)])   # 2, 3 and 5 K tiles of the direct-to-LDS loop
+                                  (128, 192), (192, 320), (320, 128)])
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_extreme_layer_widths(dims, dtype):
     """Smallest legal widths, one K tile, K tails of 8, a single column chunk, long K."""
@@ -138,6 +138,32 @@ def test_extreme_layer_widths(dims, dtype):
                        np.concatenate([[0], np.cumsum(lens)]), [0, 1, 2, 2, -1, 3, 1], 7,
                        s=[2.0, 1.0, 0.25, -3.0], std_x=0.5, std_w=0.1, std_a=0.1, std_b=0.1)
     check_problem(p, label="%s %dx%d" % (dtype, d_in, d_out))
+
+
+@pytest.mark.parametrize("T,d_in,d_out", [
+    (256, 128, 256),      # one output tile, two K tiles: the stream's prologue is the whole product
+    (257, 256, 384),      # one row over a tile: the second tile row is moved up by 255 rows; columns 256 .. 383 likewise
+    (300, 384, 264),      # last column tile moved left by 248 columns
+    (1000, 1024, 776),    # 4 x 4 tiles, both edges ragged, 16 K tiles forward and 12 (+ 8 columns: other kernel) backward
+    (5000, 512, 1280),    # 20 x 5 = 100 tiles forward, 20 x 2 backward: fewer tiles than compute units
+    (9000, 256, 2304),    # 36 x 9 = 324 tiles forward: more than one per compute unit, not a multiple of 8 per XCD
+    (70000, 128, 256),    # 274 tile rows of one column: five tiles for some workgroups, ragged last rounds
+])
+def test_persistent_gemm_tile_edges_and_round_remainders(T, d_in, d_out):
+    """Shapes around the persistent GEMM's assumptions (K a multiple of 128, at least one whole tile): tile rows and
+    columns that are moved inwards, tile counts below, at and above the number of compute units, rounds that do not
+    fill.  Segments are placed so that tile boundaries fall inside segments of every kind."""
+    rng = np.random.default_rng(T + d_in)
+    lens = []
+    while sum(lens) < T:
+        lens.append(int(rng.choice([1, 31, 100, 255, 257, 600])))
+    lens[-1] -= sum(lens) - T
+    seg_task = rng.integers(-1, 3, len(lens))
+    p = wl.make_custom("edges-%dx%dx%d" % (T, d_in, d_out), "bf16", d_in, d_out, [16, 8, 40],
+                       np.concatenate([[0], np.cumsum(lens)]), seg_task, 17, s=[2.0, -1.0, 0.5],
+                       std_x=1.0, std_w=0.05, std_a=0.05, std_b=0.05)
+    rows = None if T <= 9000 else sample_rows(p, 600, seed=1)
+    check_problem(p, rows=rows, label="edges")
 
 
 def test_config3_reversed_rank_pairing():
