@@ -572,6 +572,7 @@ def _fused_base(d_in, dg, ranks, dtype="bf16"):
 
 @pytest.mark.parametrize("n_proj,d_in,dg,ranks", [
     (3, 320, 256, [16, 16, 16, 16]),      # q/k/v at the benchmark's rank; whole K tiles
+    (2, 256, 256, [16, 32, 8]),           # the persistent GEMM in both directions, one launch over both projections
     (2, 264, 192, [8, 16, 32, 64]),       # gate/up, heterogeneous ranks, widths off the tile grid
     (3, 128, 64, [8, 24, 40]),            # windows that are not multiples of 16
     (4, 192, 128, [32]),                  # one task, stacked rank 128
