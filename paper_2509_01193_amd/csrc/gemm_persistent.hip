@@ -295,15 +295,18 @@ void gemm_persistent_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const ui
     //      began (a chain of dependent loads that would otherwise sit in front of the epilogue).
     const u32x4 zero4 = {0u, 0u, 0u, 0u};
     int32_t tab_sg = 0, tab_lo = 0, tab_hi = 0, tab_task = -1, tab_r0 = 0, tab_r1 = 0;
+    // (Table entries are the same for every lane but come from memory the kernel also writes to, so the compiler
+    //  loads them into vector registers; rfl moves them to scalars at once - they live across the main loop.)
+    auto rfl = [](int32_t v) { return __builtin_amdgcn_readfirstlane(v); };
     auto load_table = [&](int32_t row0, int32_t col0) {
         if (!P) return;
-        tab_sg = pd.rowblk_seg[row0 / kRowBlock];
-        tab_lo = pd.cseg_off[tab_sg];
-        tab_hi = pd.cseg_off[tab_sg + 1];
-        tab_task = pd.cseg_task[tab_sg];
+        tab_sg = rfl(pd.rowblk_seg[row0 / kRowBlock]);
+        tab_lo = rfl(pd.cseg_off[tab_sg]);
+        tab_hi = rfl(pd.cseg_off[tab_sg + 1]);
+        tab_task = rfl(pd.cseg_task[tab_sg]);
         const int32_t pj = proj >= 0 ? proj : col0 / pd.dg;
-        const int32_t rw = tab_task >= 0 ? (pd.rank_off[tab_task + 1] - pd.rank_off[tab_task]) / nproj : 0;
-        tab_r0 = tab_task >= 0 ? pd.rank_off[tab_task] + pj * rw : 0;
+        const int32_t rw = tab_task >= 0 ? rfl(pd.rank_off[tab_task + 1] - pd.rank_off[tab_task]) / nproj : 0;
+        tab_r0 = tab_task >= 0 ? rfl(pd.rank_off[tab_task]) + pj * rw : 0;
         tab_r1 = tab_r0 + rw;
     };
     auto epilogue = [&](int32_t row0, int32_t col0) __attribute__((always_inline)) {
@@ -325,14 +328,14 @@ void gemm_persistent_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const ui
             const int32_t mpitch = proj >= 0 ? N : pd.dg;                // row pitch of M
             for (int32_t sg = tab_sg; sg < pd.nseg; ++sg) {
                 const bool cached = sg == tab_sg;
-                const int32_t seg_lo = cached ? tab_lo : pd.cseg_off[sg];
+                const int32_t seg_lo = cached ? tab_lo : rfl(pd.cseg_off[sg]);
                 if (seg_lo >= row_end) break;
-                const int32_t t = cached ? tab_task : pd.cseg_task[sg];
+                const int32_t t = cached ? tab_task : rfl(pd.cseg_task[sg]);
                 if (t < 0) continue;
-                const int32_t seg_hi = cached ? tab_hi : pd.cseg_off[sg + 1];
+                const int32_t seg_hi = cached ? tab_hi : rfl(pd.cseg_off[sg + 1]);
                 const int32_t lo = max(seg_lo, row0), hi = min(seg_hi, row_end);
-                const int32_t r = cached ? tab_r1 - tab_r0 : (pd.rank_off[t + 1] - pd.rank_off[t]) / nproj;
-                const int32_t r0 = cached ? tab_r0 : pd.rank_off[t] + pj * r;
+                const int32_t r = cached ? tab_r1 - tab_r0 : rfl(pd.rank_off[t + 1] - pd.rank_off[t]) / nproj;
+                const int32_t r0 = cached ? tab_r0 : rfl(pd.rank_off[t]) + pj * r;
                 const int32_t rp = (r + 31) & ~31;
                 const bool mine = hi > wrow0 && lo < wrow0 + TM;   // wave-uniform: the segment crosses this wave's rows
                 // the P fragments of a rank step: lane (j, kg) holds the ranks kk + 8 kg .. + 7 of token row j of
