@@ -188,8 +188,10 @@ LOBRA_API lobra_status lobra_mlora_plan_query(const lobra_mlora_plan *plan, int3
  *   s             : device fp32 [n_tasks]
  *   h_save        : device, h_save_bytes, or NULL.  When given, bwd can reuse the
  *                   down-projected activations instead of recomputing them
- *   ws, ws_bytes  : device scratch of at least fwd_ws_bytes; only used (and only checked) when
- *                   h_save is NULL
+ *   ws, ws_bytes  : device scratch of at least fwd_ws_bytes.  With h_save given only its first
+ *                   fwd_ws_bytes - h_save_bytes bytes are used and checked: the partial sums of the
+ *                   K-sliced down projection that long batches of ranks up to 16 take (0 bytes for all
+ *                   other batches, for which ws may then be NULL)
  *   hip_stream    : hipStream_t (NULL = default stream); work is enqueued, not awaited
  * x, W, A, B, s are read only; y and h_save are overwritten. */
 LOBRA_API lobra_status lobra_mlora_plan_fwd(const lobra_mlora_plan *plan, const void *x, const void *W,

@@ -90,7 +90,10 @@ lobra_status fwd_check(const Plan& p, const void* x, const void* W, const void* 
     if (!aligned16(x) || !aligned16(W) || !aligned16(y) || !aligned16(A) || !aligned16(B) ||
         !aligned16(h_save) || !aligned16(ws))
         return LOBRA_ERR_ALIGN;
-    if (adapters && !h_save && (!ws || ws_bytes < p.fwd_ws_bytes)) return LOBRA_ERR_WORKSPACE;
+    // the workspace holds the sliced projection's partial sums (if the plan uses it) and, without h_save, the
+    // projected activations behind them
+    const size_t need = p.fwd_off_p + (h_save ? 0 : p.p_layout.total);
+    if (adapters && need > 0 && (!ws || ws_bytes < need)) return LOBRA_ERR_WORKSPACE;
     return LOBRA_OK;
 }
 
@@ -304,7 +307,7 @@ lobra_status lobra_mlora_plan_fwd(const lobra_mlora_plan* plan, const void* x, c
     rs = fwd_check(p, x, W, A, B, s, y, h_save, ws, ws_bytes);
     if (rs != LOBRA_OK) return rs;
     const bool adapters = !p.tb.empty();
-    void* hbuf = h_save ? h_save : ws;
+    void* hbuf = h_save ? h_save : static_cast<char*>(ws) + p.fwd_off_p;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const PlanDev pd = device_view(p);
     const int dt = p.desc.dtype;
@@ -326,7 +329,8 @@ lobra_status lobra_mlora_plan_fwd(const lobra_mlora_plan* plan, const void* x, c
     char* hb = static_cast<char*>(hbuf);
     if (adapters)   // all projections' down factors are stacked in A: one pass over x
         LOBRA_LAUNCH(p, st, LOBRA_K_SHRINK,
-                     shrink_mfma(pd, x, A, s, hb + p.p_layout.p_tok, hb + p.p_layout.p_blk, pd.d_in, pd.d_in, 1, 0, st));
+                     shrink_mfma(pd, x, A, s, hb + p.p_layout.p_tok, hb + p.p_layout.p_blk, pd.d_in, pd.d_in, 1, 0, st,
+                                 p.sliced_in, static_cast<float*>(ws)));
     if (p.n_proj == 1) {
         LOBRA_LAUNCH(p, st, LOBRA_K_GEMM,
                      gemm_mfma(pd, false, x, W, adapters ? hb + p.p_layout.p_tok : nullptr, B, y, pd.d_in,
@@ -422,12 +426,14 @@ lobra_status lobra_mlora_plan_bwd(const lobra_mlora_plan* plan, const void* x, c
     }
     // bf16 MFMA path
     char* G = adapters ? wsb + p.bwd_off_g : nullptr;
+    float* spart = adapters ? reinterpret_cast<float*>(wsb + p.bwd_off_spart) : nullptr;
     const char* H = static_cast<const char*>(h_saved);
     if (adapters) {
         if (!H) {
             char* Hr = wsb + p.bwd_off_h;
             LOBRA_LAUNCH(p, st, LOBRA_K_SHRINK,
-                         shrink_mfma(pd, x, A, s, Hr + p.p_layout.p_tok, Hr + p.p_layout.p_blk, pd.d_in, pd.d_in, 1, 0, st));
+                         shrink_mfma(pd, x, A, s, Hr + p.p_layout.p_tok, Hr + p.p_layout.p_blk, pd.d_in, pd.d_in, 1, 0, st,
+                                     p.sliced_in, spart));
             H = Hr;
         }
         // G = s dy B^T; with fused projections one launch per projection: its column block of dy
@@ -435,7 +441,8 @@ lobra_status lobra_mlora_plan_bwd(const lobra_mlora_plan* plan, const void* x, c
         for (int32_t j = 0; j < p.n_proj; ++j)
             LOBRA_LAUNCH(p, st, LOBRA_K_SHRINK,
                          shrink_mfma(pd, static_cast<const char*>(dy) + size_t(j) * pd.dg * 2, B, s,
-                                     G + p.p_layout.p_tok, G + p.p_layout.p_blk, pd.dg, pd.d_out, p.n_proj, j, st));
+                                     G + p.p_layout.p_tok, G + p.p_layout.p_blk, pd.dg, pd.d_out, p.n_proj, j, st,
+                                     p.sliced_out, spart));
     }
     if (want_dx && p.desc.T > 0)
         LOBRA_LAUNCH(p, st, LOBRA_K_GEMM,
@@ -540,7 +547,7 @@ lobra_status lobra_mlora_fwd(const lobra_mlora_desc* desc, const void* x, const 
     const size_t img = align256(p->blob_bytes);
     char* rest = static_cast<char*>(ws) + img;
     if (p->desc.T == 0) st = LOBRA_OK;
-    else if (!ws || ws_bytes < img + (h_save ? 0 : p->fwd_ws_bytes)) st = LOBRA_ERR_WORKSPACE;
+    else if (!ws || ws_bytes < img + p->fwd_off_p + (h_save ? 0 : p->p_layout.total)) st = LOBRA_ERR_WORKSPACE;
     else if (!aligned16(ws)) st = LOBRA_ERR_ALIGN;
     else if ((st = fwd_check(*p, x, W, A, B, s, y, h_save, rest, ws_bytes - img)) == LOBRA_OK &&
              (st = upload_oneshot(p, ws, stream)) == LOBRA_OK) {

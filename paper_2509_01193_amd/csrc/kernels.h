@@ -61,9 +61,11 @@ hipError_t gemm_persistent(const PlanDev& pd, bool transW, const void* Z, const 
 bool gemm_mfma_shape_ok(int64_t T, int32_t K, int32_t N, int32_t ldw);
 // P = s_t Z M_t^T in bf16, written token-major [T][r_pad] and block-transposed [ntb][r_pad][32].
 // (ldz: row pitch of Z; nproj > 1: projection `proj` of a fused call - rank window, see the kernel)
+// sliced.nsl > 0 (chosen by the plan, see sliced_shrink_shape) and part != nullptr: the K-sliced kernel with its
+// fp32 partial projections in part [nsl][T][16], followed by the finish kernel.
 hipError_t shrink_mfma(const PlanDev& pd, const void* Z, const void* M, const float* s,
                        void* P_tok, void* P_blk, int32_t D, int32_t ldz, int32_t nproj, int32_t proj,
-                       hipStream_t st);
+                       hipStream_t st, const SlicedShape& sliced = SlicedShape{}, float* part = nullptr);
 
 // Stage 1 of dM_t = sum_i P_i^T Z_i from the block-transposed P; partial sums per reduction chunk.
 // (P = block-transposed bf16 copy; one launch for up to two gradients, jb.P == nullptr: only ja.)

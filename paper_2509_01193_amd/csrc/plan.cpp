@@ -198,17 +198,38 @@ lobra_status build_host_plan(const lobra_mlora_desc* d, uint32_t flags, Plan* p)
             L.p_blk = 0;
             L.total = align_up(size_t(T) * p->r_max * 4, 256);
         }
+        // the K-sliced projection and its partial sums
+        p->sliced_in = p->sliced_out = SlicedShape{};
+        if (p->mfma && ntb > 0) {
+            p->sliced_in = sliced_shrink_shape(int64_t(ntb), p->r_pad, d->d_in);
+            if (p->n_proj == 1) p->sliced_out = sliced_shrink_shape(int64_t(ntb), p->r_pad, d->d_out);
+        }
+        const size_t spart_in = align_up(size_t(p->sliced_in.nsl) * size_t(T) * 64, 256);
+        const size_t spart_out = align_up(size_t(p->sliced_out.nsl) * size_t(T) * 64, 256);
         p->h_save_bytes = L.total;
-        p->fwd_ws_bytes = L.total;
+        p->fwd_off_p = spart_in;
+        p->fwd_ws_bytes = spart_in + L.total;
         p->bwd_off_g = 0;
         p->bwd_off_h = L.total;
         p->bwd_off_part_b = 2 * L.total;
         p->bwd_off_part_a = p->bwd_off_part_b + align_up(size_t(p->part_rows) * size_t(d->d_out) * 4, 256);
-        p->bwd_ws_bytes = p->bwd_off_part_a + align_up(size_t(p->part_rows) * size_t(d->d_in) * 4, 256);
+        p->bwd_off_spart = p->bwd_off_part_a + align_up(size_t(p->part_rows) * size_t(d->d_in) * 4, 256);
+        p->bwd_ws_bytes = p->bwd_off_spart + std::max(spart_in, spart_out);
     } catch (const std::bad_alloc&) {
         return LOBRA_ERR_NOMEM;
     }
     return LOBRA_OK;
+}
+
+SlicedShape sliced_shrink_shape(int64_t ntb, int32_t r_pad, int32_t D)
+{
+    SlicedShape none;
+    // whole slices only (the kernel's copies carry no bound); at least a dozen items per compute unit
+    if (r_pad != 16 || ntb <= 0 || D <= 0 || D % 512 != 0) return none;
+    const int64_t nsl = D / 512;
+    const int64_t items = ntb * nsl;
+    if (items < 3072 || items >= 0x7fffffff) return none;
+    return SlicedShape{1, int32_t(nsl)};
 }
 
 std::vector<int32_t> pack_blob(Plan* p)

@@ -17,6 +17,15 @@ constexpr int64_t kPlainMaxTokens = 65535 * 64;   // the plain kernels put 64-to
 struct TokenBlock { int32_t row0, nrows, task, rank_row0; };
 struct GradChunk  { int32_t tb_begin, tb_end, task, part_row0; };
 
+// The rank-r projection of a long batch of ranks up to 16 cuts K into slices of 512 columns and lets one
+// workgroup per compute unit walk (token block, slice) items (shrink_sliced_kernel).  nsl = slices; nsl = 0: the
+// one-block-per-workgroup kernels are used.  (m = slabs of 128 columns per wave and item: always 1.)
+struct SlicedShape { int32_t m = 0, nsl = 0; };
+constexpr int kSlicedGrid = 256;      // its workgroups: 8 XCDs x 32 compute units
+// The shape for ntb token blocks projected from width D, or none: widths that are not a multiple of the slice,
+// other ranks, too few items to keep every compute unit busy.
+SlicedShape sliced_shrink_shape(int64_t ntb, int32_t r_pad, int32_t D);
+
 // Byte offsets of the sub-buffers inside h_save and the workspaces.
 struct BufferLayout {
     size_t p_tok = 0;     // token-major projected activations  [T][pstride]
@@ -50,6 +59,11 @@ struct Plan {
     BufferLayout p_layout;              // layout of h_save (and of the G buffer in bwd)
     size_t h_save_bytes = 0, fwd_ws_bytes = 0, bwd_ws_bytes = 0;
     size_t bwd_off_g = 0, bwd_off_h = 0, bwd_off_part_b = 0, bwd_off_part_a = 0;
+    // K-sliced projection: its shape for the projection from d_in (x, A) and from d_out (dy, B), and where its
+    // fp32 partial projections [nsl][T][16] go: at the start of the forward workspace (the projected
+    // activations follow at fwd_off_p unless the caller gives h_save), at bwd_off_spart in the backward one
+    SlicedShape sliced_in, sliced_out;
+    size_t fwd_off_p = 0, bwd_off_spart = 0;
 
     // optional launch trace (see lobra_mlora_plan_set_trace)
     mutable void* const* trace_events = nullptr;

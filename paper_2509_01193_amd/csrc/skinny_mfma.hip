@@ -6,6 +6,9 @@
 //                    Z = dy; dA from P = s g, Z = x), partial sums per chunk
 // (paper section 2.1: the two low-rank factors of X (down)(up) and their gradients; section 1:
 // each task of the fused batch has its own pair.)
+#include <atomic>
+
+#include "gemm_common.h"
 #include "kernels.h"
 
 #ifndef LOBRA_GRAD_ORDER
@@ -321,11 +324,235 @@ __global__ __launch_bounds__(256) void shrink_lds_kernel(PlanDev pd, const uint1
     }
 }
 
+// -------------------------------------------------------------------------------------------------
+// shrink for ranks up to 16 on long batches: K is cut into slices of 512 columns, a work item is (token
+// block, slice), and one workgroup per compute unit walks a contiguous range of the items of its XCD's
+// token blocks in slice-major order.  What the one-block-per-workgroup kernel above loses on such a batch,
+// measured: (a) its workgroups all start, stream and finish in step, so the dependent loads at the start
+// and the reduction and stores at the end of a block are exposed once per launch with nothing behind them;
+// (b) a compute unit sustains about 20 GB/s of token rows however many workgroups it holds, so a launch of
+// 513 blocks on 256 compute units takes as long as one of 768 (one unit gets three blocks instead of two);
+// (c) the adapter rows are a third of what passes through the vector memory path.  Here a wave keeps the
+// adapter columns of its part of the slice in registers for as long as task and slice stay the same (they are
+// read once per dozen token blocks), the loads of the next three items are in flight while an item is
+// multiplied, reduced and stored, and the items are dealt to the workgroups to within one item.
+// The eight waves of a workgroup share an item: wave (h, w) takes token half h (16 tokens) and the 128 columns
+// number w of the slice; the four waves of a half add their sums through LDS (fixed order) and wave (h, 0)
+// writes the fp32 partial projection part[slice][token][16]; the finish kernel below adds the slices in
+// order, scales, rounds and writes both bf16 layouts.
+// The token rows go global -> LDS without passing through registers (global_load_lds_dwordx4, lane-linear:
+// the lane that fetched 16 bytes reads them back as its MFMA operand), into a ring of R slots of 4 KiB per
+// wave.  The compiler does not see these copies, so the kernel places their waits itself (s_waitcnt vmcnt
+// with the number of younger copies): with ordinary loads under the loop's conditions the compiler's own
+// waits drained every wave's prefetched loads at every item.  For the same reason the item barrier is a bare
+// s_barrier (no fence), and the tables are restrict-qualified arguments of their own rather than members of
+// the plan structure: only then are they read with scalar loads, which vmcnt does not count.
+// -------------------------------------------------------------------------------------------------
+constexpr int kSlicedRing = 4;                                     // ring slots per wave
+constexpr int kSlicedLds = 8 * kSlicedRing * 4096 + 2 * 8 * 64 * 16;   // rings + the two reduction buffers
+
+__global__ __launch_bounds__(512) void shrink_sliced_kernel(const TokenBlock* __restrict__ tbs,
+                                                           const int32_t* __restrict__ rank_off, int32_t ntb,
+                                                           int32_t T, const uint16_t* __restrict__ Z,
+                                                           const uint16_t* __restrict__ Mx,
+                                                           float* __restrict__ part, int32_t D, int32_t ldz,
+                                                           int32_t nsl)
+{
+    constexpr int R = kSlicedRing;
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(int(threadIdx.x >> 6));
+    const int h = wave >> 2, w = wave & 3;
+    const int j = lane & 15, kg = lane >> 4;
+    unsigned char* ring = lds + wave * (R * 4096);                 // this wave's ring
+    const uint32_t ring_addr = uint32_t(uintptr_t((__attribute__((address_space(3))) unsigned char*)ring));
+    float* red = reinterpret_cast<float*>(lds + 8 * R * 4096);     // [item parity][wave][lane][4]
+
+    // consecutive workgroup ids run on different XCDs: XCD x takes the token blocks [bx0, bx1) - a
+    // contiguous piece of the activation tensor when the batch is sorted - and its workgroups split the
+    // items (slice, block) of that piece, slice-major, into contiguous ranges
+    const int32_t per_xcd = int32_t(gridDim.x >> 3), xcd = int32_t(blockIdx.x & 7), idx = int32_t(blockIdx.x >> 3);
+    const int32_t bx0 = int32_t((int64_t(ntb) * xcd) >> 3), bx1 = int32_t((int64_t(ntb) * (xcd + 1)) >> 3);
+    const int32_t nbx = bx1 - bx0;
+    const int64_t nit = int64_t(nbx) * nsl;
+    const int32_t e0 = int32_t(nit * idx / per_xcd), e1 = int32_t(nit * (idx + 1) / per_xcd);
+    const int32_t n = e1 - e0;                   // the same for all waves of the workgroup
+    if (n <= 0) return;
+
+    struct Cursor { int32_t sl, bo, slot; };     // slice, block offset inside the XCD's piece, ring slot
+    auto advance = [&](Cursor& c) {
+        if (++c.bo == nbx) { c.bo = 0; ++c.sl; }
+        if (++c.slot == R) c.slot = 0;
+    };
+    // the four copies of an item: lane (j, kg) of copy q fetches the 8 columns 32 q + 8 kg .. + 7 of its row
+    // out of this wave's 128 columns (one 64-byte piece per four lanes, a 256-byte run of the row in all);
+    // rows beyond the block repeat its last row (what they produce is never stored)
+    auto issue = [&](const Cursor& c) {
+        const TokenBlock b = tbs[bx0 + c.bo];
+        const unsigned char* base = reinterpret_cast<const unsigned char*>(Z) +
+                                    (size_t(b.row0) * ldz + size_t(c.sl) * 512 + w * 128) * 2;
+        const uint32_t voff = (uint32_t(min(16 * h + j, b.nrows - 1)) * uint32_t(ldz) + 8u * kg) * 2u;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) gemm::dma16(ring_addr + c.slot * 4096 + q * 1024, base + q * 64, voff);
+    };
+
+    u32x4 av[4];                                 // the adapter columns of this wave's part of the slice
+    int32_t cur_task = -1, cur_sl = -1;
+    auto consume = [&](const Cursor& c, int32_t it) {
+        const TokenBlock b = tbs[bx0 + c.bo];
+        if (b.task != cur_task || c.sl != cur_sl) {          // uniform; once per dozen items
+            const int32_t r = rank_off[b.task + 1] - b.rank_row0;
+            // rank rows beyond r_t repeat a valid row; the finish kernel drops what they produce
+            const uint16_t* mrow = Mx + size_t(b.rank_row0 + min(j, r - 1)) * D + c.sl * 512 + w * 128 + 8 * kg;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) av[q] = *reinterpret_cast<const u32x4*>(mrow + 32 * q);
+            // the values are "used" here so that the compiler waits for them inside this branch: a wait behind
+            // the branch would also wait, at every item, for the copies in flight
+#pragma unroll
+            for (int q = 0; q < 4; ++q) asm volatile("" : "+v"(av[q]));
+            cur_task = b.task;
+            cur_sl = c.sl;
+        }
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const u32x4 zv = *reinterpret_cast<const u32x4*>(ring + c.slot * 4096 + q * 1024 + lane * 16);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(av[q]), as_bf16x8(zv), acc, 0, 0, 0);
+        }
+        float* rbuf = red + (it & 1) * (8 * 64 * 4);
+        *reinterpret_cast<f32x4*>(rbuf + (wave * 64 + lane) * 4) = acc;
+        // one barrier per item: the next write to this half of red follows the next item's barrier,
+        // which wave (h, 0) reaches only after the reads below
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");           // the reads below stay behind the barrier
+        if (w == 0) {
+            const f32x4 s0 = *reinterpret_cast<const f32x4*>(rbuf + ((4 * h + 0) * 64 + lane) * 4);
+            const f32x4 s1 = *reinterpret_cast<const f32x4*>(rbuf + ((4 * h + 1) * 64 + lane) * 4);
+            const f32x4 s2 = *reinterpret_cast<const f32x4*>(rbuf + ((4 * h + 2) * 64 + lane) * 4);
+            const f32x4 s3 = *reinterpret_cast<const f32x4*>(rbuf + ((4 * h + 3) * 64 + lane) * 4);
+            const int32_t tok = 16 * h + j;
+            if (tok < b.nrows)     // lane (j, kg): ranks 4 kg .. 4 kg + 3 of token j
+                *reinterpret_cast<f32x4*>(part + (size_t(c.sl) * T + b.row0 + tok) * 16 + 4 * kg) = ((s0 + s1) + s2) + s3;
+        }
+    };
+
+    Cursor pc, cc;                               // next item to fetch, next item to consume
+    pc.sl = e0 / nbx;
+    pc.bo = e0 - pc.sl * nbx;
+    pc.slot = 0;
+    cc = pc;
+    if (n >= R - 1) {
+        for (int d = 0; d < R - 1; ++d) {
+            issue(pc);
+            advance(pc);
+        }
+        // vector memory operations complete in order: with the copies of R - 1 younger items behind it, an
+        // item has landed when at most 4 (R - 1) operations are outstanding (wave (h, 0)'s stores also count:
+        // they only make the wait stricter)
+        int32_t it = 0;
+        for (; it + R - 1 < n; ++it) {
+            issue(pc);
+            advance(pc);
+            gemm::wait_vmcnt<4 * (R - 1)>();
+            consume(cc, it);
+            advance(cc);
+        }
+        gemm::static_for<0, R - 1>([&](auto t) {
+            gemm::wait_vmcnt<4 * (R - 2 - decltype(t)::value)>();
+            consume(cc, it);
+            advance(cc);
+            ++it;
+        });
+    } else {
+        for (int32_t it = 0; it < n; ++it) {
+            issue(pc);
+            advance(pc);
+            gemm::wait_vmcnt<0>();
+            consume(cc, it);
+            advance(cc);
+        }
+    }
+}
+
+// Second pass of the sliced projection: P = s_t * (sum of the slices' partial projections, in slice order),
+// rounded to bf16 and written token-major and block-transposed.  Two token blocks per workgroup; thread
+// (block, token, kg) owns the ranks 4 kg .. 4 kg + 3 of its token.
+__global__ __launch_bounds__(256) void shrink_finish_kernel(PlanDev pd, const float* __restrict__ part,
+                                                           const float* __restrict__ s,
+                                                           uint16_t* __restrict__ P_tok,
+                                                           uint16_t* __restrict__ P_blk, int32_t nsl)
+{
+    const int32_t bi = int32_t(blockIdx.x) * 2 + int32_t(threadIdx.x >> 7);
+    if (bi >= pd.ntb) return;
+    const int tok = (threadIdx.x >> 2) & 31, kg = threadIdx.x & 3;
+    const TokenBlock b = pd.tb[bi];
+    const int32_t r = pd.rank_off[b.task + 1] - b.rank_row0;
+    const bool live = tok < b.nrows;
+    f32x4 sum = {0.f, 0.f, 0.f, 0.f};
+    if (live) {
+        const float* p = part + size_t(b.row0 + tok) * 16 + 4 * kg;
+        const size_t pitch = size_t(pd.T) * 16;
+        int32_t sl = 0;
+        for (; sl + 4 <= nsl; sl += 4) {         // four loads in flight, added in slice order
+            const f32x4 v0 = *reinterpret_cast<const f32x4*>(p + (sl + 0) * pitch);
+            const f32x4 v1 = *reinterpret_cast<const f32x4*>(p + (sl + 1) * pitch);
+            const f32x4 v2 = *reinterpret_cast<const f32x4*>(p + (sl + 2) * pitch);
+            const f32x4 v3 = *reinterpret_cast<const f32x4*>(p + (sl + 3) * pitch);
+            sum = (((sum + v0) + v1) + v2) + v3;
+        }
+        for (; sl < nsl; ++sl) sum = sum + *reinterpret_cast<const f32x4*>(p + sl * pitch);
+    }
+    const float st = s[b.task];
+    bf16x4 o;
+#pragma unroll
+    for (int v = 0; v < 4; ++v) o[v] = (__bf16)((live && 4 * kg + v < r) ? st * sum[v] : 0.f);
+    if (live) *reinterpret_cast<bf16x4*>(P_tok + size_t(b.row0 + tok) * pd.r_pad + 4 * kg) = o;
+    // block-transposed copy [block][rank][32 tokens]; tokens beyond the block hold 0
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+        union { __bf16 b; uint16_t u; } c;
+        c.b = o[v];
+        P_blk[(size_t(bi) * pd.r_pad + 4 * kg + v) * kTokenBlock + tok] = c.u;
+    }
+}
+
+namespace {
+// once per device: the sliced kernel's rings need more dynamic LDS than the default limit
+hipError_t sliced_setup()
+{
+    static std::atomic<int32_t> done[64];
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    if (done[dev].load(std::memory_order_acquire) == 0) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&shrink_sliced_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, kSlicedLds);
+        if (e != hipSuccess) return e;
+        done[dev].store(1, std::memory_order_release);
+    }
+    return hipSuccess;
+}
+}  // namespace
+
 hipError_t shrink_mfma(const PlanDev& pd, const void* Z, const void* M, const float* s,
                        void* P_tok, void* P_blk, int32_t D, int32_t ldz, int32_t nproj, int32_t proj,
-                       hipStream_t st)
+                       hipStream_t st, const SlicedShape& sliced, float* part)
 {
     if (pd.ntb == 0) return hipSuccess;
+    if (sliced.nsl > 0 && part && nproj == 1) {
+        hipError_t e = sliced_setup();
+        if (e != hipSuccess) return e;
+        // a fixed grid - one workgroup per compute unit of the chip this is written for - so that the split
+        // of the items, and with it the order of every sum, does not depend on the device
+        shrink_sliced_kernel<<<kSlicedGrid, 512, kSlicedLds, st>>>(pd.tb, pd.rank_off, pd.ntb, pd.T, (const uint16_t*)Z,
+                                                               (const uint16_t*)M, part, D, ldz, sliced.nsl);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        shrink_finish_kernel<<<(pd.ntb + 1) / 2, 256, 0, st>>>(pd, part, s, (uint16_t*)P_tok, (uint16_t*)P_blk, sliced.nsl);
+        return hipGetLastError();
+    }
     // rank blocks of the widest window (nproj = 1: of the widest task)
     const int nrb = (pd.r_max / nproj + 15) / 16;
     if (pd.shrink_group == 4 && nproj == 1 && ldz == D) {
