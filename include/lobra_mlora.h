@@ -175,10 +175,21 @@ LOBRA_API lobra_status lobra_mlora_plan_sizes(const lobra_mlora_plan *plan, size
  *                        projected by one workgroup
  *   LOBRA_Q_BLOCK_ORDER  order in which the token blocks are handed to the down-projection's
  *   LOBRA_Q_RUN_ORDER    workgroups, and the same for the runs: a permutation by descending rank
- *                        (stable), or empty when that is the stored order (e.g. equal ranks) */
+ *                        (stable), or empty when that is the stored order (e.g. equal ranks)
+ *   LOBRA_Q_SLICED       {slices_in, slices_out, fused_db, fused_rows, workgroups}: long batches of ranks up
+ *                        to 16 are projected by a fixed grid of `workgroups` workgroups that walk (token block,
+ *                        512-column slice) items (slices_* = number of slices of d_in / d_out, 0 = the
+ *                        one-block-per-workgroup kernels are used for that direction); fused_db = 1: the backward
+ *                        projection of dy accumulates dB in the same pass, its sums in fused_rows rows
+ *   LOBRA_Q_FUSED_WG_RUNS  [workgroups + 1]: the runs of items of one (task, slice) that workgroup g meets are
+ *                        number wg_runs[g] .. wg_runs[g + 1] - 1 (all four lists are empty unless fused_db)
+ *   LOBRA_Q_FUSED_RUN_ROW  per run: first of its 16 rows in the array of dB sums
+ *   LOBRA_Q_FUSED_COUNT  [n_tasks * slices_out]: runs of (task t, slice c) over all workgroups; its k-th run sits
+ *   LOBRA_Q_FUSED_TASK_ROW  at row task_row[t] + 16 k */
 enum { LOBRA_Q_SEGMENTS = 0, LOBRA_Q_ROWBLOCK_SEG = 1, LOBRA_Q_TOKEN_BLOCKS = 2,
        LOBRA_Q_GRAD_CHUNKS = 3, LOBRA_Q_TASK_CHUNKS = 4, LOBRA_Q_BLOCK_RUNS = 5,
-       LOBRA_Q_BLOCK_ORDER = 6, LOBRA_Q_RUN_ORDER = 7 };
+       LOBRA_Q_BLOCK_ORDER = 6, LOBRA_Q_RUN_ORDER = 7, LOBRA_Q_SLICED = 8, LOBRA_Q_FUSED_WG_RUNS = 9,
+       LOBRA_Q_FUSED_RUN_ROW = 10, LOBRA_Q_FUSED_COUNT = 11, LOBRA_Q_FUSED_TASK_ROW = 12 };
 LOBRA_API lobra_status lobra_mlora_plan_query(const lobra_mlora_plan *plan, int32_t what, int32_t *out,
                                     size_t capacity, size_t *count);
 

@@ -31,6 +31,10 @@ PlanDev device_view(const Plan& p)
     d.sb_off = b + p.o_sb;
     d.tb_order = p.tb_order.empty() ? nullptr : b + p.o_tb_order;
     d.sb_order = p.sb_order.empty() ? nullptr : b + p.o_sb_order;
+    d.fb_wg_run_off = p.fused_db ? b + p.o_fb_wg : nullptr;
+    d.fb_run_row = p.fused_db ? b + p.o_fb_run : nullptr;
+    d.fb_cnt = p.fused_db ? b + p.o_fb_cnt : nullptr;
+    d.fb_task_row0 = p.fused_db ? b + p.o_fb_row0 : nullptr;
     d.T = int32_t(p.desc.T);
     d.d_in = p.desc.d_in;
     d.d_out = p.desc.d_out;
@@ -288,6 +292,27 @@ lobra_status lobra_mlora_plan_query(const lobra_mlora_plan* plan, int32_t what, 
         src = plan->sb_order.data();
         n = plan->sb_order.size();
         break;
+    case LOBRA_Q_SLICED:
+        tmp = {plan->sliced_in.nsl, plan->sliced_out.nsl, plan->fused_db ? 1 : 0, plan->fb_rows, kSlicedGrid};
+        src = tmp.data();
+        n = tmp.size();
+        break;
+    case LOBRA_Q_FUSED_WG_RUNS:
+        src = plan->fb_wg_run_off.data();
+        n = plan->fb_wg_run_off.size();
+        break;
+    case LOBRA_Q_FUSED_RUN_ROW:
+        src = plan->fb_run_row.data();
+        n = plan->fb_run_row.size();
+        break;
+    case LOBRA_Q_FUSED_COUNT:
+        src = plan->fb_cnt.data();
+        n = plan->fb_cnt.size();
+        break;
+    case LOBRA_Q_FUSED_TASK_ROW:
+        src = plan->fb_task_row0.data();
+        n = plan->fb_task_row0.size();
+        break;
     default:
         return LOBRA_ERR_SHAPE;
     }
@@ -427,6 +452,8 @@ lobra_status lobra_mlora_plan_bwd(const lobra_mlora_plan* plan, const void* x, c
     // bf16 MFMA path
     char* G = adapters ? wsb + p.bwd_off_g : nullptr;
     float* spart = adapters ? reinterpret_cast<float*>(wsb + p.bwd_off_spart) : nullptr;
+    // dB in the same pass over dy as G = s dy B^T (then stage 1 below is dA alone)
+    const bool fused_db = adapters && p.fused_db && p.R_tot > 0;
     const char* H = static_cast<const char*>(h_saved);
     if (adapters) {
         if (!H) {
@@ -442,7 +469,7 @@ lobra_status lobra_mlora_plan_bwd(const lobra_mlora_plan* plan, const void* x, c
             LOBRA_LAUNCH(p, st, LOBRA_K_SHRINK,
                          shrink_mfma(pd, static_cast<const char*>(dy) + size_t(j) * pd.dg * 2, B, s,
                                      G + p.p_layout.p_tok, G + p.p_layout.p_blk, pd.dg, pd.d_out, p.n_proj, j, st,
-                                     p.sliced_out, spart));
+                                     p.sliced_out, spart, fused_db ? H + p.p_layout.p_blk : nullptr, part_b));
     }
     if (want_dx && p.desc.T > 0)
         LOBRA_LAUNCH(p, st, LOBRA_K_GEMM,
@@ -452,7 +479,13 @@ lobra_status lobra_mlora_plan_bwd(const lobra_mlora_plan* plan, const void* x, c
         // dB (from s h and dy) and dA (from s g and x) share one launch per stage
         GradJob jb{adapters ? H + p.p_layout.p_blk : nullptr, dy, part_b, dB, pd.dg};
         const GradJob ja{adapters ? G + p.p_layout.p_blk : nullptr, x, part_a, dA, pd.d_in};
-        if (p.n_proj == 1) {
+        if (fused_db) {
+            const GradJob none{nullptr, nullptr, nullptr, nullptr, 0};
+            LOBRA_LAUNCH(p, st, LOBRA_K_GRAD_STAGE1, grad_mfma(pd, ja, none, st));
+            jb.fcnt = pd.fb_cnt;
+            jb.frow0 = pd.fb_task_row0;
+            jb.fnsl = p.sliced_out.nsl;
+        } else if (p.n_proj == 1) {
             if (adapters) LOBRA_LAUNCH(p, st, LOBRA_K_GRAD_STAGE1, grad_mfma(pd, jb, ja, st));
         } else if (adapters) {
             // dA over all stacked ranks in one pass over x; dB per projection (its column block of dy,

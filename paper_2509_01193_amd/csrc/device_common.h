@@ -20,6 +20,11 @@ struct PlanDev {
     const int32_t* sb_off;         // [nsb+1]
     const int32_t* tb_order;       // [ntb] launch order of the token blocks, or NULL = as stored
     const int32_t* sb_order;       // [nsb] launch order of the runs, or NULL = as stored
+    // dB fused into the sliced projection of dy (NULL when the plan does not use it, see Plan::fused_db)
+    const int32_t* fb_wg_run_off;  // [kSlicedGrid + 1]
+    const int32_t* fb_run_row;     // [runs] first row of the run's partial sums
+    const int32_t* fb_cnt;         // [n_tasks * slices] runs of (task, slice)
+    const int32_t* fb_task_row0;   // [n_tasks] row of the first run of (task, any slice)
     int32_t T, d_in, d_out, n_tasks, nseg, ntb, nchunks, r_max, r_pad, R_tot, nsb, shrink_group, n_proj, dg;
 };
 

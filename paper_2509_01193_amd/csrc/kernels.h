@@ -18,6 +18,11 @@ struct GradJob {
     int32_t proj = 0;   //   proj < 0: D spans all projections (nproj * dg columns, dg a multiple of 128)
                         //   and a column tile takes the projection its columns lie in
     int32_t ldp = 0;    // row pitch of part (0: D); dg when proj < 0
+    // stage 2 only: part holds the sums of the fused projection-and-dB pass instead of chunk sums: the k-th run
+    // of (task t, 512-column slice c) at rows frow0[t] + 16 k .. + 15, fcnt[t * fnsl + c] of them
+    const int32_t* fcnt = nullptr;
+    const int32_t* frow0 = nullptr;
+    int32_t fnsl = 0;
 };
 
 // ---- plain fp32-FMA kernels (fp32 path; bf16 storage as a cross-check) ---------------------
@@ -62,10 +67,14 @@ bool gemm_mfma_shape_ok(int64_t T, int32_t K, int32_t N, int32_t ldw);
 // P = s_t Z M_t^T in bf16, written token-major [T][r_pad] and block-transposed [ntb][r_pad][32].
 // (ldz: row pitch of Z; nproj > 1: projection `proj` of a fused call - rank window, see the kernel)
 // sliced.nsl > 0 (chosen by the plan, see sliced_shrink_shape) and part != nullptr: the K-sliced kernel with its
-// fp32 partial projections in part [nsl][T][16], followed by the finish kernel.
+// fp32 partial projections in part [nsl][T][16], followed by the finish kernel.  Hblk, partb (and a plan with
+// fused_db): the same pass also accumulates sum_i Hblk_i^T Z_i (dB when Z = dy and Hblk = the block-transposed
+// s_t h) into partb [fb_rows][D], to be added up by reduce_partials (GradJob::fcnt).
+
 hipError_t shrink_mfma(const PlanDev& pd, const void* Z, const void* M, const float* s,
                        void* P_tok, void* P_blk, int32_t D, int32_t ldz, int32_t nproj, int32_t proj,
-                       hipStream_t st, const SlicedShape& sliced = SlicedShape{}, float* part = nullptr);
+                       hipStream_t st, const SlicedShape& sliced = SlicedShape{}, float* part = nullptr,
+                       const void* Hblk = nullptr, float* partb = nullptr);
 
 // Stage 1 of dM_t = sum_i P_i^T Z_i from the block-transposed P; partial sums per reduction chunk.
 // (P = block-transposed bf16 copy; one launch for up to two gradients, jb.P == nullptr: only ja.)

@@ -338,12 +338,19 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(PlanDev pd, GradJo
     int32_t t = 0;
     while (pd.rank_off[t + 1] <= R) ++t;
     const int32_t p = R - pd.rank_off[t];
-    const int32_t c0 = pd.task_chunk_off[t], c1 = pd.task_chunk_off[t + 1];
     const int32_t col = coltile * 1024 + threadIdx.x * 4;
     if (col >= D) return;
+    // the partial sums of a task: one per reduction chunk, or (fcnt) one per run of the fused pass that covers
+    // this thread's 512-column slice
+    const int32_t* fcnt = first ? ja.fcnt : jb.fcnt;
+    const int32_t c0 = fcnt ? 0 : pd.task_chunk_off[t];
+    const int32_t c1 = fcnt ? fcnt[t * (first ? ja.fnsl : jb.fnsl) + (col >> 9)] : pd.task_chunk_off[t + 1];
+    const int32_t frow = fcnt ? (first ? ja.frow0 : jb.frow0)[t] + p : 0;
     const int nv = min(4, D - col);                 // D need not be a multiple of 4 on the fp32 path
     float acc[4] = {0.f, 0.f, 0.f, 0.f};
-    auto row_ptr = [&](int32_t c) { return part + size_t(pd.chunks[c].part_row0 + p) * D + col; };
+    auto row_ptr = [&](int32_t c) {
+        return part + size_t(fcnt ? frow + 16 * c : pd.chunks[c].part_row0 + p) * D + col;
+    };
     if (nv == 4 && (D & 3) == 0) {
         typedef float f4 __attribute__((ext_vector_type(4)));
         int32_t c = c0;

@@ -204,6 +204,60 @@ lobra_status build_host_plan(const lobra_mlora_desc* d, uint32_t flags, Plan* p)
             p->sliced_in = sliced_shrink_shape(int64_t(ntb), p->r_pad, d->d_in);
             if (p->n_proj == 1) p->sliced_out = sliced_shrink_shape(int64_t(ntb), p->r_pad, d->d_out);
         }
+        // dB fused into the sliced projection of dy: the runs of (task, slice) that every workgroup meets, by
+        // the same split of the items as the kernel's (shrink_sliced_kernel)
+        p->fused_db = false;
+        p->fb_wg_run_off.clear();
+        p->fb_run_row.clear();
+        p->fb_cnt.clear();
+        p->fb_task_row0.clear();
+        p->fb_rows = 0;
+        if (p->sliced_out.nsl > 0) {
+            const int32_t nsl = p->sliced_out.nsl, per_xcd = kSlicedGrid / 8, ntb32 = int32_t(ntb);
+            std::vector<int32_t> run_task, run_k;
+            p->fb_cnt.assign(size_t(n) * nsl, 0);
+            p->fb_wg_run_off.assign(1, 0);
+            for (int32_t wg = 0; wg < kSlicedGrid; ++wg) {
+                const int32_t xcd = wg & 7, idx = wg >> 3;
+                const int32_t bx0 = int32_t((int64_t(ntb32) * xcd) >> 3), bx1 = int32_t((int64_t(ntb32) * (xcd + 1)) >> 3);
+                const int32_t nbx = bx1 - bx0;
+                const int64_t nit = int64_t(nbx) * nsl;
+                int64_t e = nit * idx / per_xcd;
+                const int64_t e1 = nit * (idx + 1) / per_xcd;
+                while (e < e1) {
+                    const int32_t sl = int32_t(e / nbx), bo = int32_t(e - int64_t(sl) * nbx);
+                    const int32_t t = p->tb[size_t(bx0 + bo)].task;
+                    // the run ends with the workgroup's range, the slice, or the task's blocks inside the piece
+                    const int64_t task_end = int64_t(sl) * nbx + std::min<int64_t>(nbx, p->task_tb_off[t + 1] - bx0);
+                    const int64_t next = std::min(e1, task_end);
+                    run_task.push_back(t);
+                    run_k.push_back(p->fb_cnt[size_t(t) * nsl + sl]++);
+                    e = next;
+                }
+                p->fb_wg_run_off.push_back(int32_t(run_task.size()));
+            }
+            p->fb_task_row0.assign(size_t(n), 0);
+            int64_t rows = 0;
+            for (int32_t t = 0; t < n; ++t) {
+                int32_t most = 0;
+                for (int32_t sl = 0; sl < nsl; ++sl) most = std::max(most, p->fb_cnt[size_t(t) * nsl + sl]);
+                p->fb_task_row0[t] = int32_t(rows);
+                rows += int64_t(most) * 16;
+            }
+            // worth it while the partial sums stay a small part of the pass over dy (4 bytes x rows per column,
+            // written and read once, against 2 bytes x T)
+            if (rows > 0 && rows <= int64_t(T) / 8 && rows < 0x7fffffff / 2) {
+                p->fused_db = true;
+                p->fb_rows = int32_t(rows);
+                p->fb_run_row.resize(run_task.size());
+                for (size_t i = 0; i < run_task.size(); ++i)
+                    p->fb_run_row[i] = p->fb_task_row0[run_task[i]] + 16 * run_k[i];
+            } else {
+                p->fb_wg_run_off.clear();
+                p->fb_cnt.clear();
+                p->fb_task_row0.clear();
+            }
+        }
         const size_t spart_in = align_up(size_t(p->sliced_in.nsl) * size_t(T) * 64, 256);
         const size_t spart_out = align_up(size_t(p->sliced_out.nsl) * size_t(T) * 64, 256);
         p->h_save_bytes = L.total;
@@ -212,7 +266,9 @@ lobra_status build_host_plan(const lobra_mlora_desc* d, uint32_t flags, Plan* p)
         p->bwd_off_g = 0;
         p->bwd_off_h = L.total;
         p->bwd_off_part_b = 2 * L.total;
-        p->bwd_off_part_a = p->bwd_off_part_b + align_up(size_t(p->part_rows) * size_t(d->d_out) * 4, 256);
+        // (with dB fused into the projection of dy, its partial sums are the fused kernel's)
+        p->bwd_off_part_a = p->bwd_off_part_b +
+                            align_up(size_t(p->fused_db ? p->fb_rows : p->part_rows) * size_t(d->d_out) * 4, 256);
         p->bwd_off_spart = p->bwd_off_part_a + align_up(size_t(p->part_rows) * size_t(d->d_in) * 4, 256);
         p->bwd_ws_bytes = p->bwd_off_spart + std::max(spart_in, spart_out);
     } catch (const std::bad_alloc&) {
@@ -253,6 +309,10 @@ std::vector<int32_t> pack_blob(Plan* p)
     p->o_sb = put(p->sb_off.data(), p->sb_off.size());
     p->o_tb_order = put(p->tb_order.data(), p->tb_order.size());
     p->o_sb_order = put(p->sb_order.data(), p->sb_order.size());
+    p->o_fb_wg = put(p->fb_wg_run_off.data(), p->fb_wg_run_off.size());
+    p->o_fb_run = put(p->fb_run_row.data(), p->fb_run_row.size());
+    p->o_fb_cnt = put(p->fb_cnt.data(), p->fb_cnt.size());
+    p->o_fb_row0 = put(p->fb_task_row0.data(), p->fb_task_row0.size());
     while (blob.size() % 4) blob.push_back(0);
     return blob;
 }

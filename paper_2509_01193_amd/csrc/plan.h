@@ -64,6 +64,16 @@ struct Plan {
     // activations follow at fwd_off_p unless the caller gives h_save), at bwd_off_spart in the backward one
     SlicedShape sliced_in, sliced_out;
     size_t fwd_off_p = 0, bwd_off_spart = 0;
+    // dB fused into the sliced projection of dy (one pass over dy for s_t B_t dy_i and for dB): a workgroup
+    // keeps the dB sums of the (task, slice) it is working on and writes them out - 16 rank rows x 512
+    // columns - whenever task or slice changes.  These tables say where: the runs of workgroup g are
+    // fb_wg_run_off[g] .. fb_wg_run_off[g + 1] - 1 in the order it meets them, run i goes to the rows
+    // fb_run_row[i] .. + 15 of the partial array [fb_rows][d_out]; the k-th run of (task t, slice s) over all
+    // workgroups sits at row fb_task_row0[t] + 16 k, and there are fb_cnt[t * nsl + s] of them (stage 2 adds
+    // them in that order).
+    bool fused_db = false;
+    std::vector<int32_t> fb_wg_run_off, fb_run_row, fb_cnt, fb_task_row0;
+    int32_t fb_rows = 0;
 
     // optional launch trace (see lobra_mlora_plan_set_trace)
     mutable void* const* trace_events = nullptr;
@@ -81,7 +91,8 @@ struct Plan {
     void* static_ws = nullptr;          // this device's copy of the library's static scratch array
     // offsets (in int32 units) of the lists inside the blob
     size_t o_cseg_off = 0, o_cseg_task = 0, o_rowblk = 0, o_tb = 0, o_chunks = 0,
-           o_task_chunk = 0, o_rank_off = 0, o_task_tb = 0, o_sb = 0, o_tb_order = 0, o_sb_order = 0;
+           o_task_chunk = 0, o_rank_off = 0, o_task_tb = 0, o_sb = 0, o_tb_order = 0, o_sb_order = 0,
+           o_fb_wg = 0, o_fb_run = 0, o_fb_cnt = 0, o_fb_row0 = 0;
 };
 
 lobra_status validate(const lobra_mlora_desc* d);

@@ -347,18 +347,36 @@ __global__ __launch_bounds__(256) void shrink_lds_kernel(PlanDev pd, const uint1
 // waits drained every wave's prefetched loads at every item.  For the same reason the item barrier is a bare
 // s_barrier (no fence), and the tables are restrict-qualified arguments of their own rather than members of
 // the plan structure: only then are they read with scalar loads, which vmcnt does not count.
+//
+// WITH_DB (the backward pass over dy): the same pass also accumulates dB_t = sum_i (s_t h_i)^T dy_i (section 2.1:
+// the gradient of the up factor), so that dy is read once for both.  The block-transposed s_t h of an item
+// (P_blk, 16 ranks x 16 tokens of the wave's half) comes in with two more copies of 4 bytes per lane; the dy
+// operand - 4 tokens of one column per lane - is gathered out of the ring with transposing reads
+// (ds_read_b64_tr_b16); eight v_mfma_f32_16x16x16_bf16 add the item to the wave's 16 ranks x 128 columns of sums,
+// which stay in registers for as long as task and slice stay the same.  When they change (and at the end) the
+// two token halves are added through LDS and written to the rows that the plan has assigned to this run of
+// the workgroup (Plan::fb_*); stage 2 of the reductions adds the runs of a (task, slice) in the plan's order.
 // -------------------------------------------------------------------------------------------------
 constexpr int kSlicedRing = 4;                                     // ring slots per wave
-constexpr int kSlicedLds = 8 * kSlicedRing * 4096 + 2 * 8 * 64 * 16;   // rings + the two reduction buffers
+constexpr int kSlicedRedOff = 8 * kSlicedRing * 4096;              // the two reduction buffers (also the dB exchange)
+constexpr int kSlicedHOff = kSlicedRedOff + 2 * 8 * 64 * 16;       // WITH_DB: ring of the items' s_t h blocks, 1 KiB per slot
+constexpr int kSlicedLds = kSlicedHOff, kSlicedLdsDb = kSlicedHOff + (kSlicedRing + 1) * 1024;
 
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+
+template <bool WITH_DB>
 __global__ __launch_bounds__(512) void shrink_sliced_kernel(const TokenBlock* __restrict__ tbs,
                                                            const int32_t* __restrict__ rank_off, int32_t ntb,
                                                            int32_t T, const uint16_t* __restrict__ Z,
                                                            const uint16_t* __restrict__ Mx,
                                                            float* __restrict__ part, int32_t D, int32_t ldz,
-                                                           int32_t nsl)
+                                                           int32_t nsl, const uint16_t* __restrict__ Hblk,
+                                                           float* __restrict__ partb,
+                                                           const int32_t* __restrict__ wg_run_off,
+                                                           const int32_t* __restrict__ run_row)
 {
     constexpr int R = kSlicedRing;
+
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(int(threadIdx.x >> 6));
@@ -366,7 +384,9 @@ __global__ __launch_bounds__(512) void shrink_sliced_kernel(const TokenBlock* __
     const int j = lane & 15, kg = lane >> 4;
     unsigned char* ring = lds + wave * (R * 4096);                 // this wave's ring
     const uint32_t ring_addr = uint32_t(uintptr_t((__attribute__((address_space(3))) unsigned char*)ring));
-    float* red = reinterpret_cast<float*>(lds + 8 * R * 4096);     // [item parity][wave][lane][4]
+    float* red = reinterpret_cast<float*>(lds + kSlicedRedOff);    // [item parity][wave][lane][4]
+    unsigned char* hring = lds + kSlicedHOff;                      // WITH_DB: [slot][16 ranks][32 tokens] bf16
+    const uint32_t hring_addr = uint32_t(uintptr_t((__attribute__((address_space(3))) unsigned char*)hring));
 
     // consecutive workgroup ids run on different XCDs: XCD x takes the token blocks [bx0, bx1) - a
     // contiguous piece of the activation tensor when the batch is sorted - and its workgroups split the
@@ -379,10 +399,14 @@ __global__ __launch_bounds__(512) void shrink_sliced_kernel(const TokenBlock* __
     const int32_t n = e1 - e0;                   // the same for all waves of the workgroup
     if (n <= 0) return;
 
-    struct Cursor { int32_t sl, bo, slot; };     // slice, block offset inside the XCD's piece, ring slot
+    // slice, block offset inside the XCD's piece, ring slot, slot in the ring of s_t h blocks.  (That ring is
+    // shared by the waves and has one slot more: wave 0 overwrites the slot of the item before the one its
+    // fellow waves may still be reading.)
+    struct Cursor { int32_t sl, bo, slot, hslot; };
     auto advance = [&](Cursor& c) {
         if (++c.bo == nbx) { c.bo = 0; ++c.sl; }
         if (++c.slot == R) c.slot = 0;
+        if (++c.hslot == R + 1) c.hslot = 0;
     };
     // the four copies of an item: lane (j, kg) of copy q fetches the 8 columns 32 q + 8 kg .. + 7 of its row
     // out of this wave's 128 columns (one 64-byte piece per four lanes, a 256-byte run of the row in all);
@@ -394,6 +418,68 @@ __global__ __launch_bounds__(512) void shrink_sliced_kernel(const TokenBlock* __
         const uint32_t voff = (uint32_t(min(16 * h + j, b.nrows - 1)) * uint32_t(ldz) + 8u * kg) * 2u;
 #pragma unroll
         for (int q = 0; q < 4; ++q) gemm::dma16(ring_addr + c.slot * 4096 + q * 1024, base + q * 64, voff);
+        if constexpr (WITH_DB) {
+            // the item's block of s_t h (1 KiB, as stored) for the whole workgroup: one more copy of wave 0,
+            // which the other waves read behind the item's barrier
+            if (wave == 0)
+                gemm::dma16(hring_addr + c.hslot * 1024,
+                            reinterpret_cast<const unsigned char*>(Hblk) + size_t(bx0 + c.bo) * (16 * kTokenBlock * 2),
+                            uint32_t(lane) * 16u);
+        }
+    };
+    // vector memory operations complete in order: with the copies of y younger items behind it, an item has
+    // landed when at most y times the copies per item are outstanding (wave (h, 0)'s stores also count: they
+    // only make the wait stricter)
+    auto wait_item = [&](auto younger) {
+        constexpr int y = decltype(younger)::value;
+        if (WITH_DB && wave == 0) gemm::wait_vmcnt<5 * y>();
+        else gemm::wait_vmcnt<4 * y>();
+    };
+
+    // WITH_DB: this wave's dB sums, 8 column tiles of 16: lane (n, kg) holds ranks 4 kg .. 4 kg + 3 of column n
+    f32x4 dbacc[WITH_DB ? 8 : 1];
+    int32_t run_idx = -1;                        // runs of (task, slice) this workgroup has met so far, minus 1
+    if constexpr (WITH_DB) {
+#pragma unroll
+        for (int tl = 0; tl < 8; ++tl) dbacc[tl] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+    // the run's sums go out: the halves are added through LDS (h = 0 plus h = 1, four column tiles at a time:
+    // the exchange memory is the two reduction buffers), wave (0, w) stores its 128 columns
+    auto flush_db = [&](int32_t sl) {
+        if constexpr (WITH_DB) {
+            const int32_t row0 = run_row[wg_run_off[blockIdx.x] + run_idx];
+            float* ex = red + (w * 4 * 64) * 4;      // [tile of the round][lane][4]
+            float* dst = partb + size_t(row0 + 4 * kg) * D + sl * 512 + w * 128 + j;
+#pragma unroll
+            for (int half = 0; half < 2; ++half) {
+                // (first round: wave (h, 0) has read the last item's sums out of this memory; second: the
+                //  first round's reads are done)
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                __builtin_amdgcn_s_barrier();
+                asm volatile("" ::: "memory");
+                if (h == 1) {
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) *reinterpret_cast<f32x4*>(ex + (u * 64 + lane) * 4) = dbacc[4 * half + u];
+                }
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                __builtin_amdgcn_s_barrier();
+                asm volatile("" ::: "memory");
+                if (h == 0) {
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const int tl = 4 * half + u;
+                        const f32x4 o = dbacc[tl] + *reinterpret_cast<const f32x4*>(ex + (u * 64 + lane) * 4);
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) dst[size_t(v) * D + tl * 16] = o[v];
+                    }
+                }
+            }
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            __builtin_amdgcn_s_barrier();        // the memory is free for the next item's sums
+            asm volatile("" ::: "memory");
+#pragma unroll
+            for (int tl = 0; tl < 8; ++tl) dbacc[tl] = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
     };
 
     u32x4 av[4];                                 // the adapter columns of this wave's part of the slice
@@ -401,6 +487,8 @@ __global__ __launch_bounds__(512) void shrink_sliced_kernel(const TokenBlock* __
     auto consume = [&](const Cursor& c, int32_t it) {
         const TokenBlock b = tbs[bx0 + c.bo];
         if (b.task != cur_task || c.sl != cur_sl) {          // uniform; once per dozen items
+            if (WITH_DB && run_idx >= 0) flush_db(cur_sl);
+            ++run_idx;
             const int32_t r = rank_off[b.task + 1] - b.rank_row0;
             // rank rows beyond r_t repeat a valid row; the finish kernel drops what they produce
             const uint16_t* mrow = Mx + size_t(b.rank_row0 + min(j, r - 1)) * D + c.sl * 512 + w * 128 + 8 * kg;
@@ -435,31 +523,47 @@ __global__ __launch_bounds__(512) void shrink_sliced_kernel(const TokenBlock* __
             if (tok < b.nrows)     // lane (j, kg): ranks 4 kg .. 4 kg + 3 of token j
                 *reinterpret_cast<f32x4*>(part + (size_t(c.sl) * T + b.row0 + tok) * 16 + 4 * kg) = ((s0 + s1) + s2) + s3;
         }
+        if constexpr (WITH_DB) {
+            // (behind the barrier: wave 0 has seen the block of s_t h land before it came here)
+            // "A" operand: s_t h transposed, lane (i, kg): rank i, tokens 16 h + 4 kg .. + 3 of the block
+            union { uint64_t u; s16x4 v; } hv;
+            hv.u = *reinterpret_cast<const uint64_t*>(hring + c.hslot * 1024 + (j * kTokenBlock + 16 * h + 4 * kg) * 2);
+            // "B" operand of column tile tl: lane (n, kg) needs tokens 4 kg .. 4 kg + 3 of column 16 tl + n.  A
+            // transposing read of a 16-lane group takes 8 bytes (4 columns) from each lane's address and hands
+            // lane 4 g + e element e of what the lanes 4 kr + g, kr = 0 .. 3, supplied: so lane j supplies token
+            // 4 kg + (j >> 2), columns 16 tl + 4 (j & 3) .. + 3.  In the ring, column c of token t lies in copy
+            // c / 32 at lane t + 16 ((c / 8) & 3), 2 (c & 7) bytes in.
+            const unsigned char* zb = ring + c.slot * 4096 + ((4 * kg + (j >> 2)) + 16 * ((j & 3) >> 1)) * 16 + (j & 1) * 8;
+#pragma unroll
+            for (int tl = 0; tl < 8; ++tl) {
+                const s16x4 bv = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                    (s16x4 __attribute__((address_space(3)))*)(zb + (tl >> 1) * 1024 + (tl & 1) * 512));
+                dbacc[tl] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(hv.v, bv, dbacc[tl], 0, 0, 0);
+            }
+        }
     };
 
     Cursor pc, cc;                               // next item to fetch, next item to consume
     pc.sl = e0 / nbx;
     pc.bo = e0 - pc.sl * nbx;
     pc.slot = 0;
+    pc.hslot = 0;
     cc = pc;
     if (n >= R - 1) {
         for (int d = 0; d < R - 1; ++d) {
             issue(pc);
             advance(pc);
         }
-        // vector memory operations complete in order: with the copies of R - 1 younger items behind it, an
-        // item has landed when at most 4 (R - 1) operations are outstanding (wave (h, 0)'s stores also count:
-        // they only make the wait stricter)
         int32_t it = 0;
         for (; it + R - 1 < n; ++it) {
             issue(pc);
             advance(pc);
-            gemm::wait_vmcnt<4 * (R - 1)>();
+            wait_item(std::integral_constant<int, R - 1>{});
             consume(cc, it);
             advance(cc);
         }
         gemm::static_for<0, R - 1>([&](auto t) {
-            gemm::wait_vmcnt<4 * (R - 2 - decltype(t)::value)>();
+            wait_item(std::integral_constant<int, R - 2 - decltype(t)::value>{});
             consume(cc, it);
             advance(cc);
             ++it;
@@ -473,6 +577,7 @@ __global__ __launch_bounds__(512) void shrink_sliced_kernel(const TokenBlock* __
             advance(cc);
         }
     }
+    if (WITH_DB) flush_db(cur_sl);
 }
 
 // Second pass of the sliced projection: P = s_t * (sum of the slices' partial projections, in slice order),
@@ -527,8 +632,11 @@ hipError_t sliced_setup()
     if (e != hipSuccess) return e;
     if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
     if (done[dev].load(std::memory_order_acquire) == 0) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&shrink_sliced_kernel),
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&shrink_sliced_kernel<false>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, kSlicedLds);
+        if (e != hipSuccess) return e;
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&shrink_sliced_kernel<true>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, kSlicedLdsDb);
         if (e != hipSuccess) return e;
         done[dev].store(1, std::memory_order_release);
     }
@@ -538,7 +646,7 @@ hipError_t sliced_setup()
 
 hipError_t shrink_mfma(const PlanDev& pd, const void* Z, const void* M, const float* s,
                        void* P_tok, void* P_blk, int32_t D, int32_t ldz, int32_t nproj, int32_t proj,
-                       hipStream_t st, const SlicedShape& sliced, float* part)
+                       hipStream_t st, const SlicedShape& sliced, float* part, const void* Hblk, float* partb)
 {
     if (pd.ntb == 0) return hipSuccess;
     if (sliced.nsl > 0 && part && nproj == 1) {
@@ -546,8 +654,14 @@ hipError_t shrink_mfma(const PlanDev& pd, const void* Z, const void* M, const fl
         if (e != hipSuccess) return e;
         // a fixed grid - one workgroup per compute unit of the chip this is written for - so that the split
         // of the items, and with it the order of every sum, does not depend on the device
-        shrink_sliced_kernel<<<kSlicedGrid, 512, kSlicedLds, st>>>(pd.tb, pd.rank_off, pd.ntb, pd.T, (const uint16_t*)Z,
-                                                               (const uint16_t*)M, part, D, ldz, sliced.nsl);
+        if (Hblk && partb && pd.fb_run_row)
+            shrink_sliced_kernel<true><<<kSlicedGrid, 512, kSlicedLdsDb, st>>>(
+                pd.tb, pd.rank_off, pd.ntb, pd.T, (const uint16_t*)Z, (const uint16_t*)M, part, D, ldz, sliced.nsl,
+                (const uint16_t*)Hblk, partb, pd.fb_wg_run_off, pd.fb_run_row);
+        else
+            shrink_sliced_kernel<false><<<kSlicedGrid, 512, kSlicedLds, st>>>(
+                pd.tb, pd.rank_off, pd.ntb, pd.T, (const uint16_t*)Z, (const uint16_t*)M, part, D, ldz, sliced.nsl,
+                nullptr, nullptr, nullptr, nullptr);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
         shrink_finish_kernel<<<(pd.ntb + 1) / 2, 256, 0, st>>>(pd, part, s, (uint16_t*)P_tok, (uint16_t*)P_blk, sliced.nsl);

@@ -669,3 +669,61 @@ def test_random_long_batches(seed):
                           fill=(P == 1), **kw)
     p = base if P == 1 else wl.fuse_projections(base, P, **kw)
     check_problem(p, rows=sample_rows(p, 400, seed=seed), label="T=%d P=%d ranks=%s" % (p.T, P, list(map(int, p.ranks))))
+
+
+# ---------------------------------------------------------------------------------------------
+# the K-sliced projection of long batches at ranks up to 16, with and without dB fused into the pass
+# over dy: adversarial tables at sizes where the plan chooses it
+# ---------------------------------------------------------------------------------------------
+def _sliced_case(name, seed):
+    rng = np.random.default_rng(5100 + seed)
+    if name == "mixed-small-ranks":
+        # five tasks of ranks up to 16 in segments of every kind of length, with spans that carry no adapter
+        n_tasks, ranks, d_in, d_out = 5, [16, 8, 4, 16, 12], 1024, 2048
+        lens = rng.choice([1, 2, 31, 32, 33, 65, 700, 1500, 3000, 5000], 70)
+        seg_task = rng.integers(-1, n_tasks, 70)
+    elif name == "forty-tasks-some-empty":
+        # many tasks, a third of them without a token: workgroups meet several (task, slice) runs each
+        n_tasks, d_in, d_out = 40, 1536, 1024
+        ranks = rng.choice([8, 16], n_tasks)
+        live = rng.permutation(n_tasks)[:27]
+        lens = rng.choice([40, 200, 900, 2500], 110)
+        seg_task = rng.choice(live, 110)
+    elif name == "one-task-one-segment":
+        n_tasks, ranks, d_in, d_out = 1, [16], 2048, 1024
+        lens, seg_task = np.asarray([50001]), np.asarray([0])
+    else:   # "tiny-tasks": more rows of dB sums than the fused pass is worth: sliced projection, dB by the reduction kernels
+        n_tasks, d_in, d_out = 750, 1024, 1024
+        ranks = np.full(n_tasks, 16)
+        lens = np.full(3000, 33)
+        seg_task = np.arange(3000) % n_tasks
+    seg_off = np.concatenate([[0], np.cumsum(lens)])
+    s = rng.uniform(0.5, 2, n_tasks).astype(np.float32)
+    return wl.make_custom(name, "bf16", d_in, d_out, ranks, seg_off, seg_task, 5100 + seed, s=s,
+                          std_x=1.0, std_w=0.05, std_a=0.05, std_b=0.05)
+
+
+@pytest.mark.parametrize("name,fused", [("mixed-small-ranks", True), ("forty-tasks-some-empty", True),
+                                        ("one-task-one-segment", True), ("tiny-tasks", False)])
+def test_sliced_projection_with_and_without_fused_db(name, fused):
+    import torch
+    p = _sliced_case(name, 0)
+    plan = bd.Plan.for_problem(p, bd.PLAN_HOST_ONLY)
+    nsl_in, nsl_out, is_fused = plan.query(bd.Q_SLICED)[:3].tolist()
+    plan.close()
+    assert nsl_in == p.d_in // 512 and nsl_out == p.d_out // 512 and bool(is_fused) == fused
+    dp, _ = check_problem(p, rows=sample_rows(p, 400), label="sliced")
+    # the same results on the next call (nothing of a call survives in the partial sums), with accumulation, and
+    # with the down-projected activations recomputed by bwd
+    first = {k: getattr(dp, k).clone() for k in ("y", "dx", "dA", "dB")}
+    dp.step()
+    torch.cuda.synchronize()
+    for k, v in first.items():
+        assert torch.equal(getattr(dp, k), v), k
+    dp.bwd(flags=bd.FLAG_ACCUMULATE_GRADS)
+    dp.bwd(use_saved_h=False, flags=bd.FLAG_ACCUMULATE_GRADS)
+    torch.cuda.synchronize()
+    for k in ("dA", "dB"):
+        got, want = getattr(dp, k), 3 * first[k]
+        assert ((got - want).abs().max() <= 1e-5 * want.abs().max()).item(), k
+    assert dp.guards_intact()

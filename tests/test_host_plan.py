@@ -252,6 +252,91 @@ def test_work_lists_adversarial_tables():
     assert check_plan(p) == (0, 0)
 
 
+def check_sliced_tables(p):
+    """The K-sliced projection's shape rule and, when dB is fused into it, the run tables: compared with a walk
+    over every item of every workgroup by the rule the kernel itself follows (the items of an XCD's token blocks,
+    slice-major, split evenly over its workgroups)."""
+    plan = bd.Plan.for_problem(p, bd.PLAN_HOST_ONLY)
+    nsl_in, nsl_out, fused, rows, G = plan.query(bd.Q_SLICED).tolist()
+    tb = plan.query(bd.Q_TOKEN_BLOCKS).reshape(-1, 4)
+    ntb = len(tb)
+    ranks = np.asarray(p.ranks)
+    r_pad = (int(ranks.max()) + 15) // 16 * 16 if len(ranks) else 0
+    n_proj = getattr(p, "n_proj", 1)
+    for nsl, D, ok in ((nsl_in, p.d_in, True), (nsl_out, p.d_out, n_proj == 1)):
+        want = D // 512 if (p.dtype == "bf16" and ok and r_pad == 16 and D % 512 == 0 and ntb * (D // 512) >= 3072) else 0
+        assert nsl == want, (p.name, nsl, want)
+    assert G == 256
+    # the workspaces hold the fp32 partial projections [slices][T][16]
+    assert plan.fwd_ws_bytes >= plan.h_save_bytes + nsl_in * p.T * 64
+    assert plan.bwd_ws_bytes >= max(nsl_in, nsl_out) * p.T * 64
+    wg_runs, run_row = plan.query(bd.Q_FUSED_WG_RUNS), plan.query(bd.Q_FUSED_RUN_ROW)
+    cnt, task_row = plan.query(bd.Q_FUSED_COUNT), plan.query(bd.Q_FUSED_TASK_ROW)
+    if not fused:
+        assert rows == 0 and len(wg_runs) == len(run_row) == len(cnt) == len(task_row) == 0
+        plan.close()
+        return False
+    assert nsl_out > 0 and len(wg_runs) == G + 1 and wg_runs[0] == 0 and wg_runs[-1] == len(run_row)
+    assert len(cnt) == p.n_tasks * nsl_out and len(task_row) == p.n_tasks
+    per, seen, covered = G // 8, {}, 0
+    for wg in range(G):
+        xcd, idx = wg & 7, wg >> 3
+        bx0, bx1 = (ntb * xcd) >> 3, (ntb * (xcd + 1)) >> 3
+        nbx = bx1 - bx0
+        nit = nbx * nsl_out
+        e0, e1 = nit * idx // per, nit * (idx + 1) // per
+        covered += e1 - e0
+        prev, nruns = None, 0
+        for e in range(e0, e1):
+            sl, bo = divmod(e, nbx)
+            key = (int(tb[bx0 + bo, 2]), sl)
+            if key != prev:
+                k = seen.get(key, 0)
+                seen[key] = k + 1
+                assert run_row[wg_runs[wg] + nruns] == task_row[key[0]] + 16 * k, (p.name, wg, e)
+                nruns, prev = nruns + 1, key
+        assert wg_runs[wg + 1] - wg_runs[wg] == nruns, (p.name, wg)
+    assert covered == ntb * nsl_out
+    want_cnt = np.zeros((p.n_tasks, nsl_out), np.int64)
+    for (t, sl), k in seen.items():
+        want_cnt[t, sl] = k
+    assert (cnt.reshape(p.n_tasks, nsl_out) == want_cnt).all()
+    # a task's runs occupy its own range of rows, 16 per run of its busiest slice
+    need = 16 * want_cnt.max(axis=1)
+    assert (task_row == np.concatenate([[0], np.cumsum(need)[:-1]])).all() and rows == need.sum()
+    assert rows <= p.T // 8 and plan.bwd_ws_bytes >= rows * p.d_out * 4
+    plan.close()
+    return True
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
+@pytest.mark.parametrize("order", ["shuffled", "sorted"])
+def test_sliced_projection_tables_of_the_five_workloads(cfg, order):
+    fused = check_sliced_tables(wl.make_config(cfg, order, fill=False))
+    assert fused == (cfg in (2, 4))          # rank 16 on long batches; workload 1 is fp32, 3 and 5 have larger ranks
+
+
+def test_sliced_projection_tables_adversarial():
+    rng = np.random.default_rng(3)
+    outcomes = set()
+    for trial in range(12):
+        n_tasks = int(rng.choice([1, 3, 17, 40]))
+        S = int(rng.integers(n_tasks, 6 * n_tasks + 2))
+        lens = rng.choice([0, 1, 7, 31, 32, 33, 500, 2000, 6000], S)
+        seg_task = rng.integers(-1, n_tasks, S)                    # some tasks get no tokens at all
+        seg_off = np.concatenate([[0], np.cumsum(lens)])
+        ranks = rng.choice([4, 8, 16], n_tasks)
+        d_in, d_out = [(1024, 2048), (4096, 512), (1536, 1000)][trial % 3]
+        p = wl.make_custom("adv", "bf16", d_in, d_out, ranks, seg_off, seg_task, trial, fill=False)
+        outcomes.add(check_sliced_tables(p))
+    # many tiny tasks: more rows of sums than the pass is worth, so dB stays with the reduction kernels
+    lens = np.full(3000, 33)
+    p = wl.make_custom("tiny-tasks", "bf16", 1024, 1024, [16] * 750, np.concatenate([[0], np.cumsum(lens)]),
+                       np.arange(3000) % 750, 0, fill=False)
+    outcomes.add(check_sliced_tables(p))
+    assert outcomes == {True, False}
+
+
 def test_fused_projections_descriptor_errors():
     mk = lambda **kw: bd.make_desc(**dict(dict(dtype="bf16", T=64, d_in=64, d_out=96, rank_off=[0, 24], seg_off=[0, 64],
                                                seg_task=[0], n_proj=3), **kw))[0]
