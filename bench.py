@@ -400,9 +400,14 @@ def main():
     skinny = {}
     # each of the two rank-r stages reads x once and dy once per step (algorithmic bytes); `traffic` is
     # the same launch by the HBM-side counters of the committed rocprofv3 --pmc summary
+    # (long batches of ranks up to 16: dB is accumulated by the projection's pass over dy, so the reduction's
+    #  stage 1 reads x alone)
+    sliced = dp.plan.query(bd.Q_SLICED).tolist()
+    fused_db = bool(sliced[2])
     for name in ("shrink", "grad_stage1"):
         if name in kern and kern[name]["launches_per_step"] > 0:
-            per_launch = float(esz) * p.T * (p.d_in + p.d_out) / kern[name]["launches_per_step"]
+            step_bytes = float(esz) * p.T * (p.d_in if (fused_db and name == "grad_stage1") else p.d_in + p.d_out)
+            per_launch = step_bytes / kern[name]["launches_per_step"]
             gbs = per_launch / (kern[name]["avg_ms"] * 1e-3) / 1e9
             gbs_cold = per_launch / (kern_cold[name]["avg_ms"] * 1e-3) / 1e9
             skinny[name] = {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
@@ -434,6 +439,7 @@ def main():
         "tokens_per_s_cold": real_tokens / (ms_cold * 1e-3), "cold_sets": COLD_SETS,
         "ceilings": ceilings, "kernels_cold": kern_cold,
         "kernels": kern, "skinny_hbm": skinny, "extras": extras, "roofline": roofline,
+        "rank_r_path": {"projection_slices_in": sliced[0], "projection_slices_out": sliced[1], "dB_fused_into_dy_pass": fused_db},
         "setup_s": time.perf_counter() - t0,
     }
     if not a.no_cpu_baseline:

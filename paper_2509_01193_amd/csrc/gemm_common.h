@@ -71,21 +71,6 @@ __device__ __forceinline__ void dma16(uint32_t lds_addr, const unsigned char* gb
                  : "memory");
 }
 
-// The same with 4 bytes per lane (global_load_lds_dword): lane i fetches 4 bytes at gbase + voff, they land at
-// lds_addr + 4 i.
-__device__ __forceinline__ void dma4(uint32_t lds_addr, const unsigned char* gbase, uint32_t voff)
-{
-    const uint32_t la = __builtin_amdgcn_readfirstlane(lds_addr);
-    const uint64_t gp = reinterpret_cast<uint64_t>(gbase);
-    const uint32_t lo = __builtin_amdgcn_readfirstlane(uint32_t(gp));
-    const uint32_t hi = __builtin_amdgcn_readfirstlane(uint32_t(gp >> 32));
-    const uint64_t gu = (uint64_t(hi) << 32) | lo;
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2"
-                 :
-                 : "s"(la), "v"(voff), "s"(gu)
-                 : "memory");
-}
-
 // ---- accumulators in explicitly named AGPRs --------------------------------------------------------------
 // The persistent kernel keeps the 64 four-register accumulators of a wave in a[0:255] for its whole life,
 // across output tiles, epilogues and a loop nest.  Handed to the register allocator as 64 values they get

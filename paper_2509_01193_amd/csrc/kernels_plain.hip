@@ -354,6 +354,15 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(PlanDev pd, GradJo
     if (nv == 4 && (D & 3) == 0) {
         typedef float f4 __attribute__((ext_vector_type(4)));
         int32_t c = c0;
+        for (; c + 8 <= c1; c += 8) {            // eight loads in flight, added in order
+            f4 v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = *reinterpret_cast<const f4*>(row_ptr(c + u));
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) acc[q] += v[u][q];
+        }
         for (; c + 4 <= c1; c += 4) {
             const f4 v0 = *reinterpret_cast<const f4*>(row_ptr(c));
             const f4 v1 = *reinterpret_cast<const f4*>(row_ptr(c + 1));

@@ -350,7 +350,8 @@ __global__ __launch_bounds__(256) void shrink_lds_kernel(PlanDev pd, const uint1
 //
 // WITH_DB (the backward pass over dy): the same pass also accumulates dB_t = sum_i (s_t h_i)^T dy_i (section 2.1:
 // the gradient of the up factor), so that dy is read once for both.  The block-transposed s_t h of an item
-// (P_blk, 16 ranks x 16 tokens of the wave's half) comes in with two more copies of 4 bytes per lane; the dy
+// (P_blk: 16 ranks x 32 tokens, 1 KiB) comes in with one more copy of wave 0 and is read by all waves behind
+// the item's barrier (one such copy per wave measured 4 us slower at workload 2); the dy
 // operand - 4 tokens of one column per lane - is gathered out of the ring with transposing reads
 // (ds_read_b64_tr_b16); eight v_mfma_f32_16x16x16_bf16 add the item to the wave's 16 ranks x 128 columns of sums,
 // which stay in registers for as long as task and slice stay the same.  When they change (and at the end) the
@@ -599,12 +600,12 @@ __global__ __launch_bounds__(256) void shrink_finish_kernel(PlanDev pd, const fl
         const float* p = part + size_t(b.row0 + tok) * 16 + 4 * kg;
         const size_t pitch = size_t(pd.T) * 16;
         int32_t sl = 0;
-        for (; sl + 4 <= nsl; sl += 4) {         // four loads in flight, added in slice order
-            const f32x4 v0 = *reinterpret_cast<const f32x4*>(p + (sl + 0) * pitch);
-            const f32x4 v1 = *reinterpret_cast<const f32x4*>(p + (sl + 1) * pitch);
-            const f32x4 v2 = *reinterpret_cast<const f32x4*>(p + (sl + 2) * pitch);
-            const f32x4 v3 = *reinterpret_cast<const f32x4*>(p + (sl + 3) * pitch);
-            sum = (((sum + v0) + v1) + v2) + v3;
+        for (; sl + 8 <= nsl; sl += 8) {         // eight loads in flight (this kernel is all latency), added in slice order
+            f32x4 v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = *reinterpret_cast<const f32x4*>(p + (sl + u) * pitch);
+#pragma unroll
+            for (int u = 0; u < 8; ++u) sum = sum + v[u];
         }
         for (; sl < nsl; ++sl) sum = sum + *reinterpret_cast<const f32x4*>(p + sl * pitch);
     }

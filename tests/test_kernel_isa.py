@@ -85,3 +85,54 @@ def test_main_loop_has_no_instruction_clumps(kernels):
             run = run + 1 if b - a <= 13 else 1
             best = max(best, run)
         assert best >= 128, (name, best)
+
+
+# ---------------------------------------------------------------------------------------------------------
+# The K-sliced rank-r kernel keeps several items' copies in flight and waits for them by count.  That only
+# works if the compiler adds no wait of its own that drains them: its tables must be read with scalar loads
+# (which the vector-memory counter does not see), the item barrier must come without a fence, and the copies
+# must be the direct-to-LDS kind with M0 written right in front of each.
+# ---------------------------------------------------------------------------------------------------------
+@pytest.fixture(scope="module")
+def sliced_kernels(tmp_path_factory):
+    out = str(tmp_path_factory.mktemp("isa") / "skinny_mfma.s")
+    cmd = [HIPCC, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
+           "-packed-fp32-ops", "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-x", "hip", "--cuda-device-only",
+           "-S", os.path.join(CSRC, "skinny_mfma.hip"), "-o", out]
+    r = subprocess.run(cmd, capture_output=True, text=True, timeout=600)
+    assert r.returncode == 0, r.stderr[-3000:]
+    text = open(out).read()
+    parts = re.split(r"^(_ZN5lobra20shrink_sliced_kernel\w+):", text, flags=re.M)
+    ks = []
+    for i in range(1, len(parts), 2):
+        body = parts[i + 1]
+        end = body.index(".end_amdhsa_kernel")
+        code = [l.split(";")[0].strip() for l in body[:end].split("\n")]
+        code = [l for l in code if l and not l.startswith(".")]
+        ks.append((parts[i], code, body[end:end + 3000]))
+    assert len(ks) == 2, [k[0] for k in ks]      # projection alone, projection with dB
+    return ks
+
+
+def test_sliced_kernel_waits_for_its_copies_by_count(sliced_kernels):
+    for name, code, tail in sliced_kernels:
+        fused = "ILb1E" in name
+        assert re.search(r"; ScratchSize: 0\b", tail), name
+        copies = [i for i, l in enumerate(code) if l.startswith("global_load_lds_dwordx4")]
+        assert len(copies) >= 16, (name, len(copies))
+        for c in copies:            # M0 is written inside the copy's own asm statement
+            assert any(re.match(r"s_mov_b32 m0,", code[k]) for k in range(max(0, c - 2), c)), (name, code[c - 3:c + 1])
+        # the steady-state wait leaves the copies of three younger items in flight (wave 0 of the fused form
+        # has a fifth copy per item), the drain at the end counts down
+        waits = {int(m.group(1)) for l in code for m in [re.match(r"s_waitcnt vmcnt\((\d+)\)$", l)] if m}
+        assert {12, 8, 4} <= waits, (name, sorted(waits))
+        if fused:
+            assert {15, 10, 5} <= waits, (name, sorted(waits))
+        # ordinary vector loads: only the adapter rows (16 bytes per lane), never the tables
+        plain = [l for l in code if re.match(r"global_load_(dword|dwordx2|dwordx3|ubyte|ushort|sbyte|sshort)\b", l)]
+        assert not plain, (name, plain[:4])
+        assert [l for l in code if l.startswith("s_load_dwordx4") or l.startswith("s_load_dwordx2")], name
+        # no barrier drags a full vector-memory wait along (what a fenced barrier would do)
+        for i, l in enumerate(code):
+            if l == "s_barrier":
+                assert not any(re.match(r"s_waitcnt.*vmcnt\(0\)", code[k]) for k in range(max(0, i - 3), i)), (name, code[i - 4:i + 1])
