@@ -508,6 +508,20 @@ __global__ __launch_bounds__(512) void shrink_sliced_kernel(const TokenBlock* __
             const u32x4 zv = *reinterpret_cast<const u32x4*>(ring + c.slot * 4096 + q * 1024 + lane * 16);
             acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(av[q]), as_bf16x8(zv), acc, 0, 0, 0);
         }
+        // WITH_DB: the dy operands of the dB product are gathered here, in front of the barrier, whose wait then
+        // covers their latency.  "B" operand of column tile tl: lane (n, kg) needs tokens 4 kg .. 4 kg + 3 of column
+        // 16 tl + n.  A transposing read of a 16-lane group takes 8 bytes (4 columns) from each lane's address and
+        // hands lane 4 g + e element e of what the lanes 4 kr + g, kr = 0 .. 3, supplied: so lane j supplies token
+        // 4 kg + (j >> 2), columns 16 tl + 4 (j & 3) .. + 3.  In the ring, column c of token t lies in copy c / 32
+        // at lane t + 16 ((c / 8) & 3), 2 (c & 7) bytes in.
+        s16x4 bv[WITH_DB ? 8 : 1];
+        if constexpr (WITH_DB) {
+            const unsigned char* zb = ring + c.slot * 4096 + ((4 * kg + (j >> 2)) + 16 * ((j & 3) >> 1)) * 16 + (j & 1) * 8;
+#pragma unroll
+            for (int tl = 0; tl < 8; ++tl)
+                bv[tl] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                    (s16x4 __attribute__((address_space(3)))*)(zb + (tl >> 1) * 1024 + (tl & 1) * 512));
+        }
         float* rbuf = red + (it & 1) * (8 * 64 * 4);
         *reinterpret_cast<f32x4*>(rbuf + (wave * 64 + lane) * 4) = acc;
         // one barrier per item: the next write to this half of red follows the next item's barrier,
@@ -529,18 +543,9 @@ __global__ __launch_bounds__(512) void shrink_sliced_kernel(const TokenBlock* __
             // "A" operand: s_t h transposed, lane (i, kg): rank i, tokens 16 h + 4 kg .. + 3 of the block
             union { uint64_t u; s16x4 v; } hv;
             hv.u = *reinterpret_cast<const uint64_t*>(hring + c.hslot * 1024 + (j * kTokenBlock + 16 * h + 4 * kg) * 2);
-            // "B" operand of column tile tl: lane (n, kg) needs tokens 4 kg .. 4 kg + 3 of column 16 tl + n.  A
-            // transposing read of a 16-lane group takes 8 bytes (4 columns) from each lane's address and hands
-            // lane 4 g + e element e of what the lanes 4 kr + g, kr = 0 .. 3, supplied: so lane j supplies token
-            // 4 kg + (j >> 2), columns 16 tl + 4 (j & 3) .. + 3.  In the ring, column c of token t lies in copy
-            // c / 32 at lane t + 16 ((c / 8) & 3), 2 (c & 7) bytes in.
-            const unsigned char* zb = ring + c.slot * 4096 + ((4 * kg + (j >> 2)) + 16 * ((j & 3) >> 1)) * 16 + (j & 1) * 8;
 #pragma unroll
-            for (int tl = 0; tl < 8; ++tl) {
-                const s16x4 bv = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                    (s16x4 __attribute__((address_space(3)))*)(zb + (tl >> 1) * 1024 + (tl & 1) * 512));
-                dbacc[tl] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(hv.v, bv, dbacc[tl], 0, 0, 0);
-            }
+            for (int tl = 0; tl < 8; ++tl)
+                dbacc[tl] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(hv.v, bv[tl], dbacc[tl], 0, 0, 0);
         }
     };
 
