@@ -727,3 +727,17 @@ def test_sliced_projection_with_and_without_fused_db(name, fused):
         got, want = getattr(dp, k), 3 * first[k]
         assert ((got - want).abs().max() <= 1e-5 * want.abs().max()).item(), k
     assert dp.guards_intact()
+    # the products read the projection that THIS call wrote: with all scales set to zero the adapter term is
+    # exactly zero, so y and dx must equal the base-only products bit for bit - a projection left over from
+    # the calls above (in the workspace, or in a cache) would show
+    base = dp.base_only()                        # (shares y and dx with dp)
+    base.step()
+    torch.cuda.synchronize()
+    y0, dx0 = dp.y.clone(), dp.dx.clone()
+    dp.y.zero_()
+    dp.dx.zero_()
+    dp.s.zero_()
+    dp.step()
+    torch.cuda.synchronize()
+    assert torch.equal(dp.y, y0) and torch.equal(dp.dx, dx0)
+    assert float(dp.dA.abs().max()) == 0.0 and float(dp.dB.abs().max()) == 0.0

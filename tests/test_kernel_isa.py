@@ -32,7 +32,7 @@ def kernels(tmp_path_factory):
     for i in range(1, len(parts), 2):
         body = parts[i + 1]
         end = body.index(".end_amdhsa_kernel")
-        code = [l.split(";")[0].strip() for l in body[:body.index("s_endpgm") + 8].split("\n")]
+        code = [l.split(";")[0].strip() for l in body[:body.rindex("s_endpgm", 0, end) + 8].split("\n")]
         code = [l for l in code if l and not l.startswith(".")]
         tail = body[end:end + 3000]
         ks.append((parts[i], code, tail))
