@@ -158,51 +158,11 @@ lobra_status build_host_plan(const lobra_mlora_desc* d, uint32_t flags, Plan* p)
             by_rank(p->sb_off.size() - 1, [&](int32_t i) { return p->tb[size_t(p->sb_off[size_t(i)])].task; }, p->sb_order);
         }
 
-        // 4. reduction chunks: runs of token blocks of one task.  The chunk length is chosen so
-        //    that (chunks x 128-column tiles) gives roughly a thousand workgroups, within
-        //    [4, 64] token blocks ([1, 64] on the plain path); fewer, longer chunks mean less partial-sum traffic.
-        const int64_t coltiles = (std::min(d->d_in, d->d_out) + 127) / 128;
-        int64_t cb = (int64_t(T) * coltiles / 1024 + kTokenBlock - 1) / kTokenBlock;
-        // (the MFMA kernel gives each of its four waves a token block of the chunk at a time; the plain
-        //  kernel walks a chunk's tokens one after the other, so small batches want short chunks there)
-        cb = std::max<int64_t>(p->mfma ? 4 : 1, std::min<int64_t>(64, cb));
-        p->chunk_blocks = int32_t(cb);
-        p->chunks.clear();
-        p->task_chunk_off.assign(size_t(n) + 1, 0);
-        p->part_rows = 0;
-        for (int32_t t = 0; t < n; ++t) {
-            const int32_t r = p->rank_off[t + 1] - p->rank_off[t];
-            for (int32_t b = p->task_tb_off[t]; b < p->task_tb_off[t + 1]; b += p->chunk_blocks) {
-                const int32_t e = std::min(b + p->chunk_blocks, p->task_tb_off[t + 1]);
-                p->chunks.push_back(GradChunk{b, e, t, p->part_rows});
-                p->part_rows += r;
-            }
-            p->task_chunk_off[t + 1] = int32_t(p->chunks.size());
-        }
-
-        // (the reduction kernels put chunks x column tiles of at least 64 columns on grid.x)
-        if (int64_t(p->chunks.size()) * ((int64_t(d->d_in) + 63) / 64 + (int64_t(d->d_out) + 63) / 64) > 0x7fffffff)
-            return LOBRA_ERR_SHAPE;
-
-        // 5. buffer sizes
-        BufferLayout& L = p->p_layout;
-        const size_t ntb = p->tb.size();
-        if (ntb == 0) {
-            L = BufferLayout{};
-        } else if (p->mfma) {
-            L.p_tok = 0;
-            L.p_blk = align_up(size_t(T) * p->r_pad * 2, 256);
-            L.total = L.p_blk + align_up(ntb * size_t(p->r_pad) * kTokenBlock * 2, 256);
-        } else {
-            L.p_tok = 0;
-            L.p_blk = 0;
-            L.total = align_up(size_t(T) * p->r_max * 4, 256);
-        }
-        // the K-sliced projection and its partial sums
+        // 3d. the K-sliced projection (long batches, ranks up to 16) and whether dB rides with its pass over dy
         p->sliced_in = p->sliced_out = SlicedShape{};
-        if (p->mfma && ntb > 0) {
-            p->sliced_in = sliced_shrink_shape(int64_t(ntb), p->r_pad, d->d_in);
-            if (p->n_proj == 1) p->sliced_out = sliced_shrink_shape(int64_t(ntb), p->r_pad, d->d_out);
+        if (p->mfma && !p->tb.empty()) {
+            p->sliced_in = sliced_shrink_shape(int64_t(p->tb.size()), p->r_pad, d->d_in);
+            if (p->n_proj == 1) p->sliced_out = sliced_shrink_shape(int64_t(p->tb.size()), p->r_pad, d->d_out);
         }
         // dB fused into the sliced projection of dy: the runs of (task, slice) that every workgroup meets, by
         // the same split of the items as the kernel's (shrink_sliced_kernel)
@@ -213,7 +173,7 @@ lobra_status build_host_plan(const lobra_mlora_desc* d, uint32_t flags, Plan* p)
         p->fb_task_row0.clear();
         p->fb_rows = 0;
         if (p->sliced_out.nsl > 0) {
-            const int32_t nsl = p->sliced_out.nsl, per_xcd = kSlicedGrid / 8, ntb32 = int32_t(ntb);
+            const int32_t nsl = p->sliced_out.nsl, per_xcd = kSlicedGrid / 8, ntb32 = int32_t(p->tb.size());
             std::vector<int32_t> run_task, run_k;
             p->fb_cnt.assign(size_t(n) * nsl, 0);
             p->fb_wg_run_off.assign(1, 0);
@@ -257,6 +217,55 @@ lobra_status build_host_plan(const lobra_mlora_desc* d, uint32_t flags, Plan* p)
                 p->fb_cnt.clear();
                 p->fb_task_row0.clear();
             }
+        }
+        // 4. reduction chunks: runs of token blocks of one task.  The chunk length is chosen so
+        //    that (chunks x 128-column tiles) gives roughly a thousand workgroups, within
+        //    [4, 64] token blocks ([1, 64] on the plain path); fewer, longer chunks mean less partial-sum traffic.
+        const int64_t coltiles = (std::min(d->d_in, d->d_out) + 127) / 128;
+        int64_t cb = (int64_t(T) * coltiles / 1024 + kTokenBlock - 1) / kTokenBlock;
+        // Where dB rides with the projection of dy, stage 1 is one short launch for dA alone and what counts is
+        // its balance: three workgroups per compute unit and a task's blocks split evenly among its chunks (at
+        // workload 2: 24 chunks of 21 or 22 blocks, 27.9 us, against 36 of 16 or 3 blocks, 30.8 us; and a quarter
+        // fewer partial sums for stage 2)
+        if (p->fused_db) cb = (int64_t(p->tb.size()) * ((d->d_in + 127) / 128) + 767) / 768;
+        // (the MFMA kernel gives each of its four waves a token block of the chunk at a time; the plain
+        //  kernel walks a chunk's tokens one after the other, so small batches want short chunks there)
+        cb = std::max<int64_t>(p->mfma ? 4 : 1, std::min<int64_t>(64, cb));
+        p->chunk_blocks = int32_t(cb);
+        p->chunks.clear();
+        p->task_chunk_off.assign(size_t(n) + 1, 0);
+        p->part_rows = 0;
+        for (int32_t t = 0; t < n; ++t) {
+            const int32_t r = p->rank_off[t + 1] - p->rank_off[t];
+            const int32_t nb = p->task_tb_off[t + 1] - p->task_tb_off[t];
+            // (an even split in the fused case: no short chunk at the end of a task)
+            const int32_t nck = (nb + p->chunk_blocks - 1) / p->chunk_blocks;
+            const int32_t len = p->fused_db && nck > 0 ? (nb + nck - 1) / nck : p->chunk_blocks;
+            for (int32_t b = p->task_tb_off[t]; b < p->task_tb_off[t + 1]; b += len) {
+                const int32_t e = std::min(b + len, p->task_tb_off[t + 1]);
+                p->chunks.push_back(GradChunk{b, e, t, p->part_rows});
+                p->part_rows += r;
+            }
+            p->task_chunk_off[t + 1] = int32_t(p->chunks.size());
+        }
+
+        // (the reduction kernels put chunks x column tiles of at least 64 columns on grid.x)
+        if (int64_t(p->chunks.size()) * ((int64_t(d->d_in) + 63) / 64 + (int64_t(d->d_out) + 63) / 64) > 0x7fffffff)
+            return LOBRA_ERR_SHAPE;
+
+        // 5. buffer sizes
+        BufferLayout& L = p->p_layout;
+        const size_t ntb = p->tb.size();
+        if (ntb == 0) {
+            L = BufferLayout{};
+        } else if (p->mfma) {
+            L.p_tok = 0;
+            L.p_blk = align_up(size_t(T) * p->r_pad * 2, 256);
+            L.total = L.p_blk + align_up(ntb * size_t(p->r_pad) * kTokenBlock * 2, 256);
+        } else {
+            L.p_tok = 0;
+            L.p_blk = 0;
+            L.total = align_up(size_t(T) * p->r_max * 4, 256);
         }
         const size_t spart_in = align_up(size_t(p->sliced_in.nsl) * size_t(T) * 64, 256);
         const size_t spart_out = align_up(size_t(p->sliced_out.nsl) * size_t(T) * 64, 256);
