@@ -213,8 +213,10 @@ LOBRA_API lobra_status lobra_mlora_plan_fwd(const lobra_mlora_plan *plan, const 
  * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the forward
  * pass with h_save = NULL whose scratch is a fixed array of LOBRA_STATIC_WS_BYTES inside the library's
  * own device image instead of a caller buffer.  Arguments as for lobra_mlora_plan_fwd.  Makes no allocation
- * of any kind and does not synchronise.  LOBRA_ERR_WORKSPACE when the plan's fwd_ws_bytes exceed
- * LOBRA_STATIC_WS_BYTES (nothing is launched).  Each GPU has ONE such array, which keeps the last
+ * of any kind and does not synchronise.  LOBRA_ERR_WORKSPACE when the projected activations (h_save_bytes)
+ * exceed LOBRA_STATIC_WS_BYTES (nothing is launched); a plan whose fwd_ws_bytes exceed the array only because of
+ * the K-sliced projection's partial sums runs the one-block-per-workgroup projection here (same result up to the
+ * order of the sums).  Each GPU has ONE such array, which keeps the last
  * call's contents: two calls of this function (or of lobra_token_task_map, which parks its tables there)
  * that overlap in time on the same GPU (different streams, or different threads) race on it and must be
  * ordered by the caller; the saved activations are not available to bwd (pass h_saved = NULL there). */

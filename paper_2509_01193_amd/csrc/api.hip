@@ -86,7 +86,7 @@ lobra_status runnable(const lobra_mlora_plan* plan)
 
 // Argument checks of a forward call on plan p (everything except the plan itself): host only.
 lobra_status fwd_check(const Plan& p, const void* x, const void* W, const void* A, const void* B, const float* s,
-                       const void* y, const void* h_save, const void* ws, size_t ws_bytes)
+                       const void* y, const void* h_save, const void* ws, size_t ws_bytes, bool sliced = true)
 {
     const bool adapters = !p.tb.empty();
     if (!x || !W || !y) return LOBRA_ERR_NULL;
@@ -96,7 +96,7 @@ lobra_status fwd_check(const Plan& p, const void* x, const void* W, const void* 
         return LOBRA_ERR_ALIGN;
     // the workspace holds the sliced projection's partial sums (if the plan uses it) and, without h_save, the
     // projected activations behind them
-    const size_t need = p.fwd_off_p + (h_save ? 0 : p.p_layout.total);
+    const size_t need = (sliced ? p.fwd_off_p : 0) + (h_save ? 0 : p.p_layout.total);
     if (adapters && need > 0 && (!ws || ws_bytes < need)) return LOBRA_ERR_WORKSPACE;
     return LOBRA_OK;
 }
@@ -321,18 +321,21 @@ lobra_status lobra_mlora_plan_query(const lobra_mlora_plan* plan, int32_t what, 
     return LOBRA_OK;
 }
 
-lobra_status lobra_mlora_plan_fwd(const lobra_mlora_plan* plan, const void* x, const void* W,
-                             const void* A, const void* B, const float* s, void* y,
-                             void* h_save, void* ws, size_t ws_bytes, void* hip_stream)
+namespace {
+// The forward pass.  sliced = false: without the K-sliced projection even where the plan would take it (its
+// partial sums are most of the forward workspace): the projected activations then start at ws itself.
+lobra_status plan_fwd(const lobra_mlora_plan* plan, const void* x, const void* W, const void* A, const void* B,
+                      const float* s, void* y, void* h_save, void* ws, size_t ws_bytes, void* hip_stream, bool sliced)
 {
     lobra_status rs = runnable(plan);
     if (rs != LOBRA_OK) return rs;
     const Plan& p = *plan;
     if (p.desc.T == 0) return LOBRA_OK;
-    rs = fwd_check(p, x, W, A, B, s, y, h_save, ws, ws_bytes);
+    rs = fwd_check(p, x, W, A, B, s, y, h_save, ws, ws_bytes, sliced);
     if (rs != LOBRA_OK) return rs;
     const bool adapters = !p.tb.empty();
-    void* hbuf = h_save ? h_save : static_cast<char*>(ws) + p.fwd_off_p;
+    void* hbuf = h_save ? h_save : static_cast<char*>(ws) + (sliced ? p.fwd_off_p : 0);
+    const SlicedShape sliced_in = sliced ? p.sliced_in : SlicedShape{};
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const PlanDev pd = device_view(p);
     const int dt = p.desc.dtype;
@@ -355,7 +358,7 @@ lobra_status lobra_mlora_plan_fwd(const lobra_mlora_plan* plan, const void* x, c
     if (adapters)   // all projections' down factors are stacked in A: one pass over x
         LOBRA_LAUNCH(p, st, LOBRA_K_SHRINK,
                      shrink_mfma(pd, x, A, s, hb + p.p_layout.p_tok, hb + p.p_layout.p_blk, pd.d_in, pd.d_in, 1, 0, st,
-                                 p.sliced_in, static_cast<float*>(ws)));
+                                 sliced_in, static_cast<float*>(ws)));
     if (p.n_proj == 1) {
         LOBRA_LAUNCH(p, st, LOBRA_K_GEMM,
                      gemm_mfma(pd, false, x, W, adapters ? hb + p.p_layout.p_tok : nullptr, B, y, pd.d_in,
@@ -380,6 +383,14 @@ lobra_status lobra_mlora_plan_fwd(const lobra_mlora_plan* plan, const void* x, c
     }
     return LOBRA_OK;
 }
+}  // namespace
+
+lobra_status lobra_mlora_plan_fwd(const lobra_mlora_plan* plan, const void* x, const void* W,
+                             const void* A, const void* B, const float* s, void* y,
+                             void* h_save, void* ws, size_t ws_bytes, void* hip_stream)
+{
+    return plan_fwd(plan, x, W, A, B, s, y, h_save, ws, ws_bytes, hip_stream, true);
+}
 
 lobra_status lobra_mlora_fwd_static_ws(const lobra_mlora_plan* plan, const void* x, const void* W,
                                        const void* A, const void* B, const float* s, void* y,
@@ -387,9 +398,12 @@ lobra_status lobra_mlora_fwd_static_ws(const lobra_mlora_plan* plan, const void*
 {
     lobra_status rs = runnable(plan);
     if (rs != LOBRA_OK) return rs;
-    if (plan->fwd_ws_bytes > size_t(LOBRA_STATIC_WS_BYTES)) return LOBRA_ERR_WORKSPACE;
+    // a batch whose K-sliced projection needs more than the array for its partial sums goes without it: the
+    // one-block-per-workgroup projection needs the projected activations only
+    const bool sliced = plan->fwd_ws_bytes <= size_t(LOBRA_STATIC_WS_BYTES);
+    if (!sliced && plan->p_layout.total > size_t(LOBRA_STATIC_WS_BYTES)) return LOBRA_ERR_WORKSPACE;
     // the kernels get the array's device address, looked up when the plan was created on this device
-    return lobra_mlora_plan_fwd(plan, x, W, A, B, s, y, nullptr, plan->static_ws, size_t(LOBRA_STATIC_WS_BYTES), hip_stream);
+    return plan_fwd(plan, x, W, A, B, s, y, nullptr, plan->static_ws, size_t(LOBRA_STATIC_WS_BYTES), hip_stream, sliced);
 }
 
 lobra_status lobra_mlora_plan_bwd(const lobra_mlora_plan* plan, const void* x, const void* W,

@@ -60,3 +60,30 @@ def test_fwd_static_ws_rejects_a_batch_beyond_the_array():
     torch.cuda.synchronize()
     assert st == -7                                   # LOBRA_ERR_WORKSPACE
     assert bool((dp.y == 1.0).all())                  # nothing was launched
+
+
+def test_fwd_static_ws_goes_without_the_sliced_projection_when_its_sums_do_not_fit():
+    """A long rank-16 batch whose K-sliced projection would need 20 MB of partial sums: the entry point uses the
+    one-block-per-workgroup projection instead (5 MB of projected activations), so y agrees with the plan form to
+    rounding, not bit for bit, and with the oracle within the layer's tolerance."""
+    import torch
+    T = 80000
+    p = wl.make_custom("static-ws-unsliced", "bf16", 2048, 256, [16, 8], [0, 30000, 30001, T], [0, -1, 1], 9,
+                       std_x=1.0, std_w=0.05, std_a=0.05, std_b=0.05)
+    dp = bd.DeviceProblem(p)
+    assert dp.plan.query(bd.Q_SLICED)[0] == 4
+    assert dp.plan.fwd_ws_bytes > bd.STATIC_WS_BYTES >= dp.plan.h_save_bytes
+    bd.lobra_mlora_plan_fwd(dp.plan, dp.x, dp.W, dp.A, dp.B, dp.s, dp.y, None, dp.ws)
+    torch.cuda.synchronize()
+    y_ref = dp.y.float().clone()
+    dp.y.fill_(-3.0)
+    bd.lobra_mlora_fwd_static_ws(dp.plan, dp.x, dp.W, dp.A, dp.B, dp.s, dp.y)
+    torch.cuda.synchronize()
+    assert float((dp.y.float() - y_ref).abs().max() / y_ref.abs().max()) <= 1e-2
+    rows = np.unique(np.concatenate([np.arange(0, T, 97), [29999, 30000, 30001, T - 1]])).astype(np.int64)
+    o = oracle.Oracle(p.x, p.W, p.A, p.B, p.s, p.dy, p.rank_off, p.seg_off, p.seg_task)
+    ref = o.y(rows)
+    got = dp.host(dp.y.index_select(0, torch.from_numpy(rows).to(dp.dev)))
+    err = float(np.abs(got - ref).max() / np.abs(ref).max())
+    print("static-ws fwd (unsliced) max|err|/max|ref| = %.3e" % err, flush=True)
+    assert err <= TOL["bf16"], err
