@@ -741,3 +741,37 @@ def test_sliced_projection_with_and_without_fused_db(name, fused):
     torch.cuda.synchronize()
     assert torch.equal(dp.y, y0) and torch.equal(dp.dx, dx0)
     assert float(dp.dA.abs().max()) == 0.0 and float(dp.dB.abs().max()) == 0.0
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_random_long_batches_at_ranks_up_to_16(seed):
+    """Random long batches that the plan hands to the sliced projection in one or both directions (widths from
+    512 to 4096, one to 33 tasks of ranks 1 to 16, segments from 1 token to 9000, spans without an adapter):
+    sampled rows of y and dx, dA and dB in full, and bit-identical results over repeated steps."""
+    import torch
+    rng = np.random.default_rng(99000 + seed)
+    n_tasks = int(rng.choice([1, 2, 5, 9, 33]))
+    ranks = rng.choice([1, 4, 8, 12, 16], n_tasks)
+    ranks[rng.integers(0, n_tasks)] = rng.choice([9, 16])
+    d_in, d_out = [(512, 1024), (1024, 512), (1536, 2048), (4096, 1024), (2048, 2560)][seed % 5]
+    S = int(rng.integers(max(2, n_tasks), 120))
+    lens = rng.choice([1, 3, 16, 31, 32, 33, 64, 100, 500, 1500, 4000, 9000], S)
+    if lens.sum() < 100000:
+        lens = lens * max(1, int(110000 / max(1, lens.sum())))
+    seg_task = rng.integers(-1, n_tasks, S)
+    seg_off = np.concatenate([[0], np.cumsum(lens)])
+    s = rng.uniform(-2, 2, n_tasks).astype(np.float32)
+    p = wl.make_custom("long16-%d" % seed, "bf16", d_in, d_out, ranks, seg_off, seg_task, 99000 + seed, s=s,
+                       std_x=1.0, std_w=0.05, std_a=0.05, std_b=0.05)
+    plan = bd.Plan.for_problem(p, bd.PLAN_HOST_ONLY)
+    q = plan.query(bd.Q_SLICED).tolist()
+    plan.close()
+    assert q[0] > 0 or q[1] > 0
+    dp, _ = check_problem(p, rows=sample_rows(p, 300, seed=seed), label="T=%d slices=%s" % (p.T, q[:4]))
+    first = {k: getattr(dp, k).clone() for k in ("y", "dx", "dA", "dB")}
+    for _ in range(3):
+        dp.step()
+    torch.cuda.synchronize()
+    for k, v in first.items():
+        assert torch.equal(getattr(dp, k), v), k
+    assert dp.guards_intact()
