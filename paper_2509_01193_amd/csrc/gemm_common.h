@@ -1,4 +1,4 @@
-// Pieces shared by the two bf16 MFMA GEMM kernels (the persistent direct-to-LDS kernel and the
+// Pieces shared by the bf16 MFMA kernels (the persistent direct-to-LDS GEMM, the K-sliced rank-r kernel and the
 // register-staged kernel for K that is not a multiple of 64): vector types, the LDS swizzles, the
 // direct global -> LDS copy and the in-place MFMA on AGPR accumulators.
 #pragma once
