@@ -224,9 +224,8 @@ lobra_status build_host_plan(const lobra_mlora_desc* d, uint32_t flags, Plan* p)
         const int64_t coltiles = (std::min(d->d_in, d->d_out) + 127) / 128;
         int64_t cb = (int64_t(T) * coltiles / 1024 + kTokenBlock - 1) / kTokenBlock;
         // Where dB rides with the projection of dy, stage 1 is one short launch for dA alone and what counts is
-        // its balance: three workgroups per compute unit and a task's blocks split evenly among its chunks (at
-        // workload 2: 24 chunks of 21 or 22 blocks, 27.9 us, against 36 of 16 or 3 blocks, 30.8 us; and a quarter
-        // fewer partial sums for stage 2)
+        // its balance: three workgroups per compute unit (at workload 2: 24 chunks of 21 or 22 blocks, 27.9 us,
+        // against 36 of 16 or 3 blocks, 30.8 us; and a quarter fewer partial sums for stage 2)
         if (p->fused_db) cb = (int64_t(p->tb.size()) * ((d->d_in + 127) / 128) + 767) / 768;
         // (the MFMA kernel gives each of its four waves a token block of the chunk at a time; the plain
         //  kernel walks a chunk's tokens one after the other, so small batches want short chunks there)
@@ -238,9 +237,10 @@ lobra_status build_host_plan(const lobra_mlora_desc* d, uint32_t flags, Plan* p)
         for (int32_t t = 0; t < n; ++t) {
             const int32_t r = p->rank_off[t + 1] - p->rank_off[t];
             const int32_t nb = p->task_tb_off[t + 1] - p->task_tb_off[t];
-            // (an even split in the fused case: no short chunk at the end of a task)
+            // (a task's blocks are split evenly among its chunks: no short chunk at the end of a task; workload 3:
+            //  stage 1 177 -> 169 us)
             const int32_t nck = (nb + p->chunk_blocks - 1) / p->chunk_blocks;
-            const int32_t len = p->fused_db && nck > 0 ? (nb + nck - 1) / nck : p->chunk_blocks;
+            const int32_t len = nck > 0 ? (nb + nck - 1) / nck : p->chunk_blocks;
             for (int32_t b = p->task_tb_off[t]; b < p->task_tb_off[t + 1]; b += len) {
                 const int32_t e = std::min(b + len, p->task_tb_off[t + 1]);
                 p->chunks.push_back(GradChunk{b, e, t, p->part_rows});
