@@ -185,11 +185,15 @@ LOBRA_API lobra_status lobra_mlora_plan_sizes(const lobra_mlora_plan *plan, size
  *                        number wg_runs[g] .. wg_runs[g + 1] - 1 (all four lists are empty unless fused_db)
  *   LOBRA_Q_FUSED_RUN_ROW  per run: first of its 16 rows in the array of dB sums
  *   LOBRA_Q_FUSED_COUNT  [n_tasks * slices_out]: runs of (task t, slice c) over all workgroups; its k-th run sits
- *   LOBRA_Q_FUSED_TASK_ROW  at row task_row[t] + 16 k */
+ *   LOBRA_Q_FUSED_TASK_ROW  at row task_row[t] + 16 k
+ *   LOBRA_Q_GEMM_TILE_ROWS  n x 8, one record per 256-token tile row of the base product (tile row i starts at token
+ *                        max(0, min(256 i, T - 256))): {segment, first token, last token + 1, task or -1, the task's
+ *                        first rank row, its stacked rank, 0, 0} of the compacted segment that holds that token */
 enum { LOBRA_Q_SEGMENTS = 0, LOBRA_Q_ROWBLOCK_SEG = 1, LOBRA_Q_TOKEN_BLOCKS = 2,
        LOBRA_Q_GRAD_CHUNKS = 3, LOBRA_Q_TASK_CHUNKS = 4, LOBRA_Q_BLOCK_RUNS = 5,
        LOBRA_Q_BLOCK_ORDER = 6, LOBRA_Q_RUN_ORDER = 7, LOBRA_Q_SLICED = 8, LOBRA_Q_FUSED_WG_RUNS = 9,
-       LOBRA_Q_FUSED_RUN_ROW = 10, LOBRA_Q_FUSED_COUNT = 11, LOBRA_Q_FUSED_TASK_ROW = 12 };
+       LOBRA_Q_FUSED_RUN_ROW = 10, LOBRA_Q_FUSED_COUNT = 11, LOBRA_Q_FUSED_TASK_ROW = 12,
+       LOBRA_Q_GEMM_TILE_ROWS = 13 };
 LOBRA_API lobra_status lobra_mlora_plan_query(const lobra_mlora_plan *plan, int32_t what, int32_t *out,
                                     size_t capacity, size_t *count);
 

@@ -21,6 +21,7 @@ PLAN_HOST_ONLY, PLAN_PLAIN_KERNELS = 1, 2
 Q_SEGMENTS, Q_ROWBLOCK_SEG, Q_TOKEN_BLOCKS, Q_GRAD_CHUNKS, Q_TASK_CHUNKS, Q_BLOCK_RUNS = 0, 1, 2, 3, 4, 5
 Q_BLOCK_ORDER, Q_RUN_ORDER = 6, 7
 Q_SLICED, Q_FUSED_WG_RUNS, Q_FUSED_RUN_ROW, Q_FUSED_COUNT, Q_FUSED_TASK_ROW = 8, 9, 10, 11, 12
+Q_GEMM_TILE_ROWS = 13
 MAX_RANK = 128
 
 EXPORTS = [

@@ -35,6 +35,7 @@ PlanDev device_view(const Plan& p)
     d.fb_run_row = p.fused_db ? b + p.o_fb_run : nullptr;
     d.fb_cnt = p.fused_db ? b + p.o_fb_cnt : nullptr;
     d.fb_task_row0 = p.fused_db ? b + p.o_fb_row0 : nullptr;
+    d.gemm_tile_tab = b + p.o_tile_tab;
     d.T = int32_t(p.desc.T);
     d.d_in = p.desc.d_in;
     d.d_out = p.desc.d_out;
@@ -312,6 +313,10 @@ lobra_status lobra_mlora_plan_query(const lobra_mlora_plan* plan, int32_t what, 
     case LOBRA_Q_FUSED_TASK_ROW:
         src = plan->fb_task_row0.data();
         n = plan->fb_task_row0.size();
+        break;
+    case LOBRA_Q_GEMM_TILE_ROWS:
+        src = plan->gemm_tile_tab.data();
+        n = plan->gemm_tile_tab.size();
         break;
     default:
         return LOBRA_ERR_SHAPE;

@@ -25,6 +25,7 @@ struct PlanDev {
     const int32_t* fb_run_row;     // [runs] first row of the run's partial sums
     const int32_t* fb_cnt;         // [n_tasks * slices] runs of (task, slice)
     const int32_t* fb_task_row0;   // [n_tasks] row of the first run of (task, any slice)
+    const int32_t* gemm_tile_tab;  // [ceil(T/kGemmTileRows)][kGemmTileRec] (see Plan::gemm_tile_tab)
     int32_t T, d_in, d_out, n_tasks, nseg, ntb, nchunks, r_max, r_pad, R_tot, nsb, shrink_group, n_proj, dg;
 };
 

@@ -65,11 +65,17 @@ constexpr int STAGE_BYTES = 2 * ZT_BYTES;            // Z tile + W tile
 constexpr int MROWS = 64;                            // rank rows of the adapter slice staged at a time
 constexpr int MSLICE_OFF = 2 * STAGE_BYTES, MSLICE_BYTES = MROWS * BN * 2;
 constexpr int LDS_BYTES = MSLICE_OFF + MSLICE_BYTES; // 160 KiB
+constexpr int PRE_RANKS = 32;                        // rank windows up to this are copied ahead of the epilogue
+constexpr int PRE_P_OFF = PRE_RANKS * BN * 2;        // where the P rows land in the adapter region
+constexpr int PRE_COPIES = 8;                        // 1 KiB copies per wave: half for the M_t slice, half for P
+static_assert(PRE_P_OFF + BM * PRE_RANKS * 2 <= MSLICE_BYTES && PRE_COPIES / 2 * NW * 1024 == PRE_P_OFF,
+              "the copied-ahead operands fill the adapter region");
 constexpr int NBZ = (BK / 2) / NW;                   // 1 KiB copy blocks per wave, for Z and for W each
 constexpr int NU = MB + NB;                          // fragments per K step of 32 = sections per K step
 static_assert(NW == 4 && MB == 8 && NB == 8 && MB * NB == 4 * NU && 2 * NBZ == NU && BK == 64,
               "four waves of 128 x 128: four MFMAs and at most one copy per section");
 static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
+static_assert(BM == kGemmTileRows, "the plan's tile-row table is made for this tile height");
 
 // Column of the wave tile that MFMA block nb produces in its result row i (= row i of its "A" operand).
 // Lane (j, kg) of a block holds result rows 4 kg .. 4 kg + 3, so with this dealing the blocks 2 p and
@@ -91,8 +97,13 @@ void gemm_persistent_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const ui
                             const uint16_t* __restrict__ P, const uint16_t* __restrict__ M,
                             uint16_t* __restrict__ C, int32_t K, int32_t N, int32_t ldw, int32_t ldc,
                             int32_t nproj, int32_t proj, int32_t tiles_m, int32_t tiles_n, int32_t GM, int32_t cpx,
-                            int32_t TPW)
+                            int32_t TPW, const int32_t* __restrict__ tile_tab, const int32_t* __restrict__ cseg_off,
+                            const int32_t* __restrict__ cseg_task, const int32_t* __restrict__ rank_off)
 {
+    // tile_tab, cseg_off, cseg_task, rank_off: pd's tables of those names once more, as arguments of their own that
+    // promise not to alias anything the kernel writes: their entries are the same for every lane, and with the
+    // promise the compiler fetches them with scalar loads, which no vector memory operation in flight - copies,
+    // stores - has to be waited for first.
     // cpx: workgroups an XCD runs at one time (one per compute unit); TPW: output tiles per workgroup.
     // ldc: row pitch of C.  nproj > 1: this launch is projection `proj` of a fused shared-input
     // call: of every task's rank rows (in M) and rank columns (in P) only the window
@@ -294,20 +305,56 @@ void gemm_persistent_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const ui
     //      tab_*: the table entries of the first segment that crosses the tile, read when the tile's main loop
     //      began (a chain of dependent loads that would otherwise sit in front of the epilogue).
     const u32x4 zero4 = {0u, 0u, 0u, 0u};
-    int32_t tab_sg = 0, tab_lo = 0, tab_hi = 0, tab_task = -1, tab_r0 = 0, tab_r1 = 0;
-    // (Table entries are the same for every lane but come from memory the kernel also writes to, so the compiler
-    //  loads them into vector registers; rfl moves them to scalars at once - they live across the main loop.)
+    int32_t tab_sg = 0, tab_lo = 0, tab_hi = 0, tab_task = -1, tab_r0 = 0, tab_r1 = 0, tab_pcol = 0;
+    bool tab_pre = false;                            // the first segment's operands are copied ahead (prefetch_adapter)
     auto rfl = [](int32_t v) { return __builtin_amdgcn_readfirstlane(v); };
     auto load_table = [&](int32_t row0, int32_t col0) {
         if (!P) return;
-        tab_sg = rfl(pd.rowblk_seg[row0 / kRowBlock]);
-        tab_lo = rfl(pd.cseg_off[tab_sg]);
-        tab_hi = rfl(pd.cseg_off[tab_sg + 1]);
-        tab_task = rfl(pd.cseg_task[tab_sg]);
+        // the record of this tile row (the last tile row may start above a multiple of the tile height)
+        const int32_t* rec = tile_tab + size_t((row0 + BM - 1) / BM) * kGemmTileRec;
+        tab_sg = rec[0];
+        tab_lo = rec[1];
+        tab_hi = rec[2];
+        tab_task = rec[3];
         const int32_t pj = proj >= 0 ? proj : col0 / pd.dg;
-        const int32_t rw = tab_task >= 0 ? rfl(pd.rank_off[tab_task + 1] - pd.rank_off[tab_task]) / nproj : 0;
-        tab_r0 = tab_task >= 0 ? rfl(pd.rank_off[tab_task]) + pj * rw : 0;
+        const int32_t rw = rec[5] / nproj;
+        tab_r0 = rec[4] + pj * rw;
         tab_r1 = tab_r0 + rw;
+        tab_pcol = pj * rw;
+        tab_pre = tab_task >= 0 && rw > 0 && rw <= PRE_RANKS;
+    };
+    // ---- the up projection's operands for the first segment of the tile at (row0, col0), copied into the adapter
+    //      region while the tile's last K tiles are multiplied, when that segment's rank window fits one rank step:
+    //      k rows 0 .. 31 of the M_t slice in the [k][256 n] layout (16 KiB; rows from r_t on repeat row r_t - 1),
+    //      then the tile's 256 rows of P, 64 bytes each (16 KiB; chunks from r_t on repeat chunk 0).  What lies
+    //      beyond r_t is masked in registers, so only the addresses have to be valid.  Always PRE_COPIES copies
+    //      per wave, whatever the rank.
+    auto prefetch_adapter = [&](int32_t row0, int32_t col0) __attribute__((always_inline)) {
+        if (!tab_pre) return;                        // uniform
+        const int32_t r = tab_r1 - tab_r0;
+        const int32_t mcol0 = proj >= 0 ? 0 : (col0 / pd.dg) * pd.dg;
+        const int32_t mpitch = proj >= 0 ? N : pd.dg;
+        const unsigned char* mbase = reinterpret_cast<const unsigned char*>(M + size_t(tab_r0) * mpitch + (col0 - mcol0));
+        const unsigned char* pbase = reinterpret_cast<const unsigned char*>(P + size_t(row0) * pd.r_pad + tab_pcol);
+        // (opaque to the optimiser: the per-lane offsets are worked out here, once per output tile, instead of
+        //  living in eight loop-invariant registers through the main loop)
+        int ln = lane;
+        asm volatile("" : "+v"(ln));
+#pragma unroll
+        for (int c = 0; c < PRE_COPIES / 2; ++c) {
+            const int blk = wave_u + NW * c;
+            const int krow = 2 * blk + (ln >> 5);
+            const int chn = (ln & 31) ^ kn_swz2(krow);
+            dma16(lds0 + MSLICE_OFF + (wave_u + NW * c) * 1024, mbase,
+                  (uint32_t(min(krow, r - 1)) * uint32_t(mpitch) + 8u * chn) * 2u);
+        }
+#pragma unroll
+        for (int c = 0; c < PRE_COPIES / 2; ++c) {
+            const int blk = wave_u + NW * c;
+            const int row = 16 * blk + (ln >> 2), ch = ln & 3;
+            dma16(lds0 + MSLICE_OFF + PRE_P_OFF + (wave_u + NW * c) * 1024, pbase,
+                  (uint32_t(row) * uint32_t(pd.r_pad) + (8 * ch < r ? 8u * ch : 0u)) * 2u);
+        }
     };
     auto epilogue = [&](int32_t row0, int32_t col0) __attribute__((always_inline)) {
         // the loop's MFMAs are asm statements, so the compiler does not know that the accumulators come out of
@@ -326,16 +373,59 @@ void gemm_persistent_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const ui
             const int32_t pj = proj >= 0 ? proj : col0 / pd.dg;          // this tile's projection
             const int32_t mcol0 = proj >= 0 ? 0 : pj * pd.dg;            // first column of that projection
             const int32_t mpitch = proj >= 0 ? N : pd.dg;                // row pitch of M
-            for (int32_t sg = tab_sg; sg < pd.nseg; ++sg) {
+            int32_t sg_first = tab_sg;
+            if (tab_pre) {                           // uniform: the first segment's operands are in the region already
+                sg_first = tab_sg + 1;
+                const int32_t lo = max(tab_lo, row0), hi = min(tab_hi, row_end);
+                if (hi > wrow0 && lo < wrow0 + TM) { // wave-uniform: the segment crosses this wave's rows
+                    // lane (j, kg) holds ranks 8 kg .. 8 kg + 7 in both operands: those from r_t on are cleared
+                    const int nv = min(max(tab_r1 - tab_r0 - 8 * kg, 0), 8);
+                    u32x4 km;
+#pragma unroll
+                    for (int w = 0; w < 4; ++w) km[w] = (2 * w < nv ? 0xffffu : 0u) | (2 * w + 1 < nv ? 0xffff0000u : 0u);
+                    const unsigned char* pl = ml + PRE_P_OFF + (wm * TM + j) * (PRE_RANKS * 2) + kg * 16;
+                    u32x4 pv[MB];
+#pragma unroll
+                    for (int mb = 0; mb < MB; ++mb) {
+                        const int32_t row = wrow0 + mb * 16 + j;
+                        const u32x4 v = *reinterpret_cast<const u32x4*>(pl + mb * 16 * (PRE_RANKS * 2));
+                        pv[mb] = (row >= lo && row < hi) ? (v & km) : zero4;
+                    }
+                    bf16x8 mf[NB];
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb) {
+                        union { bf16x8 b; u32x4 u; } cv;
+                        cv.b = read_kn(ml, 0, nb);
+                        cv.u &= km;
+                        mf[nb] = cv.b;
+                    }
+                    // The MFMAs are asm statements, which the compiler's hazard pass does not look into: an MFMA
+                    // must not read a register in the two wait states after a vector ALU instruction has
+                    // written it, and the masking above is such a write (operands that come straight from a
+                    // load need nothing).  The statements below order the masking before the wait states and
+                    // the MFMAs behind them.
+                    asm volatile("s_nop 1" : "+v"(mf[0]), "+v"(mf[1]), "+v"(mf[2]), "+v"(mf[3]), "+v"(mf[4]), "+v"(mf[5]),
+                                 "+v"(mf[6]), "+v"(mf[7]));
+                    static_for<0, MB>([&](auto mb_c) {
+                        constexpr int mb = decltype(mb_c)::value;
+                        const int32_t rb = wrow0 + mb * 16;
+                        if (hi <= rb || lo >= rb + 16) return;          // wave-uniform
+                        bf16x8 pf = as_bf16x8(pv[mb]);
+                        asm volatile("s_nop 1" : "+v"(pf));
+                        static_for<0, NB>([&](auto nb_c) { mfma_acc<acc_reg(mb, decltype(nb_c)::value)>(mf[decltype(nb_c)::value], pf); });
+                    });
+                }
+            }
+            for (int32_t sg = sg_first; sg < pd.nseg; ++sg) {
                 const bool cached = sg == tab_sg;
-                const int32_t seg_lo = cached ? tab_lo : rfl(pd.cseg_off[sg]);
+                const int32_t seg_lo = cached ? tab_lo : rfl(cseg_off[sg]);
                 if (seg_lo >= row_end) break;
-                const int32_t t = cached ? tab_task : rfl(pd.cseg_task[sg]);
+                const int32_t t = cached ? tab_task : rfl(cseg_task[sg]);
                 if (t < 0) continue;
-                const int32_t seg_hi = cached ? tab_hi : rfl(pd.cseg_off[sg + 1]);
+                const int32_t seg_hi = cached ? tab_hi : rfl(cseg_off[sg + 1]);
                 const int32_t lo = max(seg_lo, row0), hi = min(seg_hi, row_end);
-                const int32_t r = cached ? tab_r1 - tab_r0 : rfl(pd.rank_off[t + 1] - pd.rank_off[t]) / nproj;
-                const int32_t r0 = cached ? tab_r0 : rfl(pd.rank_off[t]) + pj * r;
+                const int32_t r = cached ? tab_r1 - tab_r0 : rfl(rank_off[t + 1] - rank_off[t]) / nproj;
+                const int32_t r0 = cached ? tab_r0 : rfl(rank_off[t]) + pj * r;
                 const int32_t rp = (r + 31) & ~31;
                 const bool mine = hi > wrow0 && lo < wrow0 + TM;   // wave-uniform: the segment crosses this wave's rows
                 // the P fragments of a rank step: lane (j, kg) holds the ranks kk + 8 kg .. + 7 of token row j of
@@ -519,6 +609,7 @@ void gemm_persistent_kernel(PlanDev pd, const uint16_t* __restrict__ Z, const ui
     for (;;) {
         if (t_kt == 0) ktile(stage0{}, step_first{});
         else ktile(stage0{}, step_plain{});
+        if (t_kt + 2 == KT) prefetch_adapter(t_row0, t_col0);   // waited for at the tile barrier that follows
         ktile(stage1{}, step_plain{});
         t_kt += 2;
         if (t_kt == KT) {                            // uniform: an output tile is complete
@@ -570,7 +661,7 @@ hipError_t launch_persistent(const PlanDev& pd, const void* Z, const void* W, co
     const int64_t wgs = ntiles <= 8 * int64_t(cpx) ? ntiles : 8 * rounds * cpx;   // few tiles: one workgroup each
     gemm_persistent_kernel<W_KN><<<dim3(uint32_t(wgs)), 64 * NW, LDS_BYTES, st>>>(
         pd, (const uint16_t*)Z, (const uint16_t*)W, (const uint16_t*)P, (const uint16_t*)M, (uint16_t*)C,
-        K, N, ldw, ldc, nproj, proj, tiles_m, tiles_n, gm, cpx, tpw);
+        K, N, ldw, ldc, nproj, proj, tiles_m, tiles_n, gm, cpx, tpw, pd.gemm_tile_tab, pd.cseg_off, pd.cseg_task, pd.rank_off);
     return hipGetLastError();
 }
 }  // namespace

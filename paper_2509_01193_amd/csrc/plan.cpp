@@ -101,6 +101,24 @@ lobra_status build_host_plan(const lobra_mlora_desc* d, uint32_t flags, Plan* p)
             p->rowblk_seg[b] = k;
         }
 
+        // 2b. what the first rows of every GEMM tile row belong to
+        {
+            const int32_t ntr = (T + kGemmTileRows - 1) / kGemmTileRows;
+            p->gemm_tile_tab.assign(size_t(ntr) * kGemmTileRec, 0);
+            for (int32_t i = 0, k = 0; i < ntr; ++i) {
+                const int32_t row0 = std::max(0, std::min(i * kGemmTileRows, T - kGemmTileRows));
+                while (p->cseg_off[k + 1] <= row0) ++k;      // row0 does not decrease with i
+                const int32_t t = p->cseg_task[k];
+                int32_t* rec = &p->gemm_tile_tab[size_t(i) * kGemmTileRec];
+                rec[0] = k;
+                rec[1] = p->cseg_off[k];
+                rec[2] = p->cseg_off[k + 1];
+                rec[3] = t;
+                rec[4] = t >= 0 ? p->rank_off[t] : 0;
+                rec[5] = t >= 0 ? p->rank_off[t + 1] - p->rank_off[t] : 0;
+            }
+        }
+
         // 3. token blocks, grouped by task (counting sort keeps token order inside a task)
         p->task_tb_off.assign(size_t(n) + 1, 0);
         for (int32_t k = 0; k < nseg; ++k) {
@@ -322,6 +340,7 @@ std::vector<int32_t> pack_blob(Plan* p)
     p->o_fb_run = put(p->fb_run_row.data(), p->fb_run_row.size());
     p->o_fb_cnt = put(p->fb_cnt.data(), p->fb_cnt.size());
     p->o_fb_row0 = put(p->fb_task_row0.data(), p->fb_task_row0.size());
+    p->o_tile_tab = put(p->gemm_tile_tab.data(), p->gemm_tile_tab.size());
     while (blob.size() % 4) blob.push_back(0);
     return blob;
 }

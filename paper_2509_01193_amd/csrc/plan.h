@@ -11,6 +11,8 @@ namespace lobra {
 
 constexpr int kTokenBlock = 32;   // tokens per token block (one MFMA K step of the reductions)
 constexpr int kRowBlock = 32;     // granularity of the row -> segment lookup table
+constexpr int kGemmTileRows = 256;    // token rows of a base-GEMM output tile
+constexpr int kGemmTileRec = 8;       // ints per record of Plan::gemm_tile_tab
 constexpr bool kMfmaKernels = true;   // bf16 storage runs on the MFMA kernels
 constexpr int64_t kPlainMaxTokens = 65535 * 64;   // the plain kernels put 64-token tiles on grid.y
 
@@ -44,6 +46,12 @@ struct Plan {
     std::vector<int32_t> seg_off_in, seg_task_in;   // the caller's table, as given
     std::vector<int32_t> cseg_off, cseg_task;       // compacted table
     std::vector<int32_t> rowblk_seg;    // [ceil(T/32)]
+    // One record of kGemmTileRec ints per tile row of the base GEMM (tile row i starts at token
+    // min(i kGemmTileRows, T - kGemmTileRows), never below 0): the compacted segment that holds that token, its
+    // first and last + 1 token, its task (-1: none), and that task's first rank row and stacked rank
+    // (0, 0 without a task); the rest is padding.  One 32-byte read tells a GEMM workgroup what the fused
+    // up projection of a tile starts with.
+    std::vector<int32_t> gemm_tile_tab; // [ceil(T/kGemmTileRows)][kGemmTileRec]
     std::vector<TokenBlock> tb;         // grouped by task, token order inside a task
     std::vector<int32_t> task_tb_off;   // [n_tasks+1]
     std::vector<int32_t> sb_off;        // [nsb+1] runs of <= shrink_group token blocks of one task
@@ -92,7 +100,7 @@ struct Plan {
     // offsets (in int32 units) of the lists inside the blob
     size_t o_cseg_off = 0, o_cseg_task = 0, o_rowblk = 0, o_tb = 0, o_chunks = 0,
            o_task_chunk = 0, o_rank_off = 0, o_task_tb = 0, o_sb = 0, o_tb_order = 0, o_sb_order = 0,
-           o_fb_wg = 0, o_fb_run = 0, o_fb_cnt = 0, o_fb_row0 = 0;
+           o_fb_wg = 0, o_fb_run = 0, o_fb_cnt = 0, o_fb_row0 = 0, o_tile_tab = 0;
 };
 
 lobra_status validate(const lobra_mlora_desc* d);

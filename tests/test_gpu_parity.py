@@ -166,6 +166,26 @@ def test_persistent_gemm_tile_edges_and_round_remainders(T, d_in, d_out):
     check_problem(p, rows=rows, label="edges")
 
 
+@pytest.mark.parametrize("n_proj", [1, 2])
+def test_persistent_gemm_up_projection_at_every_kind_of_rank(n_proj):
+    """The GEMM's fused up projection takes the operands of a tile's first segment from a copy made ahead of the
+    epilogue when the rank window is at most 32, and loads them itself otherwise and for every further segment:
+    ranks below, at and above 8, 16 and 32 (windows that end inside an 8-rank group rely on the masking), tiles
+    crossed by one and by many segments, the last tile row moved up."""
+    rng = np.random.default_rng(4400 + n_proj)
+    ranks = [1, 3, 12, 17, 31, 32, 33, 8] if n_proj == 1 else [8, 16, 24, 32, 40]
+    lens = []
+    while sum(lens) < 3000:
+        lens.append(int(rng.choice([1, 31, 100, 255, 257, 600])))
+    lens[-1] -= sum(lens) - 3000
+    seg_task = rng.integers(-1, len(ranks), len(lens))
+    kw = dict(std_x=1.0, std_w=0.05, std_a=0.05, std_b=0.05)
+    base = wl.make_custom("uprank-%d" % n_proj, "bf16", 256, 384, ranks, np.concatenate([[0], np.cumsum(lens)]), seg_task,
+                          23, s=rng.uniform(-2, 2, len(ranks)).astype(np.float32), fill=(n_proj == 1), **kw)
+    p = base if n_proj == 1 else wl.fuse_projections(base, n_proj, **kw)
+    check_problem(p, label="up projection ranks %s x %d" % (ranks, n_proj))
+
+
 def test_config3_reversed_rank_pairing():
     p = wl.make_config(3, "shuffled", d_in=192, d_out=344, reverse_ranks=True)
     check_problem(p)

@@ -180,8 +180,19 @@ def check_plan(p):
     assert len(rb) == (p.T + 31) // 32
     for b, k in enumerate(rb):
         assert segs[k][0] <= 32 * b < segs[k][1]
-    tb = plan.query(bd.Q_TOKEN_BLOCKS).reshape(-1, 4)
     ro = p.rank_off
+    # what the first token of every 256-token tile row of the base product belongs to
+    tr = plan.query(bd.Q_GEMM_TILE_ROWS).reshape(-1, 8)
+    assert len(tr) == (p.T + 255) // 256
+    for i, rec in enumerate(tr.tolist()):
+        row0 = max(0, min(256 * i, p.T - 256))
+        k = rec[0]
+        assert segs[k][0] <= row0 < segs[k][1]
+        task = segs[k][2]
+        want = [k, segs[k][0], segs[k][1], task, int(ro[task]) if task >= 0 else 0,
+                int(ro[task + 1] - ro[task]) if task >= 0 else 0, 0, 0]
+        assert rec == want, (i, rec, want)
+    tb = plan.query(bd.Q_TOKEN_BLOCKS).reshape(-1, 4)
     covered = np.zeros(p.T, np.int32)
     last_task, last_row = -1, -1
     for row0, nrows, task, rr0 in tb.tolist():
