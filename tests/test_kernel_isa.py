@@ -2,8 +2,9 @@
 
 The kernel names its accumulator registers itself (a[0:255], see csrc/gemm_common.h) instead of handing 64
 values to the register allocator.  That is only sound if nothing else in the kernel touches an AGPR, if the
-kernel really allocates all 256 of them, and if nothing is spilled to scratch memory; and the copy statements
-rely on M0 being written and consumed inside one asm statement.  All of that is a property of the generated
+kernel really allocates all 256 of them, and if nothing is spilled to scratch memory; the copy statements
+rely on M0 being written and consumed inside one asm statement; and the MFMA statements get no hazard
+handling from the compiler.  All of that is a property of the generated
 code, so it is checked on the generated code.
 """
 import os
@@ -72,6 +73,35 @@ def test_m0_is_written_and_consumed_inside_one_statement(kernels):
             assert 0 < c - w <= 2, (name, code[w:c + 1])         # at most the MFMA / s_nop of the statement between
         # nothing else writes M0
         assert not [l for l in code if re.search(r"\bm0\b", l) and not l.startswith(("s_mov_b32 m0,", "global_load_lds"))], name
+
+
+def _vregs(tok):
+    m = re.match(r"v\[(\d+):(\d+)\]$", tok)
+    if m:
+        return set(range(int(m.group(1)), int(m.group(2)) + 1))
+    m = re.match(r"v(\d+)$", tok)
+    return {int(m.group(1))} if m else set()
+
+
+def test_no_mfma_reads_a_register_a_vector_alu_instruction_has_just_written(kernels):
+    """The MFMAs are asm statements and the compiler's hazard pass does not look into those: an MFMA needs two
+    wait states between a vector ALU write of one of its operand registers and its own read of it (operands that
+    come from LDS or memory are covered by the waitcnt the compiler does insert)."""
+    for name, code, _ in kernels:
+        for i, l in enumerate(code):
+            if not l.startswith("v_mfma"):
+                continue
+            ops = [t.strip() for t in l.split(None, 1)[1].split(",")]
+            src = _vregs(ops[1]) | _vregs(ops[2])
+            states, k = 0, i - 1
+            while states < 2 and k >= 0:
+                pl = code[k]
+                if pl.startswith("v_") and not pl.startswith(("v_mfma", "v_accvgpr")):
+                    dst = pl.split(None, 1)[1].split(",")[0].strip()
+                    assert not (_vregs(dst) & src), (name, code[k:i + 1])
+                m = re.match(r"s_nop (\d+)$", pl)
+                states += int(m.group(1)) + 1 if m else 1
+                k -= 1
 
 
 def test_main_loop_has_no_instruction_clumps(kernels):
