@@ -11,8 +11,10 @@
 //     last K tiles of an output tile are multiplied, the first K tiles of the next one are already being
 //     copied, so no stage fill is exposed except the very first;
 //   * the epilogue keeps its hands off the two stages: the adapter slice of the fused up projection is staged
-//     in a third LDS region, and the result is rounded, passed through the same region (a 64 x 64 block per wave
-//     at a time) and stored in whole 128-byte lines; the stores drain under the next tile's first MFMAs.
+//     in a third LDS region (for the tile's first segment it and the tile's rows of P are copied there while the
+//     last K tile is multiplied, see prefetch_adapter), and the result is rounded, passed through the same region
+//     (a 64 x 64 block per wave at a time) and stored in whole 128-byte lines; the stores drain under the next
+//     tile's first MFMAs.
 // One workgroup per output tile instead costs about 15 us per tile (workgroup start, two exposed stage fills,
 // the epilogue and its store drain) next to 80 us of MFMAs at K = 4096; of that the stream hides what is not the
 // stores and the epilogue's own instructions.
