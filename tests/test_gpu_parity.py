@@ -408,12 +408,22 @@ def test_padded_bucket_layout_as_no_adapter_spans():
         assert ((a - b).abs().max() / b.abs().max()).item() < 1e-5      # same terms, other summation order
 
 
-def test_fwd_bwd_under_hip_graph_capture():
+@pytest.mark.parametrize("kernels", ["register-staged-gemm", "persistent-gemm", "sliced-projection-fused-db"])
+def test_fwd_bwd_under_hip_graph_capture(kernels):
     """fwd and bwd allocate nothing and never synchronise, so a step can be captured in a HIP graph.
     Every replay (with fresh inputs written into the same buffers and eager work in between) must
-    reproduce the eager result bit for bit."""
+    reproduce the eager result bit for bit.  Once per family of kernels a step can consist of: the GEMM for
+    widths that are not whole K tiles, the persistent GEMM (with the up projection's operands copied ahead), and
+    the K-sliced projection with dB fused into the pass over dy."""
     import torch
-    p = wl.make_config(2, "shuffled", d_in=320, d_out=448)
+    if kernels == "register-staged-gemm":
+        p = wl.make_config(2, "shuffled", d_in=320, d_out=448)
+    elif kernels == "persistent-gemm":
+        p = wl.make_config(2, "shuffled", d_in=512, d_out=768)
+    else:
+        p = wl.make_config(4, "shuffled", d_in=1024, d_out=1024)
+        q = bd.Plan.for_problem(p, bd.PLAN_HOST_ONLY).query(bd.Q_SLICED)
+        assert q[0] > 0 and q[1] > 0 and q[2] == 1, q      # the plan does take the sliced kernels here
     dp = bd.DeviceProblem(p)
     dp.step()                                     # warm-up outside capture (first-call attribute set-up)
     torch.cuda.synchronize()
